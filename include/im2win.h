@@ -1,0 +1,109 @@
+/*
+ * im2win.h -- C ABI of the MI355X (gfx950) im2win convolution library.
+ *
+ * The library implements the forward path of "Im2win: An Efficient Convolution
+ * Paradigm on GPU" (arXiv 2306.14316): the im2win data transformation
+ * (Section 3.1, Eq. 2) and the forward convolution computed over the im2win
+ * tensor (Section 3.2, Algorithms 2 and 3), in fp32.
+ *
+ * Notation and layouts (Section 2.1), all fp32, all dense and contiguous:
+ *   input   I[N][Ci][Hi][Wi]                     (NCHW)
+ *   filter  F[Co][Ci][Hf][Wf]
+ *   output  O[N][Co][Ho][Wo]                     (NCHW)
+ *   window  What[N][Ci][Ho][Wp*Hf], Wp = Wi+2*pad (the im2win tensor)
+ * One stride applies to both axes, as in the paper.  Zero padding `pad` on all
+ * four sides is an extension (every layer of the paper's Table 2 is unpadded);
+ * it is materialised in the im2win tensor, whose rows are Wp*Hf long.
+ *   Ho = floor((Hi + 2*pad - Hf)/stride) + 1,  Wo likewise (Table 2).
+ *
+ * Conventions for every entry point:
+ *   - Pointers named *_dev are DEVICE pointers on the current HIP device; the
+ *     caller owns all buffers and the library allocates nothing and keeps no
+ *     state between calls.  Buffers must not overlap.  4-byte alignment is
+ *     enough (16-byte alignment lets the kernels use wider accesses).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls only enqueue work on it and never synchronise.
+ *   - Outputs are overwritten in full (no accumulation into them).
+ *   - Errors are returned, never thrown; on any error nothing is launched.
+ *   - Every tensor must have fewer than 2^31 elements (IM2WIN_ERR_OVERFLOW).
+ */
+#ifndef IM2WIN_H_
+#define IM2WIN_H_
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    IM2WIN_OK = 0,
+    IM2WIN_ERR_NULL = -1,        /* a required pointer is NULL                           */
+    IM2WIN_ERR_SHAPE = -2,       /* a dimension <= 0, stride < 1, pad < 0, or the filter */
+                                 /* is larger than the padded input                      */
+    IM2WIN_ERR_OVERFLOW = -3,    /* a tensor has 2^31 or more elements                   */
+    IM2WIN_ERR_UNSUPPORTED = -4, /* shape needs more LDS than one workgroup can hold     */
+    IM2WIN_ERR_HIP = -5          /* the HIP runtime refused the launch                   */
+} im2win_status;
+
+/* Output extent of the convolution (size rule of Table 2, with padding). */
+im2win_status im2win_out_shape(int Hi, int Wi, int Hf, int Wf, int stride, int pad,
+                               int *Ho, int *Wo);
+
+/* Bytes of the im2win tensor, 4*N*Ci*Ho*Hf*(Wi+2*pad): the workspace the caller
+ * must provide between the two calls below (Section 3.1: size (Ni,Ci,Ho,Wi x Hf)). */
+im2win_status im2win_workspace_bytes(int N, int Ci, int Hi, int Wi, int Hf, int Wf,
+                                     int stride, int pad, size_t *bytes);
+
+/* Bytes the im2col matrices of the same layer would take, 4*N*Ho*Wo*Ci*Hf*Wf
+ * (Section 2.3); for reporting the footprint saving only. */
+im2win_status im2col_footprint_bytes(int N, int Ci, int Hi, int Wi, int Hf, int Wf,
+                                     int stride, int pad, size_t *bytes);
+
+/*
+ * im2win data transformation (Section 3.1, Eq. 2):
+ *   window(i, r, m, k*Hf + u) = Ipad(i, r, m*stride + u, k)
+ * for 0<=m<Ho, 0<=k<Wp, 0<=u<Hf, where Ipad is the input with `pad` zeros on
+ * each side.  Values are copied bit for bit; padding is written as +0.0.
+ *   input_dev   device, N*Ci*Hi*Wi floats, read only
+ *   window_dev  device, N*Ci*Ho*Wp*Hf floats, fully overwritten
+ */
+im2win_status im2win_transform(const float *input_dev, float *window_dev,
+                               int N, int Ci, int Hi, int Wi, int Hf, int Wf,
+                               int stride, int pad, void *stream);
+
+/*
+ * Forward convolution over the im2win tensor (Section 3.2, Algorithm 3's role;
+ * result defined by Eq. 1):
+ *   O(i,j,m,n) = sum_{r,u,v} window(i, r, m, (n*stride+v)*Hf + u) * F(j,r,u,v)
+ * computed as a GEMM with M = Co, N = N*Ho*Wo, K = Ci*Hf*Wf on the fp32 matrix
+ * cores (fp32 multiply, fp32 accumulate; summation order is unspecified).
+ * Hi, Wi and pad are those given to im2win_transform, so that both calls derive
+ * the same shapes.
+ *   window_dev  device, as written by im2win_transform, read only
+ *   filter_dev  device, Co*Ci*Hf*Wf floats in the paper's [Co][Ci][Hf][Wf] order
+ *   output_dev  device, N*Co*Ho*Wo floats, fully overwritten
+ */
+im2win_status conv2d_im2win_fwd(const float *window_dev, const float *filter_dev,
+                                float *output_dev,
+                                int N, int Ci, int Hi, int Wi, int Co, int Hf, int Wf,
+                                int stride, int pad, void *stream);
+
+/*
+ * The basic im2win convolution of Algorithm 2 (Section 3.2): one thread per
+ * output element, a K loop of scalar multiply-adds reading the im2win tensor
+ * and the filter from global memory.  Same arguments and result as
+ * conv2d_im2win_fwd; kept as the slow in-library reference kernel.
+ */
+im2win_status conv2d_im2win_fwd_basic(const float *window_dev, const float *filter_dev,
+                                      float *output_dev,
+                                      int N, int Ci, int Hi, int Wi, int Co, int Hf, int Wf,
+                                      int stride, int pad, void *stream);
+
+/* Static description of a status code (never NULL). */
+const char *im2win_status_str(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* IM2WIN_H_ */

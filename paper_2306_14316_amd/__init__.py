@@ -1,0 +1,19 @@
+"""MI355X (gfx950) im2win convolution: thin Python binding over libim2win.so.
+
+The package only marshals arguments: every step of the path (the im2win
+transform and the convolution over the im2win tensor) runs in the library's
+HIP kernels.  PyTorch provides device memory and streams, nothing else.  There
+is no CPU fallback: if the library is missing or no GPU is present, calls fail.
+"""
+from .binding import (  # noqa: F401
+    Im2winError,
+    conv2d_im2win_fwd,
+    conv2d_im2win_fwd_basic,
+    im2col_footprint_bytes,
+    im2win_out_shape,
+    im2win_transform,
+    im2win_workspace_bytes,
+    lib_path,
+    load_library,
+    status_str,
+)

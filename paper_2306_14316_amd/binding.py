@@ -1,0 +1,135 @@
+"""ctypes binding of the C ABI declared in include/im2win.h (same names).
+
+Tensors are torch CUDA (ROCm) tensors used as raw device buffers; the current
+torch stream is handed to the library as the hipStream_t.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libim2win.so")
+_lib = None
+
+EXPORTS = (
+    "im2win_out_shape",
+    "im2win_workspace_bytes",
+    "im2col_footprint_bytes",
+    "im2win_transform",
+    "conv2d_im2win_fwd",
+    "conv2d_im2win_fwd_basic",
+    "im2win_status_str",
+)
+
+
+class Im2winError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s: %s (status %d)" % (where, status_str(status), status))
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libim2win.so (built in-tree by paper_2306_14316_amd.build); fails loudly if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise FileNotFoundError(
+                "%s not found: build it with `python -m paper_2306_14316_amd.build` "
+                "(or __graft_entry__.build())" % _LIB_PATH)
+        lib = ctypes.CDLL(_LIB_PATH)
+        i, vp, sp = ctypes.c_int, ctypes.c_void_p, ctypes.POINTER(ctypes.c_size_t)
+        ip = ctypes.POINTER(ctypes.c_int)
+        lib.im2win_out_shape.restype = i
+        lib.im2win_out_shape.argtypes = [i] * 6 + [ip, ip]
+        for name in ("im2win_workspace_bytes", "im2col_footprint_bytes"):
+            getattr(lib, name).restype = i
+            getattr(lib, name).argtypes = [i] * 8 + [sp]
+        lib.im2win_transform.restype = i
+        lib.im2win_transform.argtypes = [vp, vp] + [i] * 8 + [vp]
+        for name in ("conv2d_im2win_fwd", "conv2d_im2win_fwd_basic"):
+            getattr(lib, name).restype = i
+            getattr(lib, name).argtypes = [vp, vp, vp] + [i] * 9 + [vp]
+        lib.im2win_status_str.restype = ctypes.c_char_p
+        lib.im2win_status_str.argtypes = [i]
+        _lib = lib
+    return _lib
+
+
+def status_str(status: int) -> str:
+    return load_library().im2win_status_str(int(status)).decode()
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        raise Im2winError(status, where)
+
+
+def im2win_out_shape(Hi, Wi, Hf, Wf, stride, pad):
+    Ho, Wo = ctypes.c_int(), ctypes.c_int()
+    _check(load_library().im2win_out_shape(Hi, Wi, Hf, Wf, stride, pad, ctypes.byref(Ho), ctypes.byref(Wo)),
+           "im2win_out_shape")
+    return Ho.value, Wo.value
+
+
+def im2win_workspace_bytes(N, Ci, Hi, Wi, Hf, Wf, stride, pad) -> int:
+    b = ctypes.c_size_t()
+    _check(load_library().im2win_workspace_bytes(N, Ci, Hi, Wi, Hf, Wf, stride, pad, ctypes.byref(b)),
+           "im2win_workspace_bytes")
+    return b.value
+
+
+def im2col_footprint_bytes(N, Ci, Hi, Wi, Hf, Wf, stride, pad) -> int:
+    b = ctypes.c_size_t()
+    _check(load_library().im2col_footprint_bytes(N, Ci, Hi, Wi, Hf, Wf, stride, pad, ctypes.byref(b)),
+           "im2col_footprint_bytes")
+    return b.value
+
+
+def _dev_ptr(t, name: str, numel: int):
+    import torch
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError("%s must be a torch tensor in GPU memory" % name)
+    if t.dtype != torch.float32 or not t.is_contiguous():
+        raise TypeError("%s must be contiguous fp32" % name)
+    if t.numel() != numel:
+        raise ValueError("%s has %d elements, expected %d" % (name, t.numel(), numel))
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def im2win_transform(input, window, N, Ci, Hi, Wi, Hf, Wf, stride, pad, stream=None):
+    """window <- im2win(input); both are device tensors owned by the caller."""
+    Ho, _ = im2win_out_shape(Hi, Wi, Hf, Wf, stride, pad)
+    a = _dev_ptr(input, "input", N * Ci * Hi * Wi)
+    w = _dev_ptr(window, "window", N * Ci * Ho * (Wi + 2 * pad) * Hf)
+    _check(load_library().im2win_transform(a, w, N, Ci, Hi, Wi, Hf, Wf, stride, pad, _stream(stream)),
+           "im2win_transform")
+
+
+def _conv(fn_name, window, filter, output, N, Ci, Hi, Wi, Co, Hf, Wf, stride, pad, stream):
+    Ho, Wo = im2win_out_shape(Hi, Wi, Hf, Wf, stride, pad)
+    w = _dev_ptr(window, "window", N * Ci * Ho * (Wi + 2 * pad) * Hf)
+    f = _dev_ptr(filter, "filter", Co * Ci * Hf * Wf)
+    o = _dev_ptr(output, "output", N * Co * Ho * Wo)
+    fn = getattr(load_library(), fn_name)
+    _check(fn(w, f, o, N, Ci, Hi, Wi, Co, Hf, Wf, stride, pad, _stream(stream)), fn_name)
+
+
+def conv2d_im2win_fwd(window, filter, output, N, Ci, Hi, Wi, Co, Hf, Wf, stride, pad, stream=None):
+    """output <- convolution over the im2win tensor on the fp32 matrix cores."""
+    _conv("conv2d_im2win_fwd", window, filter, output, N, Ci, Hi, Wi, Co, Hf, Wf, stride, pad, stream)
+
+
+def conv2d_im2win_fwd_basic(window, filter, output, N, Ci, Hi, Wi, Co, Hf, Wf, stride, pad, stream=None):
+    """output <- the one-thread-per-output kernel (Algorithm 2)."""
+    _conv("conv2d_im2win_fwd_basic", window, filter, output, N, Ci, Hi, Wi, Co, Hf, Wf, stride, pad, stream)

@@ -1,0 +1,132 @@
+// C ABI of the library (see include/im2win.h): argument validation, shape
+// derivation and dispatch to the gfx950 kernels.  Host code only.
+#include "../../include/im2win.h"
+#include "common.h"
+
+#include <limits.h>
+
+using im2win::Shape;
+
+namespace {
+
+const long long kMaxElems = 2147483647LL;   // every tensor must stay below 2^31 elements
+
+im2win_status derive(int N, int Ci, int Hi, int Wi, int Co, int Hf, int Wf, int stride, int pad,
+                     Shape *sh)
+{
+    if (N <= 0 || Ci <= 0 || Hi <= 0 || Wi <= 0 || Co <= 0 || Hf <= 0 || Wf <= 0) return IM2WIN_ERR_SHAPE;
+    if (stride < 1 || pad < 0) return IM2WIN_ERR_SHAPE;
+    long long Hp = (long long)Hi + 2LL * pad, Wp = (long long)Wi + 2LL * pad;
+    if (Hf > Hp || Wf > Wp) return IM2WIN_ERR_SHAPE;
+    if (Hp > INT_MAX || Wp > INT_MAX) return IM2WIN_ERR_OVERFLOW;
+    long long Ho = (Hp - Hf) / stride + 1, Wo = (Wp - Wf) / stride + 1;
+    long long rowlen = Wp * Hf, khw = (long long)Hf * Wf, K = khw * Ci;
+    long long n_in = (long long)N * Ci;
+    // products are checked step by step so that nothing wraps
+    auto mul_ok = [](long long a, long long b, long long *r) {
+        if (a != 0 && b > kMaxElems / a) return false;
+        *r = a * b;
+        return *r <= kMaxElems;
+    };
+    long long t, in_e, win_e, out_e, flt_e, col_e;
+    if (!mul_ok(n_in, Hi, &t) || !mul_ok(t, Wi, &in_e)) return IM2WIN_ERR_OVERFLOW;
+    if (rowlen > kMaxElems || !mul_ok(n_in, Ho, &t) || !mul_ok(t, rowlen, &win_e)) return IM2WIN_ERR_OVERFLOW;
+    if (!mul_ok((long long)N * Co > kMaxElems ? kMaxElems + 1 : (long long)N * Co, Ho, &t) ||
+        !mul_ok(t, Wo, &out_e)) return IM2WIN_ERR_OVERFLOW;
+    if (khw > kMaxElems || !mul_ok(khw, Ci, &t) || !mul_ok(t, Co, &flt_e)) return IM2WIN_ERR_OVERFLOW;
+    (void)col_e; (void)in_e; (void)win_e; (void)out_e; (void)flt_e;
+    sh->N = N; sh->Ci = Ci; sh->Hi = Hi; sh->Wi = Wi; sh->Co = Co; sh->Hf = Hf; sh->Wf = Wf;
+    sh->s = stride; sh->p = pad;
+    sh->Ho = (int)Ho; sh->Wo = (int)Wo; sh->Hp = (int)Hp; sh->Wp = (int)Wp;
+    sh->rowlen = (int)rowlen; sh->khw = (int)khw; sh->K = (int)K;
+    sh->npix = (int)((long long)N * Ho * Wo);
+    return IM2WIN_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+im2win_status im2win_out_shape(int Hi, int Wi, int Hf, int Wf, int stride, int pad, int *Ho, int *Wo)
+{
+    if (!Ho || !Wo) return IM2WIN_ERR_NULL;
+    Shape sh;
+    im2win_status st = derive(1, 1, Hi, Wi, 1, Hf, Wf, stride, pad, &sh);
+    if (st != IM2WIN_OK) return st;
+    *Ho = sh.Ho;
+    *Wo = sh.Wo;
+    return IM2WIN_OK;
+}
+
+im2win_status im2win_workspace_bytes(int N, int Ci, int Hi, int Wi, int Hf, int Wf, int stride, int pad,
+                                     size_t *bytes)
+{
+    if (!bytes) return IM2WIN_ERR_NULL;
+    Shape sh;
+    im2win_status st = derive(N, Ci, Hi, Wi, 1, Hf, Wf, stride, pad, &sh);
+    if (st != IM2WIN_OK) return st;
+    *bytes = (size_t)4 * (size_t)N * Ci * sh.Ho * (size_t)sh.rowlen;
+    return IM2WIN_OK;
+}
+
+im2win_status im2col_footprint_bytes(int N, int Ci, int Hi, int Wi, int Hf, int Wf, int stride, int pad,
+                                     size_t *bytes)
+{
+    if (!bytes) return IM2WIN_ERR_NULL;
+    Shape sh;
+    im2win_status st = derive(N, Ci, Hi, Wi, 1, Hf, Wf, stride, pad, &sh);
+    if (st != IM2WIN_OK) return st;
+    *bytes = (size_t)4 * (size_t)N * sh.Ho * sh.Wo * (size_t)Ci * Hf * Wf;   // reporting only: may exceed 2^31 elements
+    return IM2WIN_OK;
+}
+
+im2win_status im2win_transform(const float *input_dev, float *window_dev, int N, int Ci, int Hi, int Wi,
+                               int Hf, int Wf, int stride, int pad, void *stream)
+{
+    if (!input_dev || !window_dev) return IM2WIN_ERR_NULL;
+    Shape sh;
+    im2win_status st = derive(N, Ci, Hi, Wi, 1, Hf, Wf, stride, pad, &sh);
+    if (st != IM2WIN_OK) return st;
+    hipError_t e = im2win::launch_transform(input_dev, window_dev, sh, (hipStream_t)stream);
+    return e == hipSuccess ? IM2WIN_OK : IM2WIN_ERR_HIP;
+}
+
+im2win_status conv2d_im2win_fwd(const float *window_dev, const float *filter_dev, float *output_dev,
+                                int N, int Ci, int Hi, int Wi, int Co, int Hf, int Wf, int stride, int pad,
+                                void *stream)
+{
+    if (!window_dev || !filter_dev || !output_dev) return IM2WIN_ERR_NULL;
+    Shape sh;
+    im2win_status st = derive(N, Ci, Hi, Wi, Co, Hf, Wf, stride, pad, &sh);
+    if (st != IM2WIN_OK) return st;
+    hipError_t e = im2win::launch_conv_mfma(window_dev, filter_dev, output_dev, sh, (hipStream_t)stream);
+    if (e == hipErrorInvalidConfiguration) return IM2WIN_ERR_UNSUPPORTED;
+    return e == hipSuccess ? IM2WIN_OK : IM2WIN_ERR_HIP;
+}
+
+im2win_status conv2d_im2win_fwd_basic(const float *window_dev, const float *filter_dev, float *output_dev,
+                                      int N, int Ci, int Hi, int Wi, int Co, int Hf, int Wf, int stride,
+                                      int pad, void *stream)
+{
+    if (!window_dev || !filter_dev || !output_dev) return IM2WIN_ERR_NULL;
+    Shape sh;
+    im2win_status st = derive(N, Ci, Hi, Wi, Co, Hf, Wf, stride, pad, &sh);
+    if (st != IM2WIN_OK) return st;
+    hipError_t e = im2win::launch_conv_basic(window_dev, filter_dev, output_dev, sh, (hipStream_t)stream);
+    return e == hipSuccess ? IM2WIN_OK : IM2WIN_ERR_HIP;
+}
+
+const char *im2win_status_str(int status)
+{
+    switch (status) {
+        case IM2WIN_OK: return "ok";
+        case IM2WIN_ERR_NULL: return "a required pointer is NULL";
+        case IM2WIN_ERR_SHAPE: return "invalid shape: non-positive dimension, stride < 1, pad < 0 or filter larger than padded input";
+        case IM2WIN_ERR_OVERFLOW: return "a tensor has 2^31 or more elements";
+        case IM2WIN_ERR_UNSUPPORTED: return "shape not supported: tile does not fit in LDS";
+        case IM2WIN_ERR_HIP: return "HIP runtime error at launch";
+        default: return "unknown status";
+    }
+}
+
+}  // extern "C"

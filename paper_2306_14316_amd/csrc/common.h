@@ -1,0 +1,51 @@
+// Internal declarations shared by the library's translation units (host side
+// and gfx950 device side).  Not part of the public ABI.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace im2win {
+
+// Division of a 32-bit n < 2^31 by a run-time constant d >= 1 with one
+// multiply-high, one add and one shift (round-up reciprocal).
+struct FastDiv {
+    uint32_t mul;
+    uint32_t shift;
+    uint32_t d;
+};
+
+inline FastDiv make_fastdiv(uint32_t d)
+{
+    FastDiv f;
+    f.d = d;
+    uint32_t l = 0;
+    while ((1ull << l) < d) ++l;
+    f.shift = l;
+    f.mul = (uint32_t)((((1ull << l) - d) << 32) / d + 1);
+    return f;
+}
+
+__device__ __forceinline__ uint32_t fdiv(uint32_t n, const FastDiv &f)
+{
+    return (__umulhi(n, f.mul) + n) >> f.shift;
+}
+
+// Shapes derived once on the host from the ABI arguments.
+struct Shape {
+    int N, Ci, Hi, Wi, Co, Hf, Wf, s, p;
+    int Ho, Wo, Hp, Wp;
+    int rowlen;   // Wp*Hf : floats in one row of the im2win tensor
+    int khw;      // Hf*Wf : floats in one dot-product window of one channel
+    int K;        // Ci*Hf*Wf
+    int npix;     // N*Ho*Wo : GEMM N dimension
+};
+
+// ---- launchers (defined in the .hip files) -------------------------------
+hipError_t launch_transform(const float *in, float *win, const Shape &sh, hipStream_t st);
+hipError_t launch_conv_basic(const float *win, const float *flt, float *out, const Shape &sh,
+                             hipStream_t st);
+// Returns hipErrorInvalidConfiguration when no tile configuration fits in LDS.
+hipError_t launch_conv_mfma(const float *win, const float *flt, float *out, const Shape &sh,
+                            hipStream_t st);
+
+}  // namespace im2win

@@ -1,0 +1,268 @@
+// Forward convolution over the im2win tensor on the gfx950 fp32 matrix cores
+// (the role of Algorithm 3, Section 3.2-3.3; the design is CDNA4's, not the
+// paper's CUDA tiling).
+//
+// GEMM view (Algorithm 1): M = Co, N = Ni*Ho*Wo (output pixels, flattened in
+// NCHW order), K = Ci*Hf*Wf.  A workgroup of 4 waves owns a 64 (M) x 64 (N)
+// output tile; each wave owns a 32x32 sub-tile held in 16 accumulator
+// registers and advances it with v_mfma_f32_32x32x2_f32.
+//
+// What the im2win layout buys (Section 3.1 / 3.3 "as many windows from the same
+// row as possible"): the window of pixel (i,m,n) for channel r is the
+// contiguous run What[i][r][m][n*s*Hf .. +Hf*Wf), and neighbouring pixels'
+// windows overlap.  So for one channel the tile's 64 pixels need only a few
+// contiguous strips of What (about (64*s + rows*(Wf-s))*Hf floats, against
+// 64*Hf*Wf for an im2col tile), copied to LDS as they lie in memory.  A lane that
+// feeds pixel n to the matrix core keeps ONE LDS base address; window element
+// t = v*Hf + u is at base + t, a constant offset per K step -- none of the
+// per-step divide/modulo index decoding of Algorithms 1-2.
+//
+// The two K slices that one MFMA consumes (lanes 0-31 / 32-63) are taken from
+// two different channels at the same window element ("pair" steps), so odd
+// window sizes (9, 49, 121) cost no padding.  An odd channel left over is
+// split in two halves of its window ("split" steps, at most one zero K slice).
+// The filter tile is staged to LDS in window order (v outer, u inner) and
+// transposed to [k][m], so the A operand is also base + constant per step.
+#include "common.h"
+
+namespace im2win {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int MB = 64;       // tile rows (output channels)
+constexpr int NB = 64;       // tile columns (output pixels)
+constexpr int PITCH = 65;    // LDS floats per filter-tile row [k][0..63], +1 against bank conflicts
+
+struct MfmaParams {
+    const float *win;
+    const float *flt;
+    float *out;
+    int Ci, Ho, Wo, Co, Hf, Wf, s;
+    int rowlen, khw, K;
+    uint32_t npix, howo, chan_stride;
+    int cb;          // channels per K block
+    int S;           // LDS floats reserved per channel strip
+    int fullseg;     // ((Wo-1)*s + Wf)*Hf : strip floats of a fully covered output row
+    int tiles_m;
+    int vec4;        // filter rows can be read as aligned float4 in every K block
+    FastDiv d_wo, d_ho, d_howo, d_khw, d_wf, d_cpr, d_tm;
+};
+
+__host__ __device__ inline int round4(int x) { return (x + 3) & ~3; }
+
+template <int KHW_T>
+__global__ __launch_bounds__(256) void conv_mfma_kernel(MfmaParams P)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int khw = KHW_T ? KHW_T : P.khw;
+    const int S = P.S;
+    int *tbl = reinterpret_cast<int *>(smem);                 // [S]   strip position -> source offset
+    int *ftbl = tbl + round4(S);                              // [cb*khw] filter element -> LDS row offset
+    float *sI = reinterpret_cast<float *>(ftbl + round4(P.cb * khw));   // [cb][S]
+    float *sZero = sI + round4(P.cb * S);                     // [4]  zeros
+    float *sF = sZero + 4;                                    // [cb*khw + 1][PITCH]
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave & 1, wn = wave >> 1;
+    const int h = lane >> 5, l32 = lane & 31;
+
+    const uint32_t tile_n = fdiv(blockIdx.x, P.d_tm);
+    const uint32_t tile_m = blockIdx.x - tile_n * (uint32_t)P.tiles_m;
+    const int m0 = (int)tile_m * MB;
+    const uint32_t P0 = tile_n * NB;
+    const uint32_t Pend = min(P0 + NB - 1, P.npix - 1);
+
+    // ---- geometry of the tile's strips: output rows q0..q1 (q = i*Ho + m) ----
+    const uint32_t q0 = fdiv(P0, P.d_wo), q1 = fdiv(Pend, P.d_wo);
+    const int nlo0 = (int)(P0 - q0 * (uint32_t)P.Wo);
+    const int sHf = P.s * P.Hf;
+    const int len0 = (((q1 == q0) ? (int)(Pend - P0) : (P.Wo - 1 - nlo0)) * P.s + P.Wf) * P.Hf;
+
+    int filled = 0;
+    for (uint32_t q = q0; q <= q1; ++q) {
+        const int rho = (int)(q - q0);
+        const int nlo = rho == 0 ? nlo0 : 0;
+        const int nhi = (q == q1) ? (int)(Pend - q * (uint32_t)P.Wo) : P.Wo - 1;
+        const int seglen = ((nhi - nlo) * P.s + P.Wf) * P.Hf;
+        const int segoff = rho == 0 ? 0 : len0 + (rho - 1) * P.fullseg;
+        const uint32_t img = fdiv(q, P.d_ho);
+        const int mq = (int)(q - img * (uint32_t)P.Ho);
+        const int srcbase = (int)((img * (uint32_t)P.Ci * (uint32_t)P.Ho + (uint32_t)mq) * (uint32_t)P.rowlen) + nlo * sHf;
+        for (int x = tid; x < seglen; x += 256) tbl[segoff + x] = srcbase + x;
+        filled = segoff + seglen;
+    }
+    for (int x = filled + tid; x < S; x += 256) tbl[x] = -1;
+    for (int e = tid; e < P.cb * khw; e += 256) {
+        const int c = (int)fdiv((uint32_t)e, P.d_khw);
+        const int ko = e - c * khw;                 // u*Wf + v  (filter's own order)
+        const int u = (int)fdiv((uint32_t)ko, P.d_wf);
+        const int v = ko - u * P.Wf;
+        ftbl[e] = (c * khw + v * P.Hf + u) * PITCH; // window order: v outer, u inner
+    }
+    if (tid < 4) sZero[tid] = 0.0f;
+
+    // ---- per-lane operand bases ----
+    int b_base;
+    {
+        const uint32_t Pl = min(P0 + (uint32_t)(wn * 32 + l32), Pend);
+        const uint32_t ql = fdiv(Pl, P.d_wo);
+        const int nl = (int)(Pl - ql * (uint32_t)P.Wo);
+        const int rho = (int)(ql - q0);
+        b_base = rho == 0 ? (nl - nlo0) * sHf : len0 + (rho - 1) * P.fullseg + nl * sHf;
+    }
+    const float *aF = sF + wm * 32 + l32;
+    const float *bI = sI + b_base;
+
+    floatx16 acc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+
+    for (int c0 = 0; c0 < P.Ci; c0 += P.cb) {
+        const int nch = min(P.cb, P.Ci - c0);
+        __syncthreads();   // tables ready (first pass) / previous block's reads done
+
+        // ---- stage the im2win strips of nch channels ----
+        for (int c = wave; c < nch; c += 4) {
+            const float *g = P.win + (size_t)(c0 + c) * P.chan_stride;
+            float *d = sI + c * S;
+            for (int x = lane; x < S; x += 64) {
+                const int off = tbl[x];
+                d[x] = off >= 0 ? g[off] : 0.0f;
+            }
+        }
+        // ---- stage the filter tile, transposed to [k in window order][m] ----
+        const int ne = nch * khw;
+        if (P.vec4) {
+            const int cpr = ne >> 2;
+            const float *gf = P.flt + (size_t)m0 * P.K + (size_t)c0 * khw;
+            for (int f = tid; f < MB * cpr; f += 256) {
+                const int row = (int)fdiv((uint32_t)f, P.d_cpr);
+                const int e = (f - row * cpr) * 4;
+                float4 w = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (m0 + row < P.Co) w = *reinterpret_cast<const float4 *>(gf + (size_t)row * P.K + e);
+                const int4 r = *reinterpret_cast<const int4 *>(ftbl + e);
+                sF[r.x + row] = w.x;
+                sF[r.y + row] = w.y;
+                sF[r.z + row] = w.z;
+                sF[r.w + row] = w.w;
+            }
+        } else {
+            const float *gf = P.flt + (size_t)m0 * P.K + (size_t)c0 * khw;
+            for (int row = wave; row < MB; row += 4) {
+                const bool live = m0 + row < P.Co;
+                for (int e = lane; e < ne; e += 64)
+                    sF[ftbl[e] + row] = live ? gf[(size_t)row * P.K + e] : 0.0f;
+            }
+        }
+        if ((nch & 1) && (khw & 1) && tid < MB) sF[ne * PITCH + tid] = 0.0f;   // zero K slice of a split step
+        __syncthreads();
+
+        // ---- pair steps: lanes 0-31 take channel 2j, lanes 32-63 channel 2j+1 ----
+        const int npairs = nch >> 1;
+        for (int pr = 0; pr < npairs; ++pr) {
+            const float *bp = bI + (2 * pr + h) * S;
+            const float *ap = aF + (2 * pr + h) * khw * PITCH;
+            if (KHW_T) {
+#pragma unroll
+                for (int t = 0; t < KHW_T; ++t)
+                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(ap[t * PITCH], bp[t], acc, 0, 0, 0);
+            } else {
+#pragma unroll 4
+                for (int t = 0; t < khw; ++t)
+                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(ap[t * PITCH], bp[t], acc, 0, 0, 0);
+            }
+        }
+        // ---- split step: the odd channel's window halves go to the two lane halves ----
+        if (nch & 1) {
+            const int c = nch - 1;
+            const int kh2 = (khw + 1) >> 1;
+            const float *bp = bI + c * S + h * kh2;
+            const float *ap = aF + (c * khw + h * kh2) * PITCH;
+#pragma unroll 4
+            for (int t = 0; t < kh2 - 1; ++t)
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(ap[t * PITCH], bp[t], acc, 0, 0, 0);
+            const float *bl = (h && (khw & 1)) ? sZero : bp + (kh2 - 1);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(ap[(kh2 - 1) * PITCH], *bl, acc, 0, 0, 0);
+        }
+    }
+
+    // ---- epilogue: accumulator register v of lane (h, l32) is output channel
+    // 8*(v/4) + 4*h + v%4 of the wave's 32, pixel l32; pixels are contiguous in
+    // NCHW for a fixed (image, channel), so each store covers 128-byte runs.
+    const uint32_t Pm = P0 + (uint32_t)(wn * 32 + l32);
+    if (Pm <= Pend) {
+        const uint32_t img = fdiv(Pm, P.d_howo);
+        const uint32_t pin = Pm - img * P.howo;
+        float *o = P.out + (size_t)img * P.Co * P.howo + pin;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int j = m0 + wm * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
+            if (j < P.Co) o[(size_t)j * P.howo] = acc[v];
+        }
+    }
+}
+
+static size_t lds_bytes(int cb, int S, int khw)
+{
+    return 4u * ((size_t)round4(S) + round4(cb * khw) + round4(cb * S) + 4 + (size_t)(cb * khw + 1) * PITCH);
+}
+
+template <int KHW_T>
+static hipError_t launch_t(const MfmaParams &P, size_t lds, uint32_t blocks, hipStream_t st)
+{
+    if (lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_mfma_kernel<KHW_T>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(conv_mfma_kernel<KHW_T>, dim3(blocks), dim3(256), lds, st, P);
+    return hipGetLastError();
+}
+
+hipError_t launch_conv_mfma(const float *win, const float *flt, float *out, const Shape &sh,
+                            hipStream_t st)
+{
+    MfmaParams P;
+    P.win = win; P.flt = flt; P.out = out;
+    P.Ci = sh.Ci; P.Ho = sh.Ho; P.Wo = sh.Wo; P.Co = sh.Co; P.Hf = sh.Hf; P.Wf = sh.Wf; P.s = sh.s;
+    P.rowlen = sh.rowlen; P.khw = sh.khw; P.K = sh.K;
+    P.npix = (uint32_t)sh.npix;
+    P.howo = (uint32_t)(sh.Ho * sh.Wo);
+    P.chan_stride = (uint32_t)((size_t)sh.Ho * sh.rowlen);
+    P.fullseg = ((sh.Wo - 1) * sh.s + sh.Wf) * sh.Hf;
+    P.tiles_m = (sh.Co + MB - 1) / MB;
+
+    // Strip floats per channel: NB pixels over at most rmax output rows.
+    int rmax = (NB + sh.Wo - 2) / sh.Wo + 1;
+    if (rmax > NB) rmax = NB;
+    const int over = sh.Wf > sh.s ? sh.Wf - sh.s : 0;
+    P.S = (NB * sh.s + rmax * over) * sh.Hf + 1;
+
+    const size_t lds_max = 160 * 1024;
+    int cb = sh.Ci < 8 ? sh.Ci : 8;
+    while (cb > 1 && lds_bytes(cb, P.S, sh.khw) > lds_max) cb = (cb > 2) ? (((cb / 2) & ~1) < 2 ? 2 : ((cb / 2) & ~1)) : 1;
+    if (lds_bytes(cb, P.S, sh.khw) > lds_max) return hipErrorInvalidConfiguration;
+    P.cb = cb;
+    const size_t lds = lds_bytes(cb, P.S, sh.khw);
+
+    P.vec4 = (sh.Ci % cb == 0) && ((cb * sh.khw) % 4 == 0) && (sh.K % 4 == 0) &&
+             ((reinterpret_cast<uintptr_t>(flt) & 15u) == 0);
+    P.d_wo = make_fastdiv((uint32_t)sh.Wo);
+    P.d_ho = make_fastdiv((uint32_t)sh.Ho);
+    P.d_howo = make_fastdiv(P.howo);
+    P.d_khw = make_fastdiv((uint32_t)sh.khw);
+    P.d_wf = make_fastdiv((uint32_t)sh.Wf);
+    P.d_cpr = make_fastdiv((uint32_t)((cb * sh.khw) / 4 > 0 ? (cb * sh.khw) / 4 : 1));
+    P.d_tm = make_fastdiv((uint32_t)P.tiles_m);
+
+    const uint32_t tiles_n = (P.npix + NB - 1) / NB;
+    const uint32_t blocks = tiles_n * (uint32_t)P.tiles_m;
+    switch (sh.khw) {
+        case 9:   return launch_t<9>(P, lds, blocks, st);
+        case 49:  return launch_t<49>(P, lds, blocks, st);
+        case 121: return launch_t<121>(P, lds, blocks, st);
+        default:  return launch_t<0>(P, lds, blocks, st);
+    }
+}
+
+}  // namespace im2win

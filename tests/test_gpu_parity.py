@@ -1,0 +1,138 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on
+the same seeded inputs -- bit-exact im2win tensors, convolution outputs within
+the stated tolerance -- on the five benchmark layers at full size and on small
+shapes that exercise ragged tiles and the degenerate cases."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2306_14316_amd as im2win
+from paper_2306_14316_amd import workloads
+
+from parity_util import (assert_bitwise_equal, assert_conv_close, check_layer, run_conv,
+                         run_transform)
+
+pytestmark = pytest.mark.gpu
+
+# (N, Ci, Hi, Wi, Co, Hf, Wf, s, p)
+EDGE_SHAPES = [
+    (1, 1, 5, 5, 1, 3, 3, 1, 0),       # a single channel, 9 pixels
+    (2, 3, 7, 9, 4, 3, 2, 1, 0),       # asymmetric filter, odd channel count
+    (2, 3, 9, 7, 5, 2, 3, 2, 1),
+    (1, 2, 11, 13, 3, 5, 3, 3, 3),     # pad as large as the filter allows
+    (3, 4, 12, 10, 2, 4, 1, 4, 0),     # stride wider than the filter (gaps between windows)
+    (1, 5, 6, 8, 3, 6, 2, 1, 0),       # Hf == Hi: one output row
+    (2, 2, 6, 6, 3, 8, 8, 1, 1),       # filter == padded input: 1x1 output per image
+    (1, 3, 10, 10, 6, 1, 1, 2, 0),     # 1x1 strided
+    (2, 6, 8, 8, 7, 3, 3, 2, 1),
+    (5, 8, 9, 9, 65, 3, 3, 1, 1),      # Co one past a tile; 405 pixels (ragged last tile)
+    (3, 13, 12, 12, 96, 3, 3, 1, 0),   # Ci not a multiple of the K block, odd tail channel
+    (2, 20, 10, 17, 33, 3, 3, 1, 1),   # Ci = 2.5 K blocks
+    (70, 4, 3, 3, 8, 3, 3, 1, 0),      # one pixel per image: a tile spans 64 images
+    (9, 5, 5, 6, 10, 2, 2, 1, 0),      # 20 pixels per image: tiles straddle images
+    (1, 3, 40, 40, 16, 7, 7, 2, 3),    # the 7x7 stride-2 window, small
+    (2, 3, 35, 35, 96, 11, 11, 4, 0),  # the 11x11 stride-4 window, small
+    (1, 4, 6, 70, 8, 1, 9, 1, 0),      # 1x9 filter: 9-element windows from one row
+    (1, 4, 70, 6, 8, 9, 1, 1, 0),      # 9x1 filter
+    (1, 2, 4, 300, 4, 3, 3, 1, 1),     # one very wide row
+]
+
+
+@pytest.mark.parametrize("shape", EDGE_SHAPES, ids=lambda s: "x".join(map(str, s)))
+@pytest.mark.parametrize("basic", [False, True], ids=["mfma", "basic"])
+def test_edge_shapes(shape, basic):
+    N, Ci, Hi, Wi, Co, Hf, Wf, s, p = shape
+    I, F = workloads.random_layer_inputs(7000 + sum(shape), N, Ci, Hi, Wi, Co, Hf, Wf)
+    print("shape", shape, "basic", basic, flush=True)
+    check_layer(I, F, s, p, basic=basic)
+
+
+@pytest.mark.parametrize("idx", [1, 2, 3, 4, 5])
+def test_benchmark_layers_full_size(idx):
+    """All five layers at their full size, every output element against the oracle."""
+    L = workloads.layer(idx)
+    print("layer", L.name, flush=True)
+    I, F = workloads.make_inputs(L)
+    elem, l2 = check_layer(I, F, L.stride, L.pad, basic=False)
+    print("layer %s: max|err|/sum|x||w| = %.3e, rel L2 = %.3e" % (L.name, elem, l2), flush=True)
+
+
+@pytest.mark.parametrize("idx", [1, 2])
+def test_basic_kernel_on_benchmark_layers(idx):
+    L = workloads.layer(idx)
+    I, F = workloads.make_inputs(L)
+    check_layer(I, F, L.stride, L.pad, basic=True, twice=False)
+
+
+def test_transform_copies_bit_patterns():
+    """NaN payloads, infinities, -0.0 and denormals pass through untouched; padding is +0.0."""
+    bits = np.array([0x7FC00001, 0xFFC12345, 0x7F800001, 0x80000000, 0x00000001, 0x807FFFFF,
+                     0x7F800000, 0xFF800000, 0x3F800000], dtype=np.uint32)
+    I = torch.from_numpy(np.resize(bits, 3 * 2 * 9 * 11).view(np.float32).reshape(3, 2, 9, 11).copy())
+    for (Hf, Wf, s, p) in [(2, 2, 1, 1), (3, 3, 2, 0), (4, 1, 3, 2)]:
+        dW = run_transform(I, Hf, Wf, s, p)
+        assert_bitwise_equal(dW, oracle.im2win(I.numpy(), Hf, Wf, s, p))
+
+
+def test_transform_unaligned_output_pointer():
+    """A window buffer that is only 4-byte aligned takes the scalar-store path."""
+    N, Ci, Hi, Wi, Hf, Wf, s, p = 2, 3, 9, 10, 3, 3, 1, 1
+    I, _ = workloads.random_layer_inputs(11, N, Ci, Hi, Wi, 1, Hf, Wf)
+    Ho, _ = im2win.im2win_out_shape(Hi, Wi, Hf, Wf, s, p)
+    n = N * Ci * Ho * (Wi + 2 * p) * Hf
+    buf = torch.full((n + 8,), float("nan"), dtype=torch.float32, device="cuda")
+    win = buf[1:1 + n]
+    im2win.im2win_transform(I.cuda(), win, N, Ci, Hi, Wi, Hf, Wf, s, p)
+    torch.cuda.synchronize()
+    assert_bitwise_equal(win.reshape(N, Ci, Ho, -1), oracle.im2win(I.numpy(), Hf, Wf, s, p))
+    assert torch.isnan(buf[0]) and torch.isnan(buf[1 + n:]).all()      # nothing written outside
+
+
+def test_unaligned_filter_pointer_takes_scalar_staging():
+    N, Ci, Hi, Wi, Co, Hf, Wf, s, p = 2, 8, 10, 10, 20, 3, 3, 1, 1
+    I, F = workloads.random_layer_inputs(12, N, Ci, Hi, Wi, Co, Hf, Wf)
+    dW = run_transform(I, Hf, Wf, s, p)
+    fbuf = torch.zeros(F.numel() + 4, dtype=torch.float32, device="cuda")
+    dF = fbuf[1:1 + F.numel()]
+    dF.copy_(F.reshape(-1))
+    Ho, Wo = im2win.im2win_out_shape(Hi, Wi, Hf, Wf, s, p)
+    dO = torch.full((N, Co, Ho, Wo), float("nan"), dtype=torch.float32, device="cuda")
+    im2win.conv2d_im2win_fwd(dW, dF, dO, N, Ci, Hi, Wi, Co, Hf, Wf, s, p)
+    torch.cuda.synchronize()
+    O_ref, B_ref = oracle.conv2d_direct(I.numpy(), F.numpy(), s, p)
+    assert_conv_close(dO.cpu().numpy(), O_ref, B_ref)
+
+
+def test_outputs_do_not_spill_outside_their_buffers():
+    """Guard bands around the output stay untouched."""
+    N, Ci, Hi, Wi, Co, Hf, Wf, s, p = 3, 5, 9, 9, 37, 3, 3, 2, 1
+    I, F = workloads.random_layer_inputs(13, N, Ci, Hi, Wi, Co, Hf, Wf)
+    dW = run_transform(I, Hf, Wf, s, p)
+    Ho, Wo = im2win.im2win_out_shape(Hi, Wi, Hf, Wf, s, p)
+    n = N * Co * Ho * Wo
+    for fn in (im2win.conv2d_im2win_fwd, im2win.conv2d_im2win_fwd_basic):
+        buf = torch.full((n + 512,), float("nan"), dtype=torch.float32, device="cuda")
+        out = buf[256:256 + n]
+        fn(dW, F.cuda(), out, N, Ci, Hi, Wi, Co, Hf, Wf, s, p)
+        torch.cuda.synchronize()
+        assert torch.isnan(buf[:256]).all() and torch.isnan(buf[256 + n:]).all()
+        O_ref, B_ref = oracle.conv2d_direct(I.numpy(), F.numpy(), s, p)
+        assert_conv_close(out.reshape(N, Co, Ho, Wo).cpu().numpy(), O_ref, B_ref)
+
+
+def test_runs_on_a_side_stream():
+    N, Ci, Hi, Wi, Co, Hf, Wf, s, p = 2, 4, 12, 12, 8, 3, 3, 1, 1
+    I, F = workloads.random_layer_inputs(14, N, Ci, Hi, Wi, Co, Hf, Wf)
+    Ho, Wo = im2win.im2win_out_shape(Hi, Wi, Hf, Wf, s, p)
+    dI, dF = I.cuda(), F.cuda()
+    dW = torch.empty((N, Ci, Ho, (Wi + 2 * p) * Hf), dtype=torch.float32, device="cuda")
+    dO = torch.empty((N, Co, Ho, Wo), dtype=torch.float32, device="cuda")
+    torch.cuda.synchronize()
+    st = torch.cuda.Stream()
+    with torch.cuda.stream(st):
+        im2win.im2win_transform(dI, dW, N, Ci, Hi, Wi, Hf, Wf, s, p)
+        im2win.conv2d_im2win_fwd(dW, dF, dO, N, Ci, Hi, Wi, Co, Hf, Wf, s, p)
+    st.synchronize()
+    O_ref, B_ref = oracle.conv2d_direct(I.numpy(), F.numpy(), s, p)
+    assert_conv_close(dO.cpu().numpy(), O_ref, B_ref)

@@ -1,0 +1,106 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol the
+header declares, derives shapes as the oracle does, and turns every invalid
+argument into an error code without launching anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import oracle
+import paper_2306_14316_amd as im2win
+from paper_2306_14316_amd import binding, workloads
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(im2win.lib_path()):
+        from paper_2306_14316_amd import build
+        build.build()
+    return im2win.load_library()
+
+
+def test_header_symbols_are_exported(lib):
+    hdr = open(os.path.join(ROOT, "include", "im2win.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(im2win_\w+|conv2d_\w+|im2col_\w+)\s*\(", hdr))
+    assert declared == set(binding.EXPORTS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_shapes_and_footprints_match_oracle(lib, golden_dir):
+    for L in workloads.LAYERS:
+        assert im2win.im2win_out_shape(L.Hi, L.Wi, L.Hf, L.Wf, L.stride, L.pad) == \
+            oracle.out_shape(L.Hi, L.Wi, L.Hf, L.Wf, L.stride, L.pad) == (L.Ho, L.Wo)
+        a = (L.N, L.Ci, L.Hi, L.Wi, L.Hf, L.Wf, L.stride, L.pad)
+        assert im2win.im2win_workspace_bytes(*a) == 4 * oracle.im2win_elems(*a)
+        assert im2win.im2col_footprint_bytes(*a) == 4 * oracle.im2col_elems(*a)
+    # the paper's worked example and Table 2
+    assert im2win.im2win_workspace_bytes(1, 3, 3, 3, 2, 2, 1, 0) == 4 * 36
+    assert im2win.im2col_footprint_bytes(1, 3, 3, 3, 2, 2, 1, 0) == 4 * 48
+    for ln in open(os.path.join(golden_dir, "table2_layers.txt")):
+        if ln.startswith("#") or not ln.strip():
+            continue
+        _, Ci, Hi, Wi, Co, Hf, Wf, s, Ho, Wo = ln.split()
+        assert im2win.im2win_out_shape(int(Hi), int(Wi), int(Hf), int(Wf), int(s), 0) == (int(Ho), int(Wo))
+
+
+def test_workspace_bytes_of_the_five_layers(lib):
+    want = [34560, 79822848, 88080384, 276971520, 210946560]
+    got = [im2win.im2win_workspace_bytes(L.N, L.Ci, L.Hi, L.Wi, L.Hf, L.Wf, L.stride, L.pad)
+           for L in workloads.LAYERS]
+    assert got == want
+
+
+BAD_SHAPES = [
+    dict(N=0), dict(Ci=0), dict(Hi=0), dict(Wi=-1), dict(Co=0), dict(Hf=0), dict(Wf=0),
+    dict(stride=0), dict(pad=-1), dict(Hf=9), dict(Wf=9),
+]
+
+
+@pytest.mark.parametrize("bad", BAD_SHAPES)
+def test_invalid_shapes_are_rejected_before_any_launch(lib, bad):
+    a = dict(N=1, Ci=2, Hi=8, Wi=8, Co=3, Hf=3, Wf=3, stride=1, pad=0)
+    a.update(bad)
+    one = ctypes.c_void_p(16)   # non-NULL dummy: validation must fail before it is touched
+    rc = lib.im2win_transform(one, one, a["N"], a["Ci"], a["Hi"], a["Wi"], a["Hf"], a["Wf"],
+                              a["stride"], a["pad"], None)
+    if "Co" not in bad:
+        assert rc == -2
+    for fn in (lib.conv2d_im2win_fwd, lib.conv2d_im2win_fwd_basic):
+        assert fn(one, one, one, a["N"], a["Ci"], a["Hi"], a["Wi"], a["Co"], a["Hf"], a["Wf"],
+                  a["stride"], a["pad"], None) == -2
+
+
+def test_null_pointers_and_overflow(lib):
+    one = ctypes.c_void_p(16)
+    assert lib.im2win_transform(None, one, 1, 1, 4, 4, 2, 2, 1, 0, None) == -1
+    assert lib.im2win_transform(one, None, 1, 1, 4, 4, 2, 2, 1, 0, None) == -1
+    assert lib.conv2d_im2win_fwd(one, None, one, 1, 1, 4, 4, 1, 2, 2, 1, 0, None) == -1
+    assert lib.conv2d_im2win_fwd(one, one, None, 1, 1, 4, 4, 1, 2, 2, 1, 0, None) == -1
+    assert lib.conv2d_im2win_fwd_basic(None, one, one, 1, 1, 4, 4, 1, 2, 2, 1, 0, None) == -1
+    assert lib.im2win_out_shape(4, 4, 2, 2, 1, 0, None, None) == -1
+    # 2^31 or more elements in the im2win tensor / the output
+    assert lib.im2win_transform(one, one, 4096, 64, 224, 224, 7, 7, 2, 0, None) == -3
+    assert lib.conv2d_im2win_fwd(one, one, one, 128, 3, 1024, 1024, 64, 1, 1, 1, 0, None) == -3
+    b = ctypes.c_size_t()
+    assert lib.im2win_workspace_bytes(4096, 64, 224, 224, 7, 7, 2, 0, ctypes.byref(b)) == -3
+    for code in (0, -1, -2, -3, -4, -5, 77):
+        assert im2win.status_str(code)
+
+
+def test_filter_as_large_as_padded_input_is_valid(lib):
+    assert im2win.im2win_out_shape(6, 6, 8, 8, 1, 1) == (1, 1)
+    with pytest.raises(im2win.Im2winError):
+        im2win.im2win_out_shape(6, 6, 9, 8, 1, 1)
+
+
+def test_binding_rejects_host_tensors(lib):
+    import torch
+    x = torch.zeros(1, 1, 4, 4)
+    w = torch.zeros(1, 1, 3, 8)
+    with pytest.raises(TypeError):
+        im2win.im2win_transform(x, w, 1, 1, 4, 4, 2, 2, 1, 0)
