@@ -23,32 +23,11 @@
 // split in two halves of its window ("split" steps, at most one zero K slice).
 // The filter tile is staged to LDS in window order (v outer, u inner) and
 // transposed to [k][m], so the A operand is also base + constant per step.
-#include "common.h"
+#include "conv_mfma_tile.h"
 
 namespace im2win {
 
-typedef float floatx16 __attribute__((ext_vector_type(16)));
-
-constexpr int MB = 64;       // tile rows (output channels)
-constexpr int NB = 64;       // tile columns (output pixels)
 constexpr int PITCH = 65;    // LDS floats per filter-tile row [k][0..63], +1 against bank conflicts
-
-struct MfmaParams {
-    const float *win;
-    const float *flt;
-    float *out;
-    int Ci, Ho, Wo, Co, Hf, Wf, s;
-    int rowlen, khw, K;
-    uint32_t npix, howo, chan_stride;
-    int cb;          // channels per K block
-    int S;           // LDS floats reserved per channel strip
-    int fullseg;     // ((Wo-1)*s + Wf)*Hf : strip floats of a fully covered output row
-    int tiles_m;
-    int vec4;        // filter rows can be read as aligned float4 in every K block
-    FastDiv d_wo, d_ho, d_howo, d_khw, d_wf, d_cpr, d_tm;
-};
-
-__host__ __device__ inline int round4(int x) { return (x + 3) & ~3; }
 
 template <int KHW_T>
 __global__ __launch_bounds__(256) void conv_mfma_kernel(MfmaParams P)
@@ -66,8 +45,9 @@ __global__ __launch_bounds__(256) void conv_mfma_kernel(MfmaParams P)
     const int wm = wave & 1, wn = wave >> 1;
     const int h = lane >> 5, l32 = lane & 31;
 
-    const uint32_t tile_n = fdiv(blockIdx.x, P.d_tm);
-    const uint32_t tile_m = blockIdx.x - tile_n * (uint32_t)P.tiles_m;
+    const uint32_t lb = xcd_swizzle(blockIdx.x, gridDim.x);
+    const uint32_t tile_n = fdiv(lb, P.d_tm);
+    const uint32_t tile_m = lb - tile_n * (uint32_t)P.tiles_m;
     const int m0 = (int)tile_m * MB;
     const uint32_t P0 = tile_n * NB;
     const uint32_t Pend = min(P0 + NB - 1, P.npix - 1);
@@ -186,20 +166,7 @@ __global__ __launch_bounds__(256) void conv_mfma_kernel(MfmaParams P)
         }
     }
 
-    // ---- epilogue: accumulator register v of lane (h, l32) is output channel
-    // 8*(v/4) + 4*h + v%4 of the wave's 32, pixel l32; pixels are contiguous in
-    // NCHW for a fixed (image, channel), so each store covers 128-byte runs.
-    const uint32_t Pm = P0 + (uint32_t)(wn * 32 + l32);
-    if (Pm <= Pend) {
-        const uint32_t img = fdiv(Pm, P.d_howo);
-        const uint32_t pin = Pm - img * P.howo;
-        float *o = P.out + (size_t)img * P.Co * P.howo + pin;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int j = m0 + wm * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
-            if (j < P.Co) o[(size_t)j * P.howo] = acc[v];
-        }
-    }
+    store_tile(P, acc, P0, Pend, m0, wm, wn, h, l32);
 }
 
 static size_t lds_bytes(int cb, int S, int khw)
@@ -257,6 +224,10 @@ hipError_t launch_conv_mfma(const float *win, const float *flt, float *out, cons
 
     const uint32_t tiles_n = (P.npix + NB - 1) / NB;
     const uint32_t blocks = tiles_n * (uint32_t)P.tiles_m;
+    {
+        hipError_t fe = launch_conv_mfma_fast(P, sh, blocks, st);
+        if (fe != hipErrorNotSupported) return fe;
+    }
     switch (sh.khw) {
         case 9:   return launch_t<9>(P, lds, blocks, st);
         case 49:  return launch_t<49>(P, lds, blocks, st);
