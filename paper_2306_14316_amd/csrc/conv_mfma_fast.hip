@@ -16,6 +16,8 @@
 
 namespace im2win {
 
+typedef __attribute__((address_space(3))) float lds_float;   // a float in LDS
+
 template <int HF, int WF, int CB, int JX>
 __global__ __launch_bounds__(256) void conv_mfma_fast_kernel(MfmaParams P)
 {
@@ -25,13 +27,15 @@ __global__ __launch_bounds__(256) void conv_mfma_fast_kernel(MfmaParams P)
     constexpr int NF4 = MB * CPR;
     constexpr int JF = (NF4 + 255) / 256;   // float4 chunks per thread
     constexpr int PF = KB | 1;              // odd LDS pitch of a filter row
+    constexpr int SS = 256 * JX;            // LDS floats per channel strip (compile-time stride)
+    constexpr int SF_FLOATS = (MB * PF + 3) & ~3;
+    constexpr int STAGE = SF_FLOATS + CB * SS;   // floats per LDS stage
     static_assert(KB % 4 == 0, "K block must be a multiple of 4 floats");
     static_assert(CB % 2 == 0, "pair steps need an even channel count");
 
+    // two LDS stages, each [filter tile MB x PF][CB strips of SS floats]
     extern __shared__ __align__(16) unsigned char smem[];
-    float *sF = reinterpret_cast<float *>(smem);     // [MB][PF]
-    float *sI = sF + round4(MB * PF);                // [CB][S]
-    const int S = P.S;
+    float *lds = reinterpret_cast<float *>(smem);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave & 1, wn = wave >> 1;
@@ -50,10 +54,11 @@ __global__ __launch_bounds__(256) void conv_mfma_fast_kernel(MfmaParams P)
     const int sHf = P.s * HF;
     const int len0 = (((q1 == q0) ? (int)(Pend - P0) : (P.Wo - 1 - nlo0)) * P.s + WF) * HF;
 
-    // source offset (relative to a channel plane) of strip word tid + 256*j, or -1
-    int soff[JX];
+    // Byte offset (from the channel plane) of strip word tid + 256*j.  Words past
+    // the tile's segments are never used as operands; they reload word 0.
+    uint32_t soffb[JX];
 #pragma unroll
-    for (int j = 0; j < JX; ++j) soff[j] = -1;
+    for (int j = 0; j < JX; ++j) soffb[j] = 0;
     for (uint32_t q = q0; q <= q1; ++q) {
         const int rho = (int)(q - q0);
         const int nlo = rho == 0 ? nlo0 : 0;
@@ -62,27 +67,29 @@ __global__ __launch_bounds__(256) void conv_mfma_fast_kernel(MfmaParams P)
         const int segoff = rho == 0 ? 0 : len0 + (rho - 1) * P.fullseg;
         const uint32_t img = fdiv(q, P.d_ho);
         const int mq = (int)(q - img * (uint32_t)P.Ho);
-        const int srcbase = (int)((img * (uint32_t)P.Ci * (uint32_t)P.Ho + (uint32_t)mq) * (uint32_t)P.rowlen) + nlo * sHf;
+        const uint32_t srcbase = (img * (uint32_t)P.Ci * (uint32_t)P.Ho + (uint32_t)mq) * (uint32_t)P.rowlen + (uint32_t)(nlo * sHf);
 #pragma unroll
         for (int j = 0; j < JX; ++j) {
             const int x = tid + 256 * j - segoff;
-            if (x >= 0 && x < seglen) soff[j] = srcbase + x;
+            if (x >= 0 && x < seglen) soffb[j] = (srcbase + (uint32_t)x) * 4u;
         }
     }
 
     // ---- filter staging coordinates of this thread's float4 chunks ----
-    int goff[JF], loff[JF];
+    // Rows past Co feed accumulators that are never stored; they reload row 0.
+    uint32_t goffb[JF];
+    int loff[JF];
 #pragma unroll
     for (int j = 0; j < JF; ++j) {
         const int f = tid + 256 * j;
         const int row = f / CPR;
         const int e = (f - row * CPR) * 4;
         const bool live = (f < NF4) && (m0 + row < P.Co);
-        goff[j] = live ? row * P.K + e : -1;
+        goffb[j] = live ? (uint32_t)(row * P.K + e) * 4u : 0u;
         loff[j] = (f < NF4) ? row * PF + e : -1;
     }
 
-    // ---- per-lane operand bases ----
+    // ---- per-lane operand bases (stage 0) ----
     int b_base;
     {
         const uint32_t Pl = min(P0 + (uint32_t)(wn * 32 + l32), Pend);
@@ -91,8 +98,9 @@ __global__ __launch_bounds__(256) void conv_mfma_fast_kernel(MfmaParams P)
         const int rho = (int)(ql - q0);
         b_base = rho == 0 ? (nl - nlo0) * sHf : len0 + (rho - 1) * P.fullseg + nl * sHf;
     }
-    const float *ap = sF + (wm * 32 + l32) * PF + h * KHW;
-    const float *bp = sI + b_base + h * S;
+    const lds_float *ap0 = (const lds_float *)lds + (wm * 32 + l32) * PF + h * KHW;
+    const lds_float *bp0 = (const lds_float *)lds + SF_FLOATS + b_base + h * SS;
+    float *wI0 = lds + SF_FLOATS + tid;
 
     floatx16 acc;
 #pragma unroll
@@ -100,32 +108,31 @@ __global__ __launch_bounds__(256) void conv_mfma_fast_kernel(MfmaParams P)
 
     float4 fr[JF];
     float ir[CB * JX];
-    const float *gf = P.flt + (size_t)m0 * P.K;
-    const float *gw = P.win;
+    // Wave-uniform bases (kept in scalar registers) plus per-thread 32-bit byte
+    // offsets that never change: the K loop spends no vector ALU work on addresses.
+    const char *gf = reinterpret_cast<const char *>(P.flt + (size_t)m0 * P.K);
+    const char *gw = reinterpret_cast<const char *>(P.win);
+    const size_t plane_bytes = (size_t)P.chan_stride * 4u;
 
-    // Loads are unconditional (dead lanes read word 0 of a valid plane/row and
-    // the value is replaced by zero), so that all of them are in flight at once.
-    auto gload = [&](int c0) {
-        const float *gfb = gf + (size_t)c0 * KHW;
+    // All loads of a block are issued back to back with no use of their values,
+    // so they stay in flight until the block is written to LDS one iteration later.
+    auto gload = [&](int kb) {
+        const char *gfb = gf + (size_t)kb * (KB * 4);
 #pragma unroll
-        for (int j = 0; j < JF; ++j) {
-            const float4 w = *reinterpret_cast<const float4 *>(gfb + (goff[j] >= 0 ? goff[j] : 0));
-            fr[j] = goff[j] >= 0 ? w : make_float4(0.f, 0.f, 0.f, 0.f);
-        }
+        for (int j = 0; j < JF; ++j) fr[j] = *reinterpret_cast<const float4 *>(gfb + goffb[j]);
+        const char *gwb = gw + (size_t)kb * CB * plane_bytes;
 #pragma unroll
         for (int c = 0; c < CB; ++c) {
-            const float *g = gw + (size_t)(c0 + c) * P.chan_stride;
 #pragma unroll
-            for (int j = 0; j < JX; ++j) {
-                const float w = g[soff[j] >= 0 ? soff[j] : 0];
-                ir[c * JX + j] = soff[j] >= 0 ? w : 0.0f;
-            }
+            for (int j = 0; j < JX; ++j)
+                ir[c * JX + j] = *reinterpret_cast<const float *>(gwb + c * plane_bytes + soffb[j]);
         }
     };
 
-    gload(0);
-    for (int c0 = 0; c0 < P.Ci; c0 += CB) {
-        __syncthreads();   // every wave has finished reading the previous block from LDS
+    // registers -> LDS stage st (st is a compile-time constant at every call site)
+    auto lds_store = [&](int st) {
+        float *sF = lds + st * STAGE;
+        float *sI = wI0 + st * STAGE;
 #pragma unroll
         for (int j = 0; j < JF; ++j) {
             if ((j + 1) * 256 <= NF4 || loff[j] >= 0) {
@@ -134,27 +141,57 @@ __global__ __launch_bounds__(256) void conv_mfma_fast_kernel(MfmaParams P)
             }
         }
 #pragma unroll
-        for (int j = 0; j < JX; ++j) {
-            const int x = tid + 256 * j;
-            if (x < S) {
+        for (int c = 0; c < CB; ++c)
 #pragma unroll
-                for (int c = 0; c < CB; ++c) sI[c * S + x] = ir[c * JX + j];
-            }
-        }
-        __syncthreads();
-        if (c0 + CB < P.Ci) gload(c0 + CB);   // in flight while the matrix cores work
+            for (int j = 0; j < JX; ++j) sI[c * SS + 256 * j] = ir[c * JX + j];
+    };
 
+    float a[2][KHW], b[2][KHW];
+    auto lds_ops = [&](int st, int pr, int slot) {
+        const lds_float *a2 = ap0 + st * STAGE + 2 * pr * KHW;
+        const lds_float *b2 = bp0 + st * STAGE + 2 * pr * SS;
+#pragma unroll
+        for (int v = 0; v < WF; ++v)
+#pragma unroll
+            for (int u = 0; u < HF; ++u) {
+                // volatile: keeps these as single-dword LDS reads with 16-bit immediate
+                // offsets; merged two-address reads would need a VALU add each for
+                // their 8-bit offsets, and VALU work comes out of the MFMA rate.
+                a[slot][v * HF + u] = *(const volatile lds_float *)(a2 + u * WF + v);   // filter (u,v) -> window order
+                b[slot][v * HF + u] = *(const volatile lds_float *)(b2 + v * HF + u);
+            }
+    };
+
+    // One K block: the matrix cores work out of LDS stage st while block kb+1
+    // moves from registers into the other stage and block kb+2 is requested from
+    // global memory.  One barrier per block.
+    const int nkb = P.Ci / CB;
+    auto block = [&](int kb, int st) {
+        lds_ops(st, 0, 0);
 #pragma unroll
         for (int pr = 0; pr < CB / 2; ++pr) {
-            const float *a2 = ap + 2 * pr * KHW;
-            const float *b2 = bp + 2 * pr * S;
+            if (pr + 1 < CB / 2) lds_ops(st, pr + 1, (pr + 1) & 1);
+            if (pr == 0) {
+                if (kb + 1 < nkb) lds_store(st ^ 1);
+                if (kb + 2 < nkb) gload(kb + 2);
+            }
 #pragma unroll
-            for (int v = 0; v < WF; ++v)
-#pragma unroll
-                for (int u = 0; u < HF; ++u)
-                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a2[u * WF + v], b2[v * HF + u], acc, 0, 0, 0);
+            for (int t = 0; t < KHW; ++t)
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[pr & 1][t], b[pr & 1][t], acc, 0, 0, 0);
         }
+        __syncthreads();
+    };
+
+    gload(0);
+    lds_store(0);
+    if (nkb > 1) gload(1);
+    __syncthreads();
+    int kb = 0;
+    for (; kb + 1 < nkb; kb += 2) {   // unrolled by two so that the stage is a constant
+        block(kb, 0);
+        block(kb + 1, 1);
     }
+    if (kb < nkb) block(kb, 0);
 
     store_tile(P, acc, P0, Pend, m0, wm, wn, h, l32);
 }
@@ -164,7 +201,7 @@ static hipError_t launch_fast_t(const MfmaParams &P, uint32_t blocks, hipStream_
 {
     constexpr int KB = CB * HF * WF;
     constexpr int PF = KB | 1;
-    const size_t lds = 4u * ((size_t)round4(MB * PF) + (size_t)CB * P.S);
+    constexpr size_t lds = 2u * 4u * (size_t)(((MB * PF + 3) & ~3) + CB * 256 * JX);
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_mfma_fast_kernel<HF, WF, CB, JX>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
