@@ -28,11 +28,14 @@ if ROOT not in sys.path:
 PEAK_FP32_MATRIX_TFLOPS = 157.3   # MI355X dense fp32 MFMA: 256 CU x 256 flop/clk x 2.4 GHz
 PEAK_HBM_GBS = 8000.0             # MI355X HBM3E
 
-# HBM traffic of one launch of the convolution kernel, from rocprofv3 --pmc runs
-# (FETCH_SIZE and WRITE_SIZE, scaled by a copy kernel of known size); bytes per
-# launch, keyed by layer name.  None until measured; see profiles/.
-MEASURED_CONV_TRAFFIC_BYTES = {}
-MEASURED_TRANSFORM_TRAFFIC_BYTES = {}
+# HBM traffic of one launch of each kernel, bytes, keyed by layer name: measured
+# with two rocprofv3 --pmc runs (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch)
+# of this script and scaled by what the same counters read for a plain 256 MiB
+# device copy (factors 2.000 and 1.000).  The summary with the commands is in
+# profiles/conv_mfma_fast_and_transform_cfg2_3x3_c64_56.md.  Layers that were
+# not measured report null.
+MEASURED_CONV_TRAFFIC_BYTES = {"cfg2_3x3_c64_56": 107000416}
+MEASURED_TRANSFORM_TRAFFIC_BYTES = {"cfg2_3x3_c64_56": 116533520}
 
 
 def parse_args():
@@ -44,6 +47,9 @@ def parse_args():
     ap.add_argument("--layers", choices=["headline", "all"], default="all",
                     help="also time the other layers and list them under 'layers'")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 256 MiB device copy (known traffic) so that a rocprofv3 --pmc "
+                         "run of this command can scale FETCH_SIZE / WRITE_SIZE")
     return ap.parse_args()
 
 
@@ -142,6 +148,14 @@ def main():
     from paper_2306_14316_amd import workloads
     im2win.load_library()
 
+    if a.calibrate_copy:
+        src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")   # 256 MiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     L = workloads.layer(a.layer)
     t = time_layer(L, a.steps, a.warmup)
     rep = layer_report(L, t)
@@ -161,7 +175,7 @@ def main():
         "workspace_bytes": t["workspace_bytes"], "im2col_bytes": t["im2col_bytes"],
         "conv_only_tflops": conv_tflops, "conv_only_tflops_best_of_steps": rep["conv_tflops_best"],
         "transform_gbs": rep["transform_gbs_avg"],
-        "roofline": {"kernel": "conv_mfma_kernel", "bound": "mfma", "achieved": conv_tflops,
+        "roofline": {"kernel": "conv_mfma_fast_kernel" if (L.Hf == 3 and L.Wf == 3 and L.Ci % 8 == 0) else "conv_mfma_kernel", "bound": "mfma", "achieved": conv_tflops,
                      "peak": PEAK_FP32_MATRIX_TFLOPS, "unit": "TFLOP/s",
                      "frac": conv_tflops / PEAK_FP32_MATRIX_TFLOPS, "traffic": traffic,
                      "flops_per_launch": L.flops, "avg_launch_ms": t["conv_ms_avg"]},
