@@ -225,7 +225,9 @@ hipError_t launch_conv_mfma(const float *win, const float *flt, float *out, cons
     const uint32_t tiles_n = (P.npix + NB - 1) / NB;
     const uint32_t blocks = tiles_n * (uint32_t)P.tiles_m;
     {
-        hipError_t fe = launch_conv_mfma_fast(P, sh, blocks, st);
+        hipError_t fe = launch_conv_mfma_shallow(win, flt, out, sh, st);
+        if (fe != hipErrorNotSupported) return fe;
+        fe = launch_conv_mfma_fast(P, sh, blocks, st);
         if (fe != hipErrorNotSupported) return fe;
     }
     switch (sh.khw) {

@@ -36,6 +36,16 @@ EDGE_SHAPES = [
     (1, 4, 6, 70, 8, 1, 9, 1, 0),      # 1x9 filter: 9-element windows from one row
     (1, 4, 70, 6, 8, 9, 1, 1, 0),      # 9x1 filter
     (1, 2, 4, 300, 4, 3, 3, 1, 1),     # one very wide row
+    # three-channel layers with wide rows: the filter-stationary kernel
+    (2, 3, 70, 150, 40, 7, 7, 2, 3),   # 7x7 s2, Co not a multiple of 32
+    (3, 3, 20, 140, 64, 7, 7, 2, 0),
+    (1, 3, 40, 260, 96, 7, 7, 2, 3),   # three 32-row filter blocks per workgroup
+    (1, 3, 9, 400, 8, 7, 7, 2, 3),     # fewer tiles than workgroups
+    (1, 3, 100, 300, 96, 11, 11, 4, 0),  # 11x11 s4: K split between two waves
+    (1, 3, 60, 300, 20, 11, 11, 4, 2),
+    (2, 3, 50, 290, 64, 11, 11, 4, 0),
+    (1, 3, 30, 200, 16, 3, 3, 1, 1),   # 3x3 on three channels
+    (1, 3, 36, 280, 100, 3, 3, 1, 1),  # Co = 100: two filter groups in the grid
 ]
 
 
