@@ -96,73 +96,50 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
     // ---- per-tile geometry ------------------------------------------------------
     // A tile is 64 consecutive output pixels (flattened NCHW order); it touches rows
     // q0..q1 (q = image*Ho + output row), at most SH_RMAX of them.  Row r's strip is
-    // a contiguous run of the im2win tensor and lands at LDS position segoff[r].
-    struct Geo {
-        uint32_t P0, Pend;
-        int t1, t2;          // LDS positions where rows 1 and 2 start (INT_MAX-like if absent)
-        int d0, d1, d2;      // source float offset (relative to base) minus LDS position, per row
-        int filled;          // strip floats used by the tile
-        int nlo0, len0;
-        uint32_t q0;
-        size_t base;         // float offset of row q0's strip start in channel 0
-    };
+    // a contiguous run of the im2win tensor; the strips lie back to back in LDS.
+    // Everything below that depends only on the tile index is wave-uniform and is
+    // computed on the scalar unit.
     const int sHf = P.s * HF;
-    auto geometry = [&](uint32_t tile) {
-        Geo g;
-        g.P0 = tile * NB;
-        g.Pend = min(g.P0 + NB - 1, P.npix - 1);
-        g.q0 = fdiv(g.P0, P.d_wo);
-        const uint32_t q1 = fdiv(g.Pend, P.d_wo);
-        g.nlo0 = (int)(g.P0 - g.q0 * (uint32_t)P.Wo);
-        g.len0 = (((q1 == g.q0) ? (int)(g.Pend - g.P0) : (P.Wo - 1 - g.nlo0)) * P.s + WF) * HF;
-        const uint32_t img0 = fdiv(g.q0, P.d_ho);
-        const int m0r = (int)(g.q0 - img0 * (uint32_t)P.Ho);
-        g.base = ((size_t)img0 * P.img_stride) + (size_t)m0r * P.rowlen + (size_t)(g.nlo0 * sHf);
-        // rows 1 and 2 (if present): source offset relative to base
-        int src[3] = {0, 0, 0};
-        int len[3] = {g.len0, 0, 0};
-#pragma unroll
-        for (int r = 1; r < SH_RMAX; ++r) {
-            const uint32_t q = g.q0 + r;
-            if (q <= q1) {
-                const uint32_t img = fdiv(q, P.d_ho);
-                const int mq = (int)(q - img * (uint32_t)P.Ho);
-                const int nhi = (q == q1) ? (int)(g.Pend - q * (uint32_t)P.Wo) : P.Wo - 1;
-                len[r] = (nhi * P.s + WF) * HF;
-                src[r] = (int)(img - img0) * P.img_stride + (mq - m0r) * P.rowlen - g.nlo0 * sHf;
-            }
-        }
-        g.t1 = g.len0;
-        g.t2 = g.len0 + P.fullseg;
-        g.filled = len[0] + len[1] + len[2];
-        if (len[1] == 0) { g.t1 = 0x3fffffff; g.t2 = 0x3fffffff; }
-        else if (len[2] == 0) { g.t2 = 0x3fffffff; }
-        g.d0 = 0;
-        g.d1 = src[1] - g.len0;
-        g.d2 = src[2] - (g.len0 + P.fullseg);
-        return g;
-    };
-    // byte offset (relative to g.base) of strip word x
-    auto strip_src = [&](const Geo &g, int x) -> uint32_t {
-        const int xc = min(x, g.filled - 1);   // words past the strips are never operands
-        const int d = xc < g.t1 ? g.d0 : (xc < g.t2 ? g.d1 : g.d2);
-        return (uint32_t)(xc + d) * 4u;
-    };
-    // LDS float position of the window of pixel column `col` (0..63) of the tile
-    auto window_pos = [&](const Geo &g, int col) -> int {
-        const uint32_t Pl = min(g.P0 + (uint32_t)col, g.Pend);
-        const uint32_t ql = fdiv(Pl, P.d_wo);
-        const int nl = (int)(Pl - ql * (uint32_t)P.Wo);
-        const int rho = (int)(ql - g.q0);
-        return rho == 0 ? (nl - g.nlo0) * sHf : g.len0 + (rho - 1) * P.fullseg + nl * sHf;
-    };
 
     float ir[CI * JX];
-    auto gload = [&](const Geo &g) {
-        const char *gb = reinterpret_cast<const char *>(P.win + g.base);
+    // Request the strips of `tile` from global memory (values land in ir[]).
+    auto gload = [&](uint32_t tile) {
+        const uint32_t P0 = tile * NB;
+        const uint32_t Pend = min(P0 + NB - 1, P.npix - 1);
+        const uint32_t q0 = fdiv(P0, P.d_wo), q1 = fdiv(Pend, P.d_wo);
+        const int nlo0 = (int)(P0 - q0 * (uint32_t)P.Wo);
+        const int len0 = (((q1 == q0) ? (int)(Pend - P0) : (P.Wo - 1 - nlo0)) * P.s + WF) * HF;
+        const uint32_t img0 = fdiv(q0, P.d_ho);
+        const int m0r = (int)(q0 - img0 * (uint32_t)P.Ho);
+        const size_t base = ((size_t)img0 * P.img_stride) + (size_t)m0r * P.rowlen + (size_t)(nlo0 * sHf);
+        // rows 1 and 2: LDS position where they start (t1, t2), their length, and
+        // (source float offset relative to base) - (LDS position) = d1, d2
+        int t1 = 0x3fffffff, t2 = 0x3fffffff, d1 = 0, d2 = 0, filled = len0;
+        if (q0 + 1 <= q1) {
+            const uint32_t q = q0 + 1;
+            const uint32_t img = fdiv(q, P.d_ho);
+            const int mq = (int)(q - img * (uint32_t)P.Ho);
+            const int nhi = (q == q1) ? (int)(Pend - q * (uint32_t)P.Wo) : P.Wo - 1;
+            t1 = len0;
+            d1 = (int)(img - img0) * P.img_stride + (mq - m0r) * P.rowlen - nlo0 * sHf - len0;
+            filled += (nhi * P.s + WF) * HF;
+        }
+        if (q0 + 2 <= q1) {
+            const uint32_t q = q0 + 2;
+            const uint32_t img = fdiv(q, P.d_ho);
+            const int mq = (int)(q - img * (uint32_t)P.Ho);
+            const int nhi = (q == q1) ? (int)(Pend - q * (uint32_t)P.Wo) : P.Wo - 1;
+            t2 = len0 + P.fullseg;
+            d2 = (int)(img - img0) * P.img_stride + (mq - m0r) * P.rowlen - nlo0 * sHf - t2;
+            filled += (nhi * P.s + WF) * HF;
+        }
+        const char *gb = reinterpret_cast<const char *>(P.win + base);
 #pragma unroll
         for (int j = 0; j < JX; ++j) {
-            const uint32_t off = strip_src(g, tid + NT * j);
+            const int xc = min(tid + NT * j, filled - 1);   // words past the strips are never operands
+            int d = xc < t1 ? 0 : d1;
+            d = xc < t2 ? d : d2;
+            const uint32_t off = (uint32_t)(xc + d) * 4u;
 #pragma unroll
             for (int c = 0; c < CI; ++c)
                 ir[c * JX + j] = *reinterpret_cast<const float *>(gb + (size_t)c * P.chan_stride * 4u + off);
@@ -180,8 +157,7 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
 
     const uint32_t stride_tiles = gridDim.x;
     uint32_t tile = blockIdx.x;
-    Geo cur = geometry(tile);
-    gload(cur);
+    gload(tile);
     lds_store(0);
     __syncthreads();
 
@@ -189,14 +165,24 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
         const int st = it & 1;
         const uint32_t next = tile + stride_tiles;
         const bool has_next = next < P.ntiles;
-        Geo nxt = cur;
-        if (has_next) {
-            nxt = geometry(next);
-            gload(nxt);   // in flight during this tile's matrix work
+        if (has_next) gload(next);   // in flight during this tile's matrix work
+
+        // ---- this tile: where the lane's window starts in the LDS strips -----------
+        const uint32_t P0 = tile * NB;
+        const uint32_t Pend = min(P0 + NB - 1, P.npix - 1);
+        int wpos;
+        {
+            const uint32_t q0 = fdiv(P0, P.d_wo), q1 = fdiv(Pend, P.d_wo);
+            const int nlo0 = (int)(P0 - q0 * (uint32_t)P.Wo);
+            const int len0 = (((q1 == q0) ? (int)(Pend - P0) : (P.Wo - 1 - nlo0)) * P.s + WF) * HF;
+            const uint32_t Pl = min(P0 + (uint32_t)(wn * 32 + l32), Pend);
+            const uint32_t ql = fdiv(Pl, P.d_wo);
+            const int nl = (int)(Pl - ql * (uint32_t)P.Wo);
+            const int rho = (int)(ql - q0);
+            wpos = rho == 0 ? (nl - nlo0) * sHf : len0 + (rho - 1) * P.fullseg + nl * sHf;
         }
 
         // ---- K loop: TW MFMA steps, B operands fetched SH_G steps ahead -----------
-        const int wpos = window_pos(cur, wn * 32 + l32);
         const lds_f32 *sbase = lds + st * STAGE;
         const lds_f32 *bpair = sbase + wpos + h * SS;
         const lds_f32 *bsplit = sbase + wpos + (CI - 1) * SS + h * KH2;
@@ -264,8 +250,8 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
 
         // ---- epilogue ---------------------------------------------------------------
         {
-            const uint32_t Pm = cur.P0 + (uint32_t)(wn * 32 + l32);
-            if (Pm <= cur.Pend) {
+            const uint32_t Pm = P0 + (uint32_t)(wn * 32 + l32);
+            if (Pm <= Pend) {
                 const uint32_t img = fdiv(Pm, P.d_howo);
                 const uint32_t pin = Pm - img * P.howo;
                 float *o = P.out + (size_t)img * P.Co * P.howo + pin;
@@ -280,7 +266,6 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
         }
 
         if (has_next) lds_store(st ^ 1);
-        cur = nxt;
         __syncthreads();
     }
 }
