@@ -200,15 +200,20 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
                 if (t == KH2 - 1) return *(const volatile lds_f32 *)bzero;
                 return *(const volatile lds_f32 *)(bsplit + t);
             };
+            // The scheduling barriers pin the order "reads of group g+1, then MFMAs of
+            // group g": left alone the compiler sinks every LDS read to just before its
+            // MFMA and the matrix pipe waits out one LDS latency per step.
             float b[2][SH_G];
 #pragma unroll
             for (int e = 0; e < SH_G; ++e)
                 if (e < TW) b[0][e] = bread(e);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int g = 0; g < NG; ++g) {
 #pragma unroll
                 for (int e = 0; e < SH_G; ++e)
                     if ((g + 1) * SH_G + e < TW) b[(g + 1) & 1][e] = bread((g + 1) * SH_G + e);
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int e = 0; e < SH_G; ++e) {
                     const int ii = g * SH_G + e;
@@ -223,6 +228,7 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
                         }
                     }
                 }
+                __builtin_amdgcn_sched_barrier(0);
             }
         };
         if (KS == 1) {
