@@ -14,6 +14,8 @@
 //     (u,v) -> window-order permutation is a compile-time offset on the read.
 #include "conv_mfma_tile.h"
 
+#include <type_traits>
+
 namespace im2win {
 
 typedef __attribute__((address_space(3))) float lds_float;   // a float in LDS
@@ -76,18 +78,37 @@ __global__ __launch_bounds__(256) void conv_mfma_fast_kernel(MfmaParams P)
     }
 
     // ---- filter staging coordinates of this thread's float4 chunks ----
+    // The tile is MB rows x CPR chunks of 4 floats.  Chunk columns are dealt out
+    // so that each dword LDS write of a half-wave is conflict-free with the odd
+    // row pitch: columns in groups of 8 (a half-wave = 4 consecutive rows x 8
+    // chunks: 128 contiguous bytes per row in global memory), the CPR % 8
+    // leftover columns one column x 32 rows per half-wave.
     // Rows past Co feed accumulators that are never stored; they reload row 0.
+    constexpr int CG = CPR / 8;              // full groups of 8 chunk columns
+    constexpr int NMAIN = MB * CG * 8;       // chunks in full groups
     uint32_t goffb[JF];
     int loff[JF];
 #pragma unroll
     for (int j = 0; j < JF; ++j) {
         const int f = tid + 256 * j;
-        const int row = f / CPR;
-        const int e = (f - row * CPR) * 4;
+        int row, c4;
+        if (f < NMAIN) {
+            const int g = f >> 5, w = f & 31;
+            row = 4 * (g / CG) + (w >> 3);
+            c4 = 8 * (g % CG) + (w & 7);
+        } else {
+            const int r = f - NMAIN;
+            row = r % MB;
+            c4 = CG * 8 + r / MB;
+        }
+        const int e = c4 * 4;
         const bool live = (f < NF4) && (m0 + row < P.Co);
         goffb[j] = live ? (uint32_t)(row * P.K + e) * 4u : 0u;
-        loff[j] = (f < NF4) ? row * PF + e : -1;
+        loff[j] = row * PF + e;
     }
+    // A thread with no chunk in the last round repeats its first chunk (same data to
+    // the same place), which keeps the staging code free of branches.
+    if (tid + 256 * (JF - 1) >= NF4) { goffb[JF - 1] = goffb[0]; loff[JF - 1] = loff[0]; }
 
     // ---- per-lane operand bases (stage 0) ----
     int b_base;
@@ -106,92 +127,135 @@ __global__ __launch_bounds__(256) void conv_mfma_fast_kernel(MfmaParams P)
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
 
+    // Prefetch registers: one set for the filter chunks (they come from L2), two
+    // alternating sets for the strip words (they come from HBM and are given about
+    // one and a half K blocks to arrive).
     float4 fr[JF];
-    float ir[CB * JX];
+    float ir[2][CB * JX];
     // Wave-uniform bases (kept in scalar registers) plus per-thread 32-bit byte
     // offsets that never change: the K loop spends no vector ALU work on addresses.
     const char *gf = reinterpret_cast<const char *>(P.flt + (size_t)m0 * P.K);
     const char *gw = reinterpret_cast<const char *>(P.win);
     const size_t plane_bytes = (size_t)P.chan_stride * 4u;
 
-    // All loads of a block are issued back to back with no use of their values,
-    // so they stay in flight until the block is written to LDS one iteration later.
-    auto gload = [&](int kb) {
-        const char *gfb = gf + (size_t)kb * (KB * 4);
-#pragma unroll
-        for (int j = 0; j < JF; ++j) fr[j] = *reinterpret_cast<const float4 *>(gfb + goffb[j]);
-        const char *gwb = gw + (size_t)kb * CB * plane_bytes;
-#pragma unroll
-        for (int c = 0; c < CB; ++c) {
-#pragma unroll
-            for (int j = 0; j < JX; ++j)
-                ir[c * JX + j] = *reinterpret_cast<const float *>(gwb + c * plane_bytes + soffb[j]);
-        }
+    auto load_f = [&](int kb, int j) {
+        fr[j] = *reinterpret_cast<const float4 *>(gf + (size_t)kb * (KB * 4) + goffb[j]);
     };
-
-    // registers -> LDS stage st (st is a compile-time constant at every call site)
-    auto lds_store = [&](int st) {
-        float *sF = lds + st * STAGE;
-        float *sI = wI0 + st * STAGE;
-#pragma unroll
-        for (int j = 0; j < JF; ++j) {
-            if ((j + 1) * 256 <= NF4 || loff[j] >= 0) {
-                float *d = sF + loff[j];
-                d[0] = fr[j].x; d[1] = fr[j].y; d[2] = fr[j].z; d[3] = fr[j].w;
-            }
-        }
-#pragma unroll
-        for (int c = 0; c < CB; ++c)
-#pragma unroll
-            for (int j = 0; j < JX; ++j) sI[c * SS + 256 * j] = ir[c * JX + j];
+    auto load_i = [&](int kb, int set, int c, int j) {
+        ir[set][c * JX + j] = *reinterpret_cast<const float *>(gw + ((size_t)kb * CB + c) * plane_bytes + soffb[j]);
+    };
+    auto store_f = [&](int st, int j, int half) {   // half 0: words 0,1 of the chunk; half 1: words 2,3
+        lds_float *d = (lds_float *)lds + st * STAGE + loff[j] + 2 * half;
+        d[0] = half ? fr[j].z : fr[j].x;
+        d[1] = half ? fr[j].w : fr[j].y;
+    };
+    auto store_i = [&](int st, int set, int c, int j) {
+        ((lds_float *)wI0)[st * STAGE + c * SS + 256 * j] = ir[set][c * JX + j];
     };
 
     float a[2][KHW], b[2][KHW];
-    auto lds_ops = [&](int st, int pr, int slot) {
-        const lds_float *a2 = ap0 + st * STAGE + 2 * pr * KHW;
-        const lds_float *b2 = bp0 + st * STAGE + 2 * pr * SS;
-#pragma unroll
-        for (int v = 0; v < WF; ++v)
-#pragma unroll
-            for (int u = 0; u < HF; ++u) {
-                // volatile: keeps these as single-dword LDS reads with 16-bit immediate
-                // offsets; merged two-address reads would need a VALU add each for
-                // their 8-bit offsets, and VALU work comes out of the MFMA rate.
-                a[slot][v * HF + u] = *(const volatile lds_float *)(a2 + u * WF + v);   // filter (u,v) -> window order
-                b[slot][v * HF + u] = *(const volatile lds_float *)(b2 + v * HF + u);
-            }
+    // operand pair t of channel pair pr, from LDS stage st, into register slot `slot`
+    auto lds_op = [&](int st, int pr, int slot, int t) {
+        const int u = t % HF, v = t / HF;   // window order: v outer, u inner; the filter is stored (u,v)
+        // volatile: keeps these as single-dword LDS reads with 16-bit immediate
+        // offsets; merged two-address reads would need a VALU add each for
+        // their 8-bit offsets, and VALU work comes out of the MFMA rate.
+        a[slot][t] = *(const volatile lds_float *)(ap0 + st * STAGE + 2 * pr * KHW + u * WF + v);
+        b[slot][t] = *(const volatile lds_float *)(bp0 + st * STAGE + 2 * pr * SS + t);
     };
 
-    // One K block: the matrix cores work out of LDS stage st while block kb+1
-    // moves from registers into the other stage and block kb+2 is requested from
-    // global memory.  One barrier per block.
+    // ---- one K block --------------------------------------------------------------
+    // The wave issues its MFMAs as one dependent chain, so everything else is
+    // placed, in program order, in the shadow of an MFMA: after MFMA i come the two
+    // operand reads for the same step of the next channel pair and one or two
+    // staging instructions.  Block kb computes out of LDS stage ST, writes block
+    // kb+1 (held in registers) to the other stage and requests block kb+2 from
+    // global memory.  The barrier sits before the last channel pair: its operands
+    // are already in registers, so after the barrier the other stage can be read
+    // (first operands of block kb+1) and, in the next block, this stage can be
+    // overwritten.  Scheduling barriers pin this order.
+    constexpr int NG = CB / 2;            // channel pairs per block
+    constexpr int NM = NG * KHW;          // MFMAs per block
+    constexpr int NSLOT = (NG - 1) * KHW; // MFMAs before the barrier
+    constexpr int NFW = 2 * JF;           // filter half-chunk stores
+    constexpr int NIW = CB * JX;          // strip stores / loads
+    static_assert(NG % 2 == 0, "operand slots alternate per channel pair");
+    constexpr int NIWS = (NIW + 1) / 2;                       // slots that store strip words (two each)
+    constexpr int LPS = (NIW + (NSLOT - NFW - NIWS) - 1) / (NSLOT - NFW - NIWS);   // strip loads per slot
+    constexpr int NILS = (NIW + LPS - 1) / LPS;               // slots that load strip words
+    static_assert(NSLOT - NFW - NIWS > 0 && NFW + NIWS + NILS <= NSLOT, "staging work must fit before the barrier");
     const int nkb = P.Ci / CB;
-    auto block = [&](int kb, int st) {
-        lds_ops(st, 0, 0);
+    auto block = [&](int kb, auto stc, auto has1c, auto has2c) {
+        constexpr int ST = decltype(stc)::value;
+        constexpr bool HAS1 = decltype(has1c)::value, HAS2 = decltype(has2c)::value;
 #pragma unroll
-        for (int pr = 0; pr < CB / 2; ++pr) {
-            if (pr + 1 < CB / 2) lds_ops(st, pr + 1, (pr + 1) & 1);
-            if (pr == 0) {
-                if (kb + 1 < nkb) lds_store(st ^ 1);
-                if (kb + 2 < nkb) gload(kb + 2);
+        for (int i = 0; i < NM; ++i) {
+            const int g = i / KHW, t = i % KHW;
+            if (HAS1 && i == NSLOT) __syncthreads();
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[g & 1][t], b[g & 1][t], acc, 0, 0, 0);
+            if (g + 1 < NG) lds_op(ST, g + 1, (g + 1) & 1, t);
+            else if (HAS1) lds_op(ST ^ 1, 0, 0, t);
+            if (i < NFW) {                       // filter chunk i/2: store a half, then reload it
+                if (HAS1) store_f(ST ^ 1, i / 2, i & 1);
+                if (HAS2 && (i & 1)) load_f(kb + 2, i / 2);
+            } else if (i < NFW + NIWS) {   // strip words of block kb+1: two stores per slot
+                if (HAS1) {
+                    const int w = 2 * (i - NFW);
+                    store_i(ST ^ 1, ST ^ 1, w / JX, w % JX);
+                    if (w + 1 < NIW) store_i(ST ^ 1, ST ^ 1, (w + 1) / JX, (w + 1) % JX);
+                }
+            } else if (i < NFW + NIWS + NILS) {   // strip words of block kb+2: LPS loads per slot
+                if (HAS2) {
+#pragma unroll
+                    for (int q = 0; q < LPS; ++q) {
+                        const int w = (i - NFW - NIWS) * LPS + q;
+                        if (w < NIW) load_i(kb + 2, ST, w / JX, w % JX);
+                    }
+                }
             }
-#pragma unroll
-            for (int t = 0; t < KHW; ++t)
-                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[pr & 1][t], b[pr & 1][t], acc, 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
-        __syncthreads();
     };
+    using I0 = std::integral_constant<int, 0>;
+    using I1 = std::integral_constant<int, 1>;
+    using T = std::true_type;
+    using F = std::false_type;
 
-    gload(0);
-    lds_store(0);
-    if (nkb > 1) gload(1);
-    __syncthreads();
-    int kb = 0;
-    for (; kb + 1 < nkb; kb += 2) {   // unrolled by two so that the stage is a constant
-        block(kb, 0);
-        block(kb + 1, 1);
+    // ---- prologue: block 0 into stage 0, block 1 into the registers ----
+#pragma unroll
+    for (int j = 0; j < JF; ++j) load_f(0, j);
+#pragma unroll
+    for (int w = 0; w < NIW; ++w) load_i(0, 0, w / JX, w % JX);
+#pragma unroll
+    for (int j = 0; j < JF; ++j) { store_f(0, j, 0); store_f(0, j, 1); }
+#pragma unroll
+    for (int w = 0; w < NIW; ++w) store_i(0, 0, w / JX, w % JX);
+    if (nkb > 1) {
+#pragma unroll
+        for (int j = 0; j < JF; ++j) load_f(1, j);
+#pragma unroll
+        for (int w = 0; w < NIW; ++w) load_i(1, 1, w / JX, w % JX);
     }
-    if (kb < nkb) block(kb, 0);
+    __syncthreads();
+#pragma unroll
+    for (int t = 0; t < KHW; ++t) lds_op(0, 0, 0, t);
+
+    int kb = 0;
+    for (; kb + 3 < nkb; kb += 2) {   // unrolled by two so that the stage is a constant
+        block(kb, I0{}, T{}, T{});
+        block(kb + 1, I1{}, T{}, T{});
+    }
+    const int rem = nkb - kb;   // 1, 2 or 3 blocks left
+    if (rem == 3) {
+        block(kb, I0{}, T{}, T{});
+        block(kb + 1, I1{}, T{}, F{});
+        block(kb + 2, I0{}, F{}, F{});
+    } else if (rem == 2) {
+        block(kb, I0{}, T{}, F{});
+        block(kb + 1, I1{}, F{}, F{});
+    } else {
+        block(kb, I0{}, F{}, F{});
+    }
 
     store_tile(P, acc, P0, Pend, m0, wm, wn, h, l32);
 }
