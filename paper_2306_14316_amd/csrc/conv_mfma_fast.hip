@@ -21,7 +21,7 @@ namespace im2win {
 typedef __attribute__((address_space(3))) float lds_float;   // a float in LDS
 
 template <int HF, int WF, int CB, int JX>
-__global__ __launch_bounds__(256) void conv_mfma_fast_kernel(MfmaParams P)
+__global__ __launch_bounds__(256, 3) void conv_mfma_fast_kernel(MfmaParams P)
 {
     constexpr int KHW = HF * WF;
     constexpr int KB = CB * KHW;            // K elements per block
