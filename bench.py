@@ -46,6 +46,8 @@ def parse_args():
     ap.add_argument("--layer", type=int, default=2, help="headline layer, 1..5 (default 2)")
     ap.add_argument("--layers", choices=["headline", "all"], default="all",
                     help="also time the other layers and list them under 'layers'")
+    ap.add_argument("--table2", action="store_true",
+                    help="also time the twelve layers of the paper's Table 2 at batch 128 (listed under 'table2')")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (known traffic) so that a rocprofv3 --pmc "
@@ -196,6 +198,8 @@ def main():
                 k = max(10, min(a.steps, 30))
                 reps.append(layer_report(other, time_layer(other, k, min(a.warmup, 5))))
         out["layers"] = reps
+    if a.table2:
+        out["table2"] = [layer_report(t2, time_layer(t2, max(5, min(a.steps, 20)), 3)) for t2 in workloads.TABLE2]
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(L)
     print(json.dumps(out))

@@ -280,6 +280,8 @@ hipError_t launch_conv_mfma_fast(MfmaParams P, const Shape &sh, uint32_t blocks,
 {
     const bool aligned = (reinterpret_cast<uintptr_t>(P.flt) & 15u) == 0 && (sh.K % 4 == 0);
     if (!aligned) return hipErrorNotSupported;
+    // strip words are addressed with 32-bit byte offsets from the start of the im2win tensor
+    if ((unsigned long long)sh.N * sh.Ci * sh.Ho * (unsigned long long)sh.rowlen * 4ull >= (1ull << 32)) return hipErrorNotSupported;
     if (sh.Hf == 3 && sh.Wf == 3 && sh.Ci % 8 == 0) {
         if (P.S <= 256) return launch_fast_t<3, 3, 8, 1>(P, blocks, st);
         if (P.S <= 512) return launch_fast_t<3, 3, 8, 2>(P, blocks, st);

@@ -65,11 +65,27 @@ LAYERS = (
 )
 
 
+# The twelve benchmark layers of the paper's Table 2 (unpadded, batch 128 as in Section 4.2).
+# The paper does not say what values its tensors hold: N(0,1) inputs and He-normal filters here.
+def _t2(name, Ci, Hi, Co, Hf, s, seed):
+    return Layer("table2_" + name, 128, Ci, Hi, Hi, Co, Hf, Hf, s, 0, seed, "normal", "he_normal")
+
+
+TABLE2 = (
+    _t2("conv1", 3, 227, 96, 11, 4, 2001), _t2("conv2", 3, 231, 96, 11, 4, 2002),
+    _t2("conv3", 3, 227, 64, 7, 2, 2003), _t2("conv4", 64, 224, 64, 7, 2, 2004),
+    _t2("conv5", 96, 24, 256, 5, 1, 2005), _t2("conv6", 256, 12, 512, 3, 1, 2006),
+    _t2("conv7", 3, 224, 64, 3, 1, 2007), _t2("conv8", 64, 112, 128, 3, 1, 2008),
+    _t2("conv9", 64, 56, 64, 3, 1, 2009), _t2("conv10", 128, 28, 128, 3, 1, 2010),
+    _t2("conv11", 256, 14, 256, 3, 1, 2011), _t2("conv12", 512, 7, 512, 3, 1, 2012),
+)
+
+
 def layer(index_or_name) -> Layer:
     """Layer by 1-based index (1..5) or by name."""
     if isinstance(index_or_name, int):
         return LAYERS[index_or_name - 1]
-    for l in LAYERS:
+    for l in LAYERS + TABLE2:
         if l.name == index_or_name:
             return l
     raise KeyError(index_or_name)

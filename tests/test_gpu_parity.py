@@ -68,6 +68,44 @@ def test_benchmark_layers_full_size(idx):
     print("layer %s: max|err|/sum|x||w| = %.3e, rel L2 = %.3e" % (L.name, elem, l2), flush=True)
 
 
+@pytest.mark.parametrize("L", workloads.TABLE2, ids=lambda l: l.name)
+def test_table2_layers_small_batch(L):
+    """The twelve layers of the paper's Table 2 (unpadded), at batch 3, every element."""
+    Ls = workloads.with_batch(L, 3)
+    print("layer", Ls.name, flush=True)
+    I, F = workloads.make_inputs(Ls)
+    check_layer(I, F, Ls.stride, Ls.pad, basic=False, twice=False)
+
+
+def test_im2win_tensor_larger_than_4_gib():
+    """A 5 GB im2win tensor (byte offsets pass 2^32): images at both ends and in the
+    middle are checked in full, plus sampled outputs anywhere."""
+    N, Ci, Hi, Wi, Co, Hf, Wf, s, p = 512, 64, 112, 112, 16, 3, 3, 1, 1
+    g = torch.Generator(device="cpu")
+    g.manual_seed(4242)
+    I = torch.rand((N, Ci, Hi, Wi), generator=g, dtype=torch.float32)
+    F = torch.randn((Co, Ci, Hf, Wf), generator=g, dtype=torch.float32) * 0.06
+    Ho, Wo = im2win.im2win_out_shape(Hi, Wi, Hf, Wf, s, p)
+    assert im2win.im2win_workspace_bytes(N, Ci, Hi, Wi, Hf, Wf, s, p) > 2 ** 32
+    print("large tensor: transform", flush=True)
+    dW = run_transform(I, Hf, Wf, s, p)
+    print("large tensor: convolution", flush=True)
+    dO = run_conv(dW, F, N, Ci, Hi, Wi, s, p)
+    for i in (0, 255, 511):
+        Ii = I[i:i + 1].numpy()
+        assert_bitwise_equal(dW[i:i + 1], oracle.im2win(Ii, Hf, Wf, s, p))
+        O_ref, B_ref = oracle.conv2d_direct(Ii, F.numpy(), s, p)
+        assert_conv_close(dO[i:i + 1].cpu().numpy(), O_ref, B_ref)
+    rng = np.random.default_rng(7)
+    idx = np.stack([rng.integers(0, N, 20000), rng.integers(0, Co, 20000),
+                    rng.integers(0, Ho, 20000), rng.integers(0, Wo, 20000)], axis=1).astype(np.int32)
+    O_s, B_s = oracle.conv2d_direct_at(I.numpy(), F.numpy(), s, p, idx)
+    got = dO.cpu().numpy()[idx[:, 0], idx[:, 1], idx[:, 2], idx[:, 3]].astype(np.float64)
+    assert np.isfinite(got).all()
+    assert (np.abs(got - O_s) <= 1e-4 * B_s).all()
+    assert not bool(torch.isnan(dO).any())
+
+
 @pytest.mark.parametrize("idx", [1, 2])
 def test_basic_kernel_on_benchmark_layers(idx):
     L = workloads.layer(idx)
