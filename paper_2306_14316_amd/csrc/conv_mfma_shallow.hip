@@ -255,18 +255,22 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
         }
 
         // ---- epilogue ---------------------------------------------------------------
+        // Lane (h, l32) holds pixel l32 of the wave's 32 and, in register v, output
+        // channel jl + 8*(v/4) + v%4 with jl = block base + 4*h.  The per-lane part of
+        // the address is formed once; the per-register part is wave-uniform.
         {
             const uint32_t Pm = P0 + (uint32_t)(wn * 32 + l32);
             if (Pm <= Pend) {
                 const uint32_t img = fdiv(Pm, P.d_howo);
                 const uint32_t pin = Pm - img * P.howo;
-                float *o = P.out + (size_t)img * P.Co * P.howo + pin;
-                const int jbase = (int)blockIdx.y * (WM * 32) + wm * 32 + 4 * h;
+                const int jl = (int)blockIdx.y * (WM * 32) + wm * 32 + 4 * h;
+                float *o = P.out + ((size_t)img * P.Co + jl) * P.howo + pin;
+                const int room = P.Co - jl;   // channels jl .. Co-1 exist
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     if (KS == 2 && ((v >> 3) != ks)) continue;   // the partner stores that half
-                    const int j = jbase + 8 * (v >> 2) + (v & 3);
-                    if (j < P.Co) o[(size_t)j * P.howo] = acc[v];
+                    const int dj = 8 * (v >> 2) + (v & 3);
+                    if (dj < room) o[(size_t)dj * P.howo] = acc[v];
                 }
             }
         }
