@@ -155,16 +155,20 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
 
     if (tid < 8) { lds[CI * SS + (tid & 3) + (tid >> 2) * STAGE] = 0.0f; }   // zero slots of both stages
 
-    const uint32_t stride_tiles = gridDim.x;
-    uint32_t tile = blockIdx.x;
+    // Each workgroup walks a contiguous range of tiles: neighbouring tiles share
+    // strip words (L2 hits) and write to the same pages of the output.
+    const uint32_t per = (P.ntiles + gridDim.x - 1) / gridDim.x;
+    uint32_t tile = blockIdx.x * per;
+    const uint32_t tile_end = min(tile + per, P.ntiles);
+    if (tile >= tile_end) return;   // whole workgroup: no barrier is skipped by part of it
     gload(tile);
     lds_store(0);
     __syncthreads();
 
-    for (int it = 0; tile < P.ntiles; ++it, tile += stride_tiles) {
+    for (int it = 0; tile < tile_end; ++it, ++tile) {
         const int st = it & 1;
-        const uint32_t next = tile + stride_tiles;
-        const bool has_next = next < P.ntiles;
+        const uint32_t next = tile + 1;
+        const bool has_next = next < tile_end;
         if (has_next) gload(next);   // in flight during this tile's matrix work
 
         // ---- this tile: where the lane's window starts in the LDS strips -----------
