@@ -19,13 +19,26 @@
 #include "conv_mfma_tile.h"
 
 #include <type_traits>
+#include <utility>
 
 namespace im2win {
 
 typedef __attribute__((address_space(3))) float lds_f32;
 
+template <class F, int... Is>
+__device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, Is...>)
+{
+    (f(std::integral_constant<int, Is>{}), ...);
+}
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>), in order
+template <int N, class F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
 constexpr int SH_RMAX = 3;   // a 64-pixel tile may touch at most this many output rows
-constexpr int SH_G = 8;      // B operands are fetched from LDS this many steps ahead
+constexpr int SH_G_MAX = 8;  // B operands are fetched from LDS up to this many steps ahead
 
 struct ShallowParams {
     const float *win;
@@ -58,7 +71,7 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
     constexpr int NT = 64 * WM * 2 * KS;       // threads per workgroup
     constexpr int SS = JX * NT;                // LDS floats per channel strip
     constexpr int STAGE = CI * SS + 4;         // one LDS stage: CI strips + a zero slot
-    constexpr int NG = (TW + SH_G - 1) / SH_G;
+    constexpr int SH_G = (KS == 2) ? 4 : SH_G_MAX;   // shorter ring where registers are scarce
     static_assert(T % KS == 0, "K steps must split evenly between the waves of a block");
 
     extern __shared__ __align__(16) unsigned char smem[];
@@ -93,195 +106,216 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
         }
     }
 
-    // ---- per-tile geometry ------------------------------------------------------
+    // ---- tile pipeline ------------------------------------------------------------
     // A tile is 64 consecutive output pixels (flattened NCHW order); it touches rows
     // q0..q1 (q = image*Ho + output row), at most SH_RMAX of them.  Row r's strip is
     // a contiguous run of the im2win tensor; the strips lie back to back in LDS.
-    // Everything below that depends only on the tile index is wave-uniform and is
-    // computed on the scalar unit.
+    //
+    // A wave issues its MFMAs as one dependent chain and issues in order, so work
+    // placed between two MFMAs of the chain is free while work placed outside the
+    // chain leaves the matrix pipe idle.  Everything a tile needs besides its MFMAs
+    // is therefore cut into small pieces that ride inside the chain of the tile
+    // before or after it:
+    //   chain of tile T carries   - geometry, offsets and global loads of tile T+1,
+    //                             - window position / output pointer of tile T+1,
+    //                             - the output stores of tile T-1 (with KS == 2 each one
+    //                               first adds the partner wave's partial sum from LDS),
+    //                             - the LDS writes of tile T+1's strips (late, so the
+    //                               loads have had most of the chain to arrive).
+    // Accumulators alternate between two register sets with the tile parity.
     const int sHf = P.s * HF;
+    constexpr int NIW = CI * JX;                 // strip words per thread and tile
+    constexpr int NL = (NIW + 1) / 2;            // pieces that load / store two words each
+    constexpr int NE = (KS == 2) ? 8 : 16;       // output-store pieces
+    constexpr int P_GEO = 0, P_OFF = 4, P_LD = P_OFF + JX, P_WPOS = P_LD + NL, P_OPTR = P_WPOS + 1,
+                  P_ST = P_OPTR + 1, P_LDS = P_ST + NE, NP = P_LDS + NL;
 
-    float ir[CI * JX];
-    // Request the strips of `tile` from global memory (values land in ir[]).
-    auto gload = [&](uint32_t tile) {
-        const uint32_t P0 = tile * NB;
-        const uint32_t Pend = min(P0 + NB - 1, P.npix - 1);
-        const uint32_t q0 = fdiv(P0, P.d_wo), q1 = fdiv(Pend, P.d_wo);
-        const int nlo0 = (int)(P0 - q0 * (uint32_t)P.Wo);
-        const int len0 = (((q1 == q0) ? (int)(Pend - P0) : (P.Wo - 1 - nlo0)) * P.s + WF) * HF;
-        const uint32_t img0 = fdiv(q0, P.d_ho);
-        const int m0r = (int)(q0 - img0 * (uint32_t)P.Ho);
-        const size_t base = ((size_t)img0 * P.img_stride) + (size_t)m0r * P.rowlen + (size_t)(nlo0 * sHf);
-        // rows 1 and 2: LDS position where they start (t1, t2), their length, and
-        // (source float offset relative to base) - (LDS position) = d1, d2
-        int t1 = 0x3fffffff, t2 = 0x3fffffff, d1 = 0, d2 = 0, filled = len0;
-        if (q0 + 1 <= q1) {
-            const uint32_t q = q0 + 1;
+    // state of the tile being fetched ("n": next) -- wave-uniform unless noted
+    uint32_t nP0 = 0, nPend = 0, nq0 = 0, nq1 = 0, nimg0 = 0;
+    int nnlo0 = 0, nlen0 = 0, nm0r = 0, nt1 = 0, nt2 = 0, nd1 = 0, nd2 = 0, nfilled = 1;
+    size_t nbase = 0;
+    uint32_t noff[JX];      // per thread: byte offset of its strip words from nbase
+    float ir[NIW];          // per thread: the strip words in flight
+    int nwpos = 0;          // per lane: LDS position of its window
+    float *no = P.out;      // per lane: output address of (pixel, first channel of the lane)
+    int nroom = 0;          // per lane: number of channels it may store (<= 0: none)
+    // state of the tile being computed ("c") and of the one before it ("p")
+    int cwpos = 0, croom = 0, proom = 0;
+    float *co = P.out, *po = P.out;
+    floatx16 acc[2];
+    float own[8];           // (KS == 2) this wave's partial sums of that half, kept from the previous tile
+
+    const uint32_t per = (P.ntiles + gridDim.x - 1) / gridDim.x;
+    const uint32_t tile0 = blockIdx.x * per;
+    const uint32_t tile_end = min(tile0 + per, P.ntiles);
+    if (tile0 >= tile_end) return;   // whole workgroup: no barrier is skipped by part of it
+    const int jl = (int)blockIdx.y * (WM * 32) + wm * 32 + 4 * h;   // first channel of this lane
+
+    // One piece of the work for tile `t` (pieces are numbered in dependency order).
+    auto piece = [&](auto pc, uint32_t t, int st_next, const floatx16 &pacc, int xpar) {
+        constexpr int p = decltype(pc)::value;
+        if constexpr (p == P_GEO) {
+            nP0 = t * NB;
+            nPend = min(nP0 + NB - 1, P.npix - 1);
+            nq0 = fdiv(nP0, P.d_wo);
+            nq1 = fdiv(nPend, P.d_wo);
+            nnlo0 = (int)(nP0 - nq0 * (uint32_t)P.Wo);
+            nlen0 = (((nq1 == nq0) ? (int)(nPend - nP0) : (P.Wo - 1 - nnlo0)) * P.s + WF) * HF;
+        } else if constexpr (p == P_GEO + 1) {
+            nimg0 = fdiv(nq0, P.d_ho);
+            nm0r = (int)(nq0 - nimg0 * (uint32_t)P.Ho);
+            nbase = ((size_t)nimg0 * P.img_stride) + (size_t)nm0r * P.rowlen + (size_t)(nnlo0 * sHf);
+            nfilled = nlen0;
+        } else if constexpr (p == P_GEO + 2 || p == P_GEO + 3) {
+            // row r = 1 or 2 of the tile: LDS position where it starts, and
+            // (source float offset relative to nbase) - (LDS position)
+            constexpr int r = p - P_GEO - 1;
+            const uint32_t q = nq0 + r;
+            const bool has = q <= nq1;
             const uint32_t img = fdiv(q, P.d_ho);
             const int mq = (int)(q - img * (uint32_t)P.Ho);
-            const int nhi = (q == q1) ? (int)(Pend - q * (uint32_t)P.Wo) : P.Wo - 1;
-            t1 = len0;
-            d1 = (int)(img - img0) * P.img_stride + (mq - m0r) * P.rowlen - nlo0 * sHf - len0;
-            filled += (nhi * P.s + WF) * HF;
-        }
-        if (q0 + 2 <= q1) {
-            const uint32_t q = q0 + 2;
-            const uint32_t img = fdiv(q, P.d_ho);
-            const int mq = (int)(q - img * (uint32_t)P.Ho);
-            const int nhi = (q == q1) ? (int)(Pend - q * (uint32_t)P.Wo) : P.Wo - 1;
-            t2 = len0 + P.fullseg;
-            d2 = (int)(img - img0) * P.img_stride + (mq - m0r) * P.rowlen - nlo0 * sHf - t2;
-            filled += (nhi * P.s + WF) * HF;
-        }
-        const char *gb = reinterpret_cast<const char *>(P.win + base);
+            const int nhi = (q == nq1) ? (int)(nPend - q * (uint32_t)P.Wo) : P.Wo - 1;
+            const int pos = nlen0 + (r - 1) * P.fullseg;
+            const int d = (int)(img - nimg0) * P.img_stride + (mq - nm0r) * P.rowlen - nnlo0 * sHf - pos;
+            if (r == 1) { nt1 = has ? pos : 0x3fffffff; nd1 = has ? d : 0; }
+            else        { nt2 = has ? pos : 0x3fffffff; nd2 = has ? d : 0; }
+            nfilled += has ? (nhi * P.s + WF) * HF : 0;
+        } else if constexpr (p >= P_OFF && p < P_LD) {
+            constexpr int j = p - P_OFF;
+            const int xc = min(tid + NT * j, nfilled - 1);   // words past the strips are never operands
+            int d = xc < nt1 ? 0 : nd1;
+            d = xc < nt2 ? d : nd2;
+            noff[j] = (uint32_t)(xc + d) * 4u;
+        } else if constexpr (p >= P_LD && p < P_WPOS) {
+            const char *gb = reinterpret_cast<const char *>(P.win + nbase);
 #pragma unroll
-        for (int j = 0; j < JX; ++j) {
-            const int xc = min(tid + NT * j, filled - 1);   // words past the strips are never operands
-            int d = xc < t1 ? 0 : d1;
-            d = xc < t2 ? d : d2;
-            const uint32_t off = (uint32_t)(xc + d) * 4u;
+            for (int w = 2 * (p - P_LD); w < 2 * (p - P_LD) + 2 && w < NIW; ++w)
+                ir[w] = *reinterpret_cast<const float *>(gb + (size_t)(w / JX) * P.chan_stride * 4u + noff[w % JX]);
+        } else if constexpr (p == P_WPOS) {
+            const uint32_t Pl = min(nP0 + (uint32_t)(wn * 32 + l32), nPend);
+            const uint32_t ql = fdiv(Pl, P.d_wo);
+            const int nl = (int)(Pl - ql * (uint32_t)P.Wo);
+            const int rho = (int)(ql - nq0);
+            nwpos = rho == 0 ? (nl - nnlo0) * sHf : nlen0 + (rho - 1) * P.fullseg + nl * sHf;
+        } else if constexpr (p == P_OPTR) {
+            const uint32_t Pm = nP0 + (uint32_t)(wn * 32 + l32);
+            const uint32_t Pc = min(Pm, nPend);
+            const uint32_t img = fdiv(Pc, P.d_howo);
+            const uint32_t pin = Pc - img * P.howo;
+            no = P.out + ((size_t)img * P.Co + jl) * P.howo + pin;
+            nroom = Pm <= nPend ? P.Co - jl : 0;
+        } else if constexpr (p >= P_ST && p < P_LDS) {
+            // one output store of the previous tile
+            constexpr int q = p - P_ST;
+            if (KS == 2) {
+                // add the partner's partial sum to this wave's (kept in own[]) first
+                const lds_f32 *theirs = lds + 2 * STAGE + xpar * (WM * 2 * 2 * 512) + ((wn * WM + wm) * 2 + (ks ^ 1)) * 512 + lane;
+                const float sum = own[q] + *(const volatile lds_f32 *)(theirs + q * 64);
+                const int dj = (ks ? 16 : 0) + 8 * (q >> 2) + (q & 3);
+                if (dj < proom) po[(size_t)dj * P.howo] = sum;
+            } else {
+                constexpr int dj = 8 * (q >> 2) + (q & 3);
+                if (dj < proom) po[(size_t)dj * P.howo] = pacc[q];
+            }
+        } else if constexpr (p >= P_LDS && p < NP) {
+            lds_f32 *d = lds + st_next * STAGE + tid;
 #pragma unroll
-            for (int c = 0; c < CI; ++c)
-                ir[c * JX + j] = *reinterpret_cast<const float *>(gb + (size_t)c * P.chan_stride * 4u + off);
+            for (int w = 2 * (p - P_LDS); w < 2 * (p - P_LDS) + 2 && w < NIW; ++w)
+                d[(w / JX) * SS + NT * (w % JX)] = ir[w];
         }
     };
-    auto lds_store = [&](int st) {
-        lds_f32 *d = lds + st * STAGE + tid;
-#pragma unroll
-        for (int c = 0; c < CI; ++c)
-#pragma unroll
-            for (int j = 0; j < JX; ++j) d[c * SS + NT * j] = ir[c * JX + j];
+    // pieces lo..hi-1
+    auto pieces = [&](auto loc, auto hic, uint32_t t, int st_next, const floatx16 &pacc, int xpar) {
+        constexpr int lo = decltype(loc)::value, hi = decltype(hic)::value;
+        static_for<hi - lo>([&](auto k) { piece(std::integral_constant<int, lo + decltype(k)::value>{}, t, st_next, pacc, xpar); });
     };
 
     if (tid < 8) { lds[CI * SS + (tid & 3) + (tid >> 2) * STAGE] = 0.0f; }   // zero slots of both stages
 
-    // Each workgroup walks a contiguous range of tiles: neighbouring tiles share
-    // strip words (L2 hits) and write to the same pages of the output.
-    const uint32_t per = (P.ntiles + gridDim.x - 1) / gridDim.x;
-    uint32_t tile = blockIdx.x * per;
-    const uint32_t tile_end = min(tile + per, P.ntiles);
-    if (tile >= tile_end) return;   // whole workgroup: no barrier is skipped by part of it
-    gload(tile);
-    lds_store(0);
+    // ---- prologue: tile0's strips into stage 0 (all "next tile" pieces but the stores) ----
+    {
+        floatx16 z;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) z[v] = 0.0f;
+        acc[0] = z; acc[1] = z;
+        pieces(std::integral_constant<int, P_GEO>{}, std::integral_constant<int, P_ST>{}, tile0, 0, z, 0);
+        pieces(std::integral_constant<int, P_LDS>{}, std::integral_constant<int, NP>{}, tile0, 0, z, 0);
+    }
     __syncthreads();
 
-    for (int it = 0; tile < tile_end; ++it, ++tile) {
-        const int st = it & 1;
-        const uint32_t next = tile + 1;
-        const bool has_next = next < tile_end;
-        if (has_next) gload(next);   // in flight during this tile's matrix work
-
-        // ---- this tile: where the lane's window starts in the LDS strips -----------
-        const uint32_t P0 = tile * NB;
-        const uint32_t Pend = min(P0 + NB - 1, P.npix - 1);
-        int wpos;
-        {
-            const uint32_t q0 = fdiv(P0, P.d_wo), q1 = fdiv(Pend, P.d_wo);
-            const int nlo0 = (int)(P0 - q0 * (uint32_t)P.Wo);
-            const int len0 = (((q1 == q0) ? (int)(Pend - P0) : (P.Wo - 1 - nlo0)) * P.s + WF) * HF;
-            const uint32_t Pl = min(P0 + (uint32_t)(wn * 32 + l32), Pend);
-            const uint32_t ql = fdiv(Pl, P.d_wo);
-            const int nl = (int)(Pl - ql * (uint32_t)P.Wo);
-            const int rho = (int)(ql - q0);
-            wpos = rho == 0 ? (nl - nlo0) * sHf : len0 + (rho - 1) * P.fullseg + nl * sHf;
-        }
-
-        // ---- K loop: TW MFMA steps, B operands fetched SH_G steps ahead -----------
-        const lds_f32 *sbase = lds + st * STAGE;
-        const lds_f32 *bpair = sbase + wpos + h * SS;
-        const lds_f32 *bsplit = sbase + wpos + (CI - 1) * SS + h * KH2;
+    // ---- one tile: the MFMA chain with the pieces in its shadow -------------------
+    auto tile_body = [&](auto parc, uint32_t tile) {
+        constexpr int PAR = decltype(parc)::value;      // tile parity: LDS stage, accumulator set
+        constexpr int AP = (KS == 2) ? 0 : PAR;         // with KS == 2 only 8 sums outlive the chain (own[])
+        // the fetched tile becomes the computed tile
+        cwpos = nwpos; co = no; croom = nroom;
+        const uint32_t nxt = min(tile + 1, tile_end - 1);   // the last tile refetches itself (unused)
+        const lds_f32 *sbase = lds + PAR * STAGE;
+        const lds_f32 *bpair = sbase + cwpos + h * SS;
+        const lds_f32 *bsplit = sbase + cwpos + (CI - 1) * SS + h * KH2;
         const lds_f32 *bzero = (h && (KHW & 1)) ? sbase + CI * SS : bsplit + (KH2 - 1);
-        floatx16 acc;
         auto run = [&](auto ksc) {
             constexpr int KSI = decltype(ksc)::value;
             auto bread = [&](int ii) -> float {
                 const int i = KSI * TW + ii;   // global step index (compile-time after unrolling)
                 if (St::is_pair(i)) {
-                    const int p = i / KHW, t = i % KHW;
-                    return *(const volatile lds_f32 *)(bpair + 2 * p * SS + t);
+                    const int pp = i / KHW, t = i % KHW;
+                    return *(const volatile lds_f32 *)(bpair + 2 * pp * SS + t);
                 }
                 const int t = i - NPAIR * KHW;
                 if (t == KH2 - 1) return *(const volatile lds_f32 *)bzero;
                 return *(const volatile lds_f32 *)(bsplit + t);
             };
-            // The scheduling barriers pin the order "reads of group g+1, then MFMAs of
-            // group g": left alone the compiler sinks every LDS read to just before its
-            // MFMA and the matrix pipe waits out one LDS latency per step.
-            float b[2][SH_G];
+            float b[SH_G];   // ring of B operands, SH_G steps ahead of the MFMAs
 #pragma unroll
             for (int e = 0; e < SH_G; ++e)
-                if (e < TW) b[0][e] = bread(e);
+                if (e < TW) b[e] = bread(e);
             __builtin_amdgcn_sched_barrier(0);
+            static_for<TW>([&](auto ic) {
+                constexpr int ii = decltype(ic)::value;
+                if (ii == 0) {
+                    floatx16 z;
 #pragma unroll
-            for (int g = 0; g < NG; ++g) {
-#pragma unroll
-                for (int e = 0; e < SH_G; ++e)
-                    if ((g + 1) * SH_G + e < TW) b[(g + 1) & 1][e] = bread((g + 1) * SH_G + e);
-                __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                for (int e = 0; e < SH_G; ++e) {
-                    const int ii = g * SH_G + e;
-                    if (ii < TW) {
-                        if (ii == 0) {
-                            floatx16 z;
-#pragma unroll
-                            for (int v = 0; v < 16; ++v) z[v] = 0.0f;
-                            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[0], b[0][0], z, 0, 0, 0);
-                        } else {
-                            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[ii], b[g & 1][e], acc, 0, 0, 0);
-                        }
-                    }
+                    for (int v = 0; v < 16; ++v) z[v] = 0.0f;
+                    acc[AP] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[0], b[0], z, 0, 0, 0);
+                } else {
+                    acc[AP] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[ii], b[ii % SH_G], acc[AP], 0, 0, 0);
                 }
+                if (ii + SH_G < TW) b[ii % SH_G] = bread(ii + SH_G);
+                // pieces whose slot is this MFMA: piece p rides behind MFMA p*TW/NP
+                constexpr int plo = (ii * NP + TW - 1) / TW, phi = ((ii + 1) * NP + TW - 1) / TW;
+                pieces(std::integral_constant<int, plo>{}, std::integral_constant<int, phi>{}, nxt, PAR ^ 1, acc[AP ^ 1], PAR ^ 1);
                 __builtin_amdgcn_sched_barrier(0);
-            }
+            });
         };
         if (KS == 1) {
             run(std::integral_constant<int, 0>{});
         } else {
             if (ks == 0) run(std::integral_constant<int, 0>{});
             else run(std::integral_constant<int, KS - 1>{});
-        }
-
-        // ---- combine the K halves (KS == 2): each wave of a pair ends up owning 8
-        // of the 16 accumulator registers of the block ------------------------------
-        if (KS == 2) {
-            lds_f32 *xch = lds + 2 * STAGE + ((wn * WM + wm) * 2) * (8 * 64);   // [2 waves][8][64]
-            lds_f32 *mine = xch + ks * (8 * 64) + lane;
-            const lds_f32 *theirs = xch + (ks ^ 1) * (8 * 64) + lane;
+            // hand the partner the half of this tile's accumulators that it owns
+            lds_f32 *mine = lds + 2 * STAGE + PAR * (WM * 2 * 2 * 512) + ((wn * WM + wm) * 2 + ks) * 512 + lane;
 #pragma unroll
-            for (int v = 0; v < 8; ++v) mine[v * 64] = ks ? acc[v] : acc[8 + v];   // the half the partner will own
-            __syncthreads();
+            for (int v = 0; v < 8; ++v) mine[v * 64] = ks ? acc[0][v] : acc[0][8 + v];
 #pragma unroll
-            for (int v = 0; v < 8; ++v) {
-                const float o = theirs[v * 64];
-                if (ks) acc[8 + v] += o; else acc[v] += o;
-            }
+            for (int v = 0; v < 8; ++v) own[v] = ks ? acc[0][8 + v] : acc[0][v];
         }
-
-        // ---- epilogue ---------------------------------------------------------------
-        // Lane (h, l32) holds pixel l32 of the wave's 32 and, in register v, output
-        // channel jl + 8*(v/4) + v%4 with jl = block base + 4*h.  The per-lane part of
-        // the address is formed once; the per-register part is wave-uniform.
-        {
-            const uint32_t Pm = P0 + (uint32_t)(wn * 32 + l32);
-            if (Pm <= Pend) {
-                const uint32_t img = fdiv(Pm, P.d_howo);
-                const uint32_t pin = Pm - img * P.howo;
-                const int jl = (int)blockIdx.y * (WM * 32) + wm * 32 + 4 * h;
-                float *o = P.out + ((size_t)img * P.Co + jl) * P.howo + pin;
-                const int room = P.Co - jl;   // channels jl .. Co-1 exist
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    if (KS == 2 && ((v >> 3) != ks)) continue;   // the partner stores that half
-                    const int dj = 8 * (v >> 2) + (v & 3);
-                    if (dj < room) o[(size_t)dj * P.howo] = acc[v];
-                }
-            }
-        }
-
-        if (has_next) lds_store(st ^ 1);
+        // the computed tile becomes the previous tile
+        po = co; proom = croom;
         __syncthreads();
+    };
+
+    uint32_t tile = tile0;
+    for (; tile + 1 < tile_end; tile += 2) {   // unrolled by two: stage and accumulator set are constants
+        tile_body(std::integral_constant<int, 0>{}, tile);
+        tile_body(std::integral_constant<int, 1>{}, tile + 1);
     }
+    int lastpar = 1;
+    if (tile < tile_end) { tile_body(std::integral_constant<int, 0>{}, tile); lastpar = 0; }
+
+    // ---- drain: exchange reads and stores of the last tile -------------------------
+    if (lastpar == 0) pieces(std::integral_constant<int, P_ST>{}, std::integral_constant<int, P_LDS>{}, 0u, 0, acc[0], 0);
+    else pieces(std::integral_constant<int, P_ST>{}, std::integral_constant<int, P_LDS>{}, 0u, 0, acc[1], 1);
 }
 
 template <int HF, int WF, int CI, int WM, int KS, int JX>
@@ -290,7 +324,7 @@ static hipError_t launch_shallow_t(const ShallowParams &P, int mgroups, hipStrea
     constexpr int NT = 64 * WM * 2 * KS;
     constexpr int SS = JX * NT;
     constexpr int STAGE = CI * SS + 4;
-    constexpr size_t lds = 4u * (size_t)(2 * STAGE + (KS == 2 ? WM * 2 * 2 * 8 * 64 : 0));
+    constexpr size_t lds = 4u * (size_t)(2 * STAGE + (KS == 2 ? 2 * WM * 2 * 2 * 8 * 64 : 0));
     auto kern = &conv_mfma_shallow_kernel<HF, WF, CI, WM, KS, JX>;
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
