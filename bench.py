@@ -34,8 +34,8 @@ PEAK_HBM_GBS = 8000.0             # MI355X HBM3E
 # device copy (factors 2.000 and 1.000).  The summary with the commands is in
 # profiles/conv_mfma_fast_and_transform_cfg2_3x3_c64_56.md.  Layers that were
 # not measured report null.
-MEASURED_CONV_TRAFFIC_BYTES = {"cfg2_3x3_c64_56": 107000416}
-MEASURED_TRANSFORM_TRAFFIC_BYTES = {"cfg2_3x3_c64_56": 116533520}
+MEASURED_CONV_TRAFFIC_BYTES = {"cfg2_3x3_c64_56": 107315805}
+MEASURED_TRANSFORM_TRAFFIC_BYTES = {"cfg2_3x3_c64_56": 116533631}
 
 
 def parse_args():
