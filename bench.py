@@ -48,6 +48,8 @@ def parse_args():
                     help="also time the other layers and list them under 'layers'")
     ap.add_argument("--table2", action="store_true",
                     help="also time the twelve layers of the paper's Table 2 at batch 128 (listed under 'table2')")
+    ap.add_argument("--ablation", action="store_true",
+                    help="also time the ablation variants of the convolution on the 3x3 layers (listed under 'ablation')")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (known traffic) so that a rocprofv3 --pmc "
@@ -71,30 +73,47 @@ def time_layer(L, steps, warmup):
         im2win.im2win_transform(dI, dW, N, Ci, Hi, Wi, Hf, Wf, s, p)
         im2win.conv2d_im2win_fwd(dW, dF, dO, N, Ci, Hi, Wi, Co, Hf, Wf, s, p)
 
-    for _ in range(warmup):
-        step()
+    # Set-up, not part of the W warm-up steps: the first pass checks that every
+    # output word is written, and a short burst brings the GPU clocks up (a cold
+    # device needs a few milliseconds of load to leave its idle clock).
+    step()
     torch.cuda.synchronize()
     if bool(torch.isnan(dO).any()) or bool(torch.isnan(dW).any()):
         raise RuntimeError("%s: an output element was never written" % L.name)
+    t_ramp = time.perf_counter()
+    while time.perf_counter() - t_ramp < 0.05:
+        for _ in range(20):
+            step()
+        torch.cuda.synchronize()
 
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # Kernel-level HIP events are recorded on every EVERY-th step of the timed
+    # region (on all of them they would add several microseconds to each step).
+    EVERY = 5
+    ev = {k: [torch.cuda.Event(enable_timing=True) for _ in range(3)] for k in range(0, steps, EVERY)}
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for k in range(steps):
-        ev[k][0].record()
-        im2win.im2win_transform(dI, dW, N, Ci, Hi, Wi, Hf, Wf, s, p)
-        ev[k][1].record()
-        im2win.conv2d_im2win_fwd(dW, dF, dO, N, Ci, Hi, Wi, Co, Hf, Wf, s, p)
-        ev[k][2].record()
+        if k in ev:
+            ev[k][0].record()
+            im2win.im2win_transform(dI, dW, N, Ci, Hi, Wi, Hf, Wf, s, p)
+            ev[k][1].record()
+            im2win.conv2d_im2win_fwd(dW, dF, dO, N, Ci, Hi, Wi, Co, Hf, Wf, s, p)
+            ev[k][2].record()
+        else:
+            step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    tr = [e[0].elapsed_time(e[1]) for e in ev]
-    cv = [e[1].elapsed_time(e[2]) for e in ev]
+    tr = [e[0].elapsed_time(e[1]) for e in ev.values()]
+    cv = [e[1].elapsed_time(e[2]) for e in ev.values()]
     ws = im2win.im2win_workspace_bytes(N, Ci, Hi, Wi, Hf, Wf, s, p)
     col = im2win.im2col_footprint_bytes(N, Ci, Hi, Wi, Hf, Wf, s, p)
     return dict(ms_per_step=(t1 - t0) * 1e3 / steps,
-                transform_ms_avg=sum(tr) / steps, transform_ms_best=min(tr),
-                conv_ms_avg=sum(cv) / steps, conv_ms_best=min(cv),
+                transform_ms_avg=sum(tr) / len(tr), transform_ms_best=min(tr),
+                conv_ms_avg=sum(cv) / len(cv), conv_ms_best=min(cv),
                 workspace_bytes=ws, im2col_bytes=col,
                 transform_alg_bytes=4 * N * Ci * Hi * Wi + ws,
                 conv_alg_bytes=ws + 4 * Co * Ci * Hf * Wf + 4 * N * Co * L.Ho * L.Wo)
@@ -116,6 +135,39 @@ def layer_report(L, t):
         "transform_ms_avg": t["transform_ms_avg"], "transform_ms_best": t["transform_ms_best"],
         "workspace_bytes": t["workspace_bytes"], "im2col_bytes": t["im2col_bytes"],
     }
+
+
+def time_variants(L, steps):
+    """Convolution-only timing of each ablation variant on one layer (HIP events, average of `steps`)."""
+    import torch
+    import paper_2306_14316_amd as im2win
+    from paper_2306_14316_amd import workloads
+    N, Ci, Hi, Wi, Co, Hf, Wf, s, p = L.dims
+    I, F = workloads.make_inputs(L)
+    dI, dF = I.cuda(), F.cuda()
+    dW = torch.empty((N, Ci, L.Ho, L.Wp * Hf), dtype=torch.float32, device="cuda")
+    dO = torch.empty((N, Co, L.Ho, L.Wo), dtype=torch.float32, device="cuda")
+    im2win.im2win_transform(dI, dW, N, Ci, Hi, Wi, Hf, Wf, s, p)
+    names = {0: "default", 1: "no_pipeline (one LDS stage, no prefetch)", 2: "no_mfma (one thread per output)"}
+    out = {}
+    for v, name in names.items():
+        k = steps if v != 2 else max(2, steps // 10)
+        try:
+            for _ in range(10 if v != 2 else 1):
+                im2win.conv2d_im2win_fwd_variant(dW, dF, dO, N, Ci, Hi, Wi, Co, Hf, Wf, s, p, v)
+        except im2win.Im2winError:
+            out[name] = None
+            continue
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(k):
+            im2win.conv2d_im2win_fwd_variant(dW, dF, dO, N, Ci, Hi, Wi, Co, Hf, Wf, s, p, v)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / k
+        out[name] = {"conv_ms": ms, "conv_tflops": L.flops / (ms * 1e-3) / 1e12}
+    return {"workload": L.name, "variants": out}
 
 
 def cpu_baseline(L):
@@ -198,6 +250,8 @@ def main():
                 k = max(10, min(a.steps, 30))
                 reps.append(layer_report(other, time_layer(other, k, min(a.warmup, 5))))
         out["layers"] = reps
+    if a.ablation:
+        out["ablation"] = [time_variants(workloads.layer(i), max(5, min(a.steps, 30))) for i in (2, 3)]
     if a.table2:
         out["table2"] = [layer_report(t2, time_layer(t2, max(5, min(a.steps, 20)), 3)) for t2 in workloads.TABLE2]
     if not a.no_cpu_baseline:

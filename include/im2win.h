@@ -42,7 +42,8 @@ typedef enum {
     IM2WIN_ERR_SHAPE = -2,       /* a dimension <= 0, stride < 1, pad < 0, or the filter */
                                  /* is larger than the padded input                      */
     IM2WIN_ERR_OVERFLOW = -3,    /* a tensor has 2^31 or more elements                   */
-    IM2WIN_ERR_UNSUPPORTED = -4, /* shape needs more LDS than one workgroup can hold     */
+    IM2WIN_ERR_UNSUPPORTED = -4, /* shape needs more LDS than one workgroup can hold, or */
+                                 /* an unknown kernel variant was requested              */
     IM2WIN_ERR_HIP = -5          /* the HIP runtime refused the launch                   */
 } im2win_status;
 
@@ -99,6 +100,26 @@ im2win_status conv2d_im2win_fwd_basic(const float *window_dev, const float *filt
                                       float *output_dev,
                                       int N, int Ci, int Hi, int Wi, int Co, int Hf, int Wf,
                                       int stride, int pad, void *stream);
+
+/*
+ * Ablation variants of the convolution (Section 4.4 removes one optimisation
+ * at a time; these are the CDNA4 counterparts).  Same arguments and result as
+ * conv2d_im2win_fwd plus `variant` (any other value: IM2WIN_ERR_UNSUPPORTED):
+ *   IM2WIN_VARIANT_DEFAULT           the kernel conv2d_im2win_fwd would pick;
+ *   IM2WIN_VARIANT_NO_PIPELINE       no double buffer / prefetch: one LDS stage,
+ *                                    staging outside the MFMA chain (any layer);
+ *   IM2WIN_VARIANT_NO_MFMA           no matrix cores, no register tile: one thread
+ *                                    per output (Algorithm 2).
+ */
+enum {
+    IM2WIN_VARIANT_DEFAULT = 0,
+    IM2WIN_VARIANT_NO_PIPELINE = 1,
+    IM2WIN_VARIANT_NO_MFMA = 2
+};
+im2win_status conv2d_im2win_fwd_variant(const float *window_dev, const float *filter_dev,
+                                        float *output_dev,
+                                        int N, int Ci, int Hi, int Wi, int Co, int Hf, int Wf,
+                                        int stride, int pad, int variant, void *stream);
 
 /* Static description of a status code (never NULL). */
 const char *im2win_status_str(int status);

@@ -9,6 +9,10 @@ from .binding import (  # noqa: F401
     Im2winError,
     conv2d_im2win_fwd,
     conv2d_im2win_fwd_basic,
+    conv2d_im2win_fwd_variant,
+    VARIANT_DEFAULT,
+    VARIANT_NO_PIPELINE,
+    VARIANT_NO_MFMA,
     im2col_footprint_bytes,
     im2win_out_shape,
     im2win_transform,

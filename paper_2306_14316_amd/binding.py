@@ -19,6 +19,7 @@ EXPORTS = (
     "im2win_transform",
     "conv2d_im2win_fwd",
     "conv2d_im2win_fwd_basic",
+    "conv2d_im2win_fwd_variant",
     "im2win_status_str",
 )
 
@@ -54,6 +55,8 @@ def load_library():
         for name in ("conv2d_im2win_fwd", "conv2d_im2win_fwd_basic"):
             getattr(lib, name).restype = i
             getattr(lib, name).argtypes = [vp, vp, vp] + [i] * 9 + [vp]
+        lib.conv2d_im2win_fwd_variant.restype = i
+        lib.conv2d_im2win_fwd_variant.argtypes = [vp, vp, vp] + [i] * 10 + [vp]
         lib.im2win_status_str.restype = ctypes.c_char_p
         lib.im2win_status_str.argtypes = [i]
         _lib = lib
@@ -133,3 +136,18 @@ def conv2d_im2win_fwd(window, filter, output, N, Ci, Hi, Wi, Co, Hf, Wf, stride,
 def conv2d_im2win_fwd_basic(window, filter, output, N, Ci, Hi, Wi, Co, Hf, Wf, stride, pad, stream=None):
     """output <- the one-thread-per-output kernel (Algorithm 2)."""
     _conv("conv2d_im2win_fwd_basic", window, filter, output, N, Ci, Hi, Wi, Co, Hf, Wf, stride, pad, stream)
+
+
+VARIANT_DEFAULT, VARIANT_NO_PIPELINE, VARIANT_NO_MFMA = 0, 1, 2
+
+
+def conv2d_im2win_fwd_variant(window, filter, output, N, Ci, Hi, Wi, Co, Hf, Wf, stride, pad, variant,
+                              stream=None):
+    """output <- the convolution computed by one of the ablation variants (VARIANT_*)."""
+    Ho, Wo = im2win_out_shape(Hi, Wi, Hf, Wf, stride, pad)
+    w = _dev_ptr(window, "window", N * Ci * Ho * (Wi + 2 * pad) * Hf)
+    f = _dev_ptr(filter, "filter", Co * Ci * Hf * Wf)
+    o = _dev_ptr(output, "output", N * Co * Ho * Wo)
+    _check(load_library().conv2d_im2win_fwd_variant(w, f, o, N, Ci, Hi, Wi, Co, Hf, Wf, stride, pad,
+                                                     int(variant), _stream(stream)),
+           "conv2d_im2win_fwd_variant")

@@ -104,6 +104,20 @@ im2win_status conv2d_im2win_fwd(const float *window_dev, const float *filter_dev
     return e == hipSuccess ? IM2WIN_OK : IM2WIN_ERR_HIP;
 }
 
+im2win_status conv2d_im2win_fwd_variant(const float *window_dev, const float *filter_dev, float *output_dev,
+                                        int N, int Ci, int Hi, int Wi, int Co, int Hf, int Wf, int stride,
+                                        int pad, int variant, void *stream)
+{
+    if (!window_dev || !filter_dev || !output_dev) return IM2WIN_ERR_NULL;
+    if (variant < IM2WIN_VARIANT_DEFAULT || variant > IM2WIN_VARIANT_NO_MFMA) return IM2WIN_ERR_UNSUPPORTED;
+    Shape sh;
+    im2win_status st = derive(N, Ci, Hi, Wi, Co, Hf, Wf, stride, pad, &sh);
+    if (st != IM2WIN_OK) return st;
+    hipError_t e = im2win::launch_conv_mfma(window_dev, filter_dev, output_dev, sh, (hipStream_t)stream, variant);
+    if (e == hipErrorInvalidConfiguration || e == hipErrorNotSupported) return IM2WIN_ERR_UNSUPPORTED;
+    return e == hipSuccess ? IM2WIN_OK : IM2WIN_ERR_HIP;
+}
+
 im2win_status conv2d_im2win_fwd_basic(const float *window_dev, const float *filter_dev, float *output_dev,
                                       int N, int Ci, int Hi, int Wi, int Co, int Hf, int Wf, int stride,
                                       int pad, void *stream)
@@ -123,7 +137,7 @@ const char *im2win_status_str(int status)
         case IM2WIN_ERR_NULL: return "a required pointer is NULL";
         case IM2WIN_ERR_SHAPE: return "invalid shape: non-positive dimension, stride < 1, pad < 0 or filter larger than padded input";
         case IM2WIN_ERR_OVERFLOW: return "a tensor has 2^31 or more elements";
-        case IM2WIN_ERR_UNSUPPORTED: return "shape not supported: tile does not fit in LDS";
+        case IM2WIN_ERR_UNSUPPORTED: return "not supported: tile does not fit in LDS, or unknown kernel variant";
         case IM2WIN_ERR_HIP: return "HIP runtime error at launch";
         default: return "unknown status";
     }

@@ -44,8 +44,11 @@ struct Shape {
 hipError_t launch_transform(const float *in, float *win, const Shape &sh, hipStream_t st);
 hipError_t launch_conv_basic(const float *win, const float *flt, float *out, const Shape &sh,
                              hipStream_t st);
+// Kernel selection for the MFMA convolution (the values of the public
+// IM2WIN_VARIANT_* constants).
+enum ConvVariant { kVariantDefault = 0, kVariantNoPipeline = 1, kVariantNoMfma = 2 };
 // Returns hipErrorInvalidConfiguration when no tile configuration fits in LDS.
 hipError_t launch_conv_mfma(const float *win, const float *flt, float *out, const Shape &sh,
-                            hipStream_t st);
+                            hipStream_t st, int variant = kVariantDefault);
 
 }  // namespace im2win

@@ -187,8 +187,9 @@ static hipError_t launch_t(const MfmaParams &P, size_t lds, uint32_t blocks, hip
 }
 
 hipError_t launch_conv_mfma(const float *win, const float *flt, float *out, const Shape &sh,
-                            hipStream_t st)
+                            hipStream_t st, int variant)
 {
+    if (variant == kVariantNoMfma) return launch_conv_basic(win, flt, out, sh, st);
     MfmaParams P;
     P.win = win; P.flt = flt; P.out = out;
     P.Ci = sh.Ci; P.Ho = sh.Ho; P.Wo = sh.Wo; P.Co = sh.Co; P.Hf = sh.Hf; P.Wf = sh.Wf; P.s = sh.s;
@@ -224,7 +225,7 @@ hipError_t launch_conv_mfma(const float *win, const float *flt, float *out, cons
 
     const uint32_t tiles_n = (P.npix + NB - 1) / NB;
     const uint32_t blocks = tiles_n * (uint32_t)P.tiles_m;
-    {
+    if (variant == kVariantDefault) {
         hipError_t fe = launch_conv_mfma_shallow(win, flt, out, sh, st);
         if (fe != hipErrorNotSupported) return fe;
         fe = launch_conv_mfma_fast(P, sh, blocks, st);

@@ -113,6 +113,41 @@ def test_basic_kernel_on_benchmark_layers(idx):
     check_layer(I, F, L.stride, L.pad, basic=True, twice=False)
 
 
+VARIANT_SHAPES = [
+    (1, 3, 32, 32, 16, 3, 3, 1, 0),      # the tiny benchmark layer
+    (4, 64, 56, 56, 64, 3, 3, 1, 1),     # the headline layer at batch 4
+    (2, 16, 20, 20, 40, 3, 3, 1, 1),     # ragged Co
+    (1, 3, 40, 260, 64, 7, 7, 2, 3),     # a three-channel 7x7 layer
+    (2, 5, 9, 9, 7, 2, 3, 2, 1),         # a small odd layer
+]
+
+
+@pytest.mark.parametrize("shape", VARIANT_SHAPES, ids=lambda s: "x".join(map(str, s)))
+@pytest.mark.parametrize("variant", [0, 1, 2])
+def test_ablation_variants(shape, variant):
+    """Every ablation variant computes the same convolution."""
+    N, Ci, Hi, Wi, Co, Hf, Wf, s, p = shape
+    I, F = workloads.random_layer_inputs(9000 + sum(shape), N, Ci, Hi, Wi, Co, Hf, Wf)
+    dW = run_transform(I, Hf, Wf, s, p)
+    Ho, Wo = im2win.im2win_out_shape(Hi, Wi, Hf, Wf, s, p)
+    dO = torch.full((N, Co, Ho, Wo), float("nan"), dtype=torch.float32, device="cuda")
+    im2win.conv2d_im2win_fwd_variant(dW, F.cuda(), dO, N, Ci, Hi, Wi, Co, Hf, Wf, s, p, variant)
+    torch.cuda.synchronize()
+    O_ref, B_ref = oracle.conv2d_direct(I.numpy(), F.numpy(), s, p)
+    assert_conv_close(dO.cpu().numpy(), O_ref, B_ref)
+
+
+def test_unknown_variant_is_rejected():
+    N, Ci, Hi, Wi, Co, Hf, Wf, s, p = 1, 2, 6, 6, 3, 3, 3, 1, 0
+    I, F = workloads.random_layer_inputs(5, N, Ci, Hi, Wi, Co, Hf, Wf)
+    dW = run_transform(I, Hf, Wf, s, p)
+    dO = torch.zeros((N, Co, 4, 4), dtype=torch.float32, device="cuda")
+    for bad in (-1, 3, 99):
+        with pytest.raises(im2win.Im2winError):
+            im2win.conv2d_im2win_fwd_variant(dW, F.cuda(), dO, N, Ci, Hi, Wi, Co, Hf, Wf, s, p, bad)
+    assert not bool(dO.any())      # nothing was launched
+
+
 def test_transform_copies_bit_patterns():
     """NaN payloads, infinities, -0.0 and denormals pass through untouched; padding is +0.0."""
     bits = np.array([0x7FC00001, 0xFFC12345, 0x7F800001, 0x80000000, 0x00000001, 0x807FFFFF,

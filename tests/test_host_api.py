@@ -73,6 +73,8 @@ def test_invalid_shapes_are_rejected_before_any_launch(lib, bad):
     for fn in (lib.conv2d_im2win_fwd, lib.conv2d_im2win_fwd_basic):
         assert fn(one, one, one, a["N"], a["Ci"], a["Hi"], a["Wi"], a["Co"], a["Hf"], a["Wf"],
                   a["stride"], a["pad"], None) == -2
+    assert lib.conv2d_im2win_fwd_variant(one, one, one, a["N"], a["Ci"], a["Hi"], a["Wi"], a["Co"], a["Hf"],
+                                         a["Wf"], a["stride"], a["pad"], 1, None) == -2
 
 
 def test_null_pointers_and_overflow(lib):
@@ -83,6 +85,8 @@ def test_null_pointers_and_overflow(lib):
     assert lib.conv2d_im2win_fwd(one, one, None, 1, 1, 4, 4, 1, 2, 2, 1, 0, None) == -1
     assert lib.conv2d_im2win_fwd_basic(None, one, one, 1, 1, 4, 4, 1, 2, 2, 1, 0, None) == -1
     assert lib.im2win_out_shape(4, 4, 2, 2, 1, 0, None, None) == -1
+    assert lib.conv2d_im2win_fwd_variant(one, one, None, 1, 1, 4, 4, 1, 2, 2, 1, 0, 0, None) == -1
+    assert lib.conv2d_im2win_fwd_variant(one, one, one, 1, 1, 4, 4, 1, 2, 2, 1, 0, 7, None) == -4
     # 2^31 or more elements in the im2win tensor / the output
     assert lib.im2win_transform(one, one, 4096, 64, 224, 224, 7, 7, 2, 0, None) == -3
     assert lib.conv2d_im2win_fwd(one, one, one, 128, 3, 1024, 1024, 64, 1, 1, 1, 0, None) == -3
