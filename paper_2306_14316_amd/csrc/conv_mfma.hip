@@ -205,6 +205,7 @@ hipError_t launch_conv_mfma(const float *win, const float *flt, float *out, cons
     if (rmax > NB) rmax = NB;
     const int over = sh.Wf > sh.s ? sh.Wf - sh.s : 0;
     P.S = (NB * sh.s + rmax * over) * sh.Hf + 1;
+    P.rmax = rmax;
 
     const size_t lds_max = 160 * 1024;
     int cb = sh.Ci < 8 ? sh.Ci : 8;

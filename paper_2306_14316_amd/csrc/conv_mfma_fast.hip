@@ -1,17 +1,20 @@
-// Software-pipelined variant of the MFMA im2win convolution for layers with
-// many input channels and a small, compile-time filter (the 3x3 layers that
-// make up most of the paper's Table 2).  Same tile, same strip geometry and
-// same pair-step K order as conv_mfma.hip; what differs:
+// Software-pipelined MFMA im2win convolution for layers with many input
+// channels and a compile-time filter (3x3, 5x5, 7x7: all multi-channel layers of
+// the paper's Table 2).  Same 64x64 tile, strip geometry and pair-step K order
+// as conv_mfma.hip; what differs:
 //   - the filter shape and the channels per K block are template constants,
 //     so every LDS operand address is base + immediate and all staging
 //     coordinates are computed once per thread, before the K loop;
-//   - the next K block's global loads (filter rows as float4, strip words)
-//     are issued into registers before the current block's MFMAs and written
-//     to LDS after them (the prefetch/double-buffer idea of Section 3.3, done
-//     in registers), so global latency overlaps the matrix work;
+//   - the next K blocks' global loads (filter rows as 16- or 8-byte chunks,
+//     strip words) are issued into registers during the current block's MFMAs
+//     and written to the other LDS stage one block later (the prefetch /
+//     double-buffer idea of Section 3.3, done in registers), so global latency
+//     overlaps the matrix work;
 //   - the filter tile stays row-major [m][k] in LDS with an odd pitch, which
 //     makes both the staging writes and the A-operand reads conflict-free; the
-//     (u,v) -> window-order permutation is a compile-time offset on the read.
+//     (u,v) -> window-order permutation is a compile-time offset on the read;
+//   - every non-MFMA instruction of the K loop is placed, in program order,
+//     between two MFMAs of the wave's dependent chain, where it issues for free.
 #include "conv_mfma_tile.h"
 
 #include <type_traits>
@@ -20,19 +23,35 @@ namespace im2win {
 
 typedef __attribute__((address_space(3))) float lds_float;   // a float in LDS
 
-template <int HF, int WF, int CB, int JX>
-__global__ __launch_bounds__(256, 3) void conv_mfma_fast_kernel(MfmaParams P)
+// MFMA operands are read from LDS R steps ahead, through a ring of R register
+// pairs; R divides the MFMAs per K block so that ring positions line up from one
+// block to the next.
+constexpr int pick_ring(int nm)
+{
+    const int cand[] = {9, 10, 8, 7, 11, 12, 6, 5};
+    for (int r : cand)
+        if (nm % r == 0) return r;
+    return 0;
+}
+
+// CW: floats per filter staging chunk (4: 16-byte loads, 2: 8-byte loads).
+// OCC: workgroups per CU the register allocation should leave room for.
+template <int HF, int WF, int CB, int JX, int CW, int OCC>
+__global__ __launch_bounds__(256, OCC) void conv_mfma_fast_kernel(MfmaParams P)
 {
     constexpr int KHW = HF * WF;
     constexpr int KB = CB * KHW;            // K elements per block
-    constexpr int CPR = KB / 4;             // float4 chunks per filter row per block
-    constexpr int NF4 = MB * CPR;
-    constexpr int JF = (NF4 + 255) / 256;   // float4 chunks per thread
+    constexpr int CPR = KB / CW;            // chunks per filter row per block
+    constexpr int NFC = MB * CPR;           // chunks per filter tile
+    constexpr int JF = (NFC + 255) / 256;   // chunks per thread
     constexpr int PF = KB | 1;              // odd LDS pitch of a filter row
     constexpr int SS = 256 * JX;            // LDS floats per channel strip (compile-time stride)
     constexpr int SF_FLOATS = (MB * PF + 3) & ~3;
     constexpr int STAGE = SF_FLOATS + CB * SS;   // floats per LDS stage
-    static_assert(KB % 4 == 0, "K block must be a multiple of 4 floats");
+    constexpr int R = pick_ring((CB / 2) * KHW);
+    static_assert(R > 0, "no ring length divides the MFMAs per block");
+    static_assert(CW == 4 || CW == 2, "chunks are 16 or 8 bytes");
+    static_assert(KB % CW == 0, "K block must be a whole number of chunks");
     static_assert(CB % 2 == 0, "pair steps need an even channel count");
 
     // two LDS stages, each [filter tile MB x PF][CB strips of SS floats]
@@ -55,9 +74,13 @@ __global__ __launch_bounds__(256, 3) void conv_mfma_fast_kernel(MfmaParams P)
     const int nlo0 = (int)(P0 - q0 * (uint32_t)P.Wo);
     const int sHf = P.s * HF;
     const int len0 = (((q1 == q0) ? (int)(Pend - P0) : (P.Wo - 1 - nlo0)) * P.s + WF) * HF;
+    // float offset, in channel plane 0, of the first strip word of the tile
+    const uint32_t img0 = fdiv(q0, P.d_ho);
+    const size_t tile_base = ((size_t)img0 * P.Ci * P.Ho + (q0 - img0 * (uint32_t)P.Ho)) * (size_t)P.rowlen +
+                             (size_t)(nlo0 * sHf);
 
-    // Byte offset (from the channel plane) of strip word tid + 256*j.  Words past
-    // the tile's segments are never used as operands; they reload word 0.
+    // Byte offset (from tile_base, same channel) of strip word tid + 256*j.  Words
+    // past the tile's segments are never used as operands; they reload word 0.
     uint32_t soffb[JX];
 #pragma unroll
     for (int j = 0; j < JX; ++j) soffb[j] = 0;
@@ -69,46 +92,48 @@ __global__ __launch_bounds__(256, 3) void conv_mfma_fast_kernel(MfmaParams P)
         const int segoff = rho == 0 ? 0 : len0 + (rho - 1) * P.fullseg;
         const uint32_t img = fdiv(q, P.d_ho);
         const int mq = (int)(q - img * (uint32_t)P.Ho);
-        const uint32_t srcbase = (img * (uint32_t)P.Ci * (uint32_t)P.Ho + (uint32_t)mq) * (uint32_t)P.rowlen + (uint32_t)(nlo * sHf);
+        const size_t src = ((size_t)img * P.Ci * P.Ho + (size_t)mq) * (size_t)P.rowlen + (size_t)(nlo * sHf);
+        const uint32_t rel = (uint32_t)(src - tile_base);   // the host checked that a tile's rows span < 4 GiB
 #pragma unroll
         for (int j = 0; j < JX; ++j) {
             const int x = tid + 256 * j - segoff;
-            if (x >= 0 && x < seglen) soffb[j] = (srcbase + (uint32_t)x) * 4u;
+            if (x >= 0 && x < seglen) soffb[j] = (rel + (uint32_t)x) * 4u;
         }
     }
 
-    // ---- filter staging coordinates of this thread's float4 chunks ----
-    // The tile is MB rows x CPR chunks of 4 floats.  Chunk columns are dealt out
+    // ---- filter staging coordinates of this thread's chunks ----
+    // The tile is MB rows x CPR chunks of CW floats.  Chunk columns are dealt out
     // so that each dword LDS write of a half-wave is conflict-free with the odd
-    // row pitch: columns in groups of 8 (a half-wave = 4 consecutive rows x 8
-    // chunks: 128 contiguous bytes per row in global memory), the CPR % 8
-    // leftover columns one column x 32 rows per half-wave.
+    // row pitch: a half-wave covers CW consecutive rows x 32/CW chunk columns
+    // (128 contiguous bytes per row in global memory); the CPR % (32/CW) leftover
+    // columns go one column x 32 rows per half-wave.
     // Rows past Co feed accumulators that are never stored; they reload row 0.
-    constexpr int CG = CPR / 8;              // full groups of 8 chunk columns
-    constexpr int NMAIN = MB * CG * 8;       // chunks in full groups
+    constexpr int COLS = 32 / CW;              // chunk columns per half-wave
+    constexpr int CG = CPR / COLS;             // full column groups
+    constexpr int NMAIN = MB * CG * COLS;      // chunks in full groups
     uint32_t goffb[JF];
     int loff[JF];
 #pragma unroll
     for (int j = 0; j < JF; ++j) {
         const int f = tid + 256 * j;
-        int row, c4;
-        if (f < NMAIN) {
+        int row, cc;
+        if (CG > 0 && f < NMAIN) {
             const int g = f >> 5, w = f & 31;
-            row = 4 * (g / CG) + (w >> 3);
-            c4 = 8 * (g % CG) + (w & 7);
+            row = CW * (g / (CG > 0 ? CG : 1)) + (w / COLS);
+            cc = COLS * (g % (CG > 0 ? CG : 1)) + (w % COLS);
         } else {
             const int r = f - NMAIN;
             row = r % MB;
-            c4 = CG * 8 + r / MB;
+            cc = CG * COLS + r / MB;
         }
-        const int e = c4 * 4;
-        const bool live = (f < NF4) && (m0 + row < P.Co);
+        const int e = cc * CW;
+        const bool live = (f < NFC) && (m0 + row < P.Co);
         goffb[j] = live ? (uint32_t)(row * P.K + e) * 4u : 0u;
         loff[j] = row * PF + e;
     }
     // A thread with no chunk in the last round repeats its first chunk (same data to
     // the same place), which keeps the staging code free of branches.
-    if (tid + 256 * (JF - 1) >= NF4) { goffb[JF - 1] = goffb[0]; loff[JF - 1] = loff[0]; }
+    if (tid + 256 * (JF - 1) >= NFC) { goffb[JF - 1] = goffb[0]; loff[JF - 1] = loff[0]; }
 
     // ---- per-lane operand bases (stage 0) ----
     int b_base;
@@ -130,74 +155,85 @@ __global__ __launch_bounds__(256, 3) void conv_mfma_fast_kernel(MfmaParams P)
     // Prefetch registers: one set for the filter chunks (they come from L2), two
     // alternating sets for the strip words (they come from HBM and are given about
     // one and a half K blocks to arrive).
-    float4 fr[JF];
+    float fr[JF][CW];
     float ir[2][CB * JX];
     // Wave-uniform bases (kept in scalar registers) plus per-thread 32-bit byte
     // offsets that never change: the K loop spends no vector ALU work on addresses.
     const char *gf = reinterpret_cast<const char *>(P.flt + (size_t)m0 * P.K);
-    const char *gw = reinterpret_cast<const char *>(P.win);
+    const char *gw = reinterpret_cast<const char *>(P.win + tile_base);
     const size_t plane_bytes = (size_t)P.chan_stride * 4u;
 
     auto load_f = [&](int kb, int j) {
-        fr[j] = *reinterpret_cast<const float4 *>(gf + (size_t)kb * (KB * 4) + goffb[j]);
+        const char *src = gf + (size_t)kb * (KB * 4) + goffb[j];
+        if (CW == 4) {
+            const float4 w = *reinterpret_cast<const float4 *>(src);
+            fr[j][0] = w.x; fr[j][1] = w.y; fr[j][CW - 2] = w.z; fr[j][CW - 1] = w.w;
+        } else {
+            const float2 w = *reinterpret_cast<const float2 *>(src);
+            fr[j][0] = w.x; fr[j][1] = w.y;
+        }
     };
     auto load_i = [&](int kb, int set, int c, int j) {
         ir[set][c * JX + j] = *reinterpret_cast<const float *>(gw + ((size_t)kb * CB + c) * plane_bytes + soffb[j]);
     };
-    auto store_f = [&](int st, int j, int half) {   // half 0: words 0,1 of the chunk; half 1: words 2,3
+    auto store_f = [&](int st, int j, int half) {   // words 2*half, 2*half+1 of chunk j
         lds_float *d = (lds_float *)lds + st * STAGE + loff[j] + 2 * half;
-        d[0] = half ? fr[j].z : fr[j].x;
-        d[1] = half ? fr[j].w : fr[j].y;
+        d[0] = fr[j][2 * half];
+        d[1] = fr[j][2 * half + 1];
     };
     auto store_i = [&](int st, int set, int c, int j) {
         ((lds_float *)wI0)[st * STAGE + c * SS + 256 * j] = ir[set][c * JX + j];
     };
 
-    float a[2][KHW], b[2][KHW];
-    // operand pair t of channel pair pr, from LDS stage st, into register slot `slot`
-    auto lds_op = [&](int st, int pr, int slot, int t) {
-        const int u = t % HF, v = t / HF;   // window order: v outer, u inner; the filter is stored (u,v)
-        // volatile: keeps these as single-dword LDS reads with 16-bit immediate
-        // offsets; merged two-address reads would need a VALU add each for
-        // their 8-bit offsets, and VALU work comes out of the MFMA rate.
-        a[slot][t] = *(const volatile lds_float *)(ap0 + st * STAGE + 2 * pr * KHW + u * WF + v);
-        b[slot][t] = *(const volatile lds_float *)(bp0 + st * STAGE + 2 * pr * SS + t);
-    };
-
     // ---- one K block --------------------------------------------------------------
     // The wave issues its MFMAs as one dependent chain, so everything else is
     // placed, in program order, in the shadow of an MFMA: after MFMA i come the two
-    // operand reads for the same step of the next channel pair and one or two
+    // operand reads for step i+R (a ring of R register pairs) and one or two
     // staging instructions.  Block kb computes out of LDS stage ST, writes block
     // kb+1 (held in registers) to the other stage and requests block kb+2 from
-    // global memory.  The barrier sits before the last channel pair: its operands
-    // are already in registers, so after the barrier the other stage can be read
-    // (first operands of block kb+1) and, in the next block, this stage can be
-    // overwritten.  Scheduling barriers pin this order.
+    // global memory.  The barrier sits R steps before the end of the block: the
+    // operands of those last steps are already in registers, so after the barrier
+    // the other stage can be read (first operands of block kb+1) and, in the next
+    // block, this stage can be overwritten.  Scheduling barriers pin this order.
     constexpr int NG = CB / 2;            // channel pairs per block
     constexpr int NM = NG * KHW;          // MFMAs per block
-    constexpr int NSLOT = (NG - 1) * KHW; // MFMAs before the barrier
-    constexpr int NFW = 2 * JF;           // filter half-chunk stores
+    constexpr int NSLOT = NM - R;         // MFMAs before the barrier
+    constexpr int HPC = CW / 2;           // two-word stores per filter chunk
+    constexpr int NFW = HPC * JF;         // filter store slots
     constexpr int NIW = CB * JX;          // strip stores / loads
-    static_assert(NG % 2 == 0, "operand slots alternate per channel pair");
-    constexpr int NIWS = (NIW + 1) / 2;                       // slots that store strip words (two each)
+    constexpr int NIWS = (NIW + 1) / 2;   // slots that store strip words (two each)
+    static_assert(NM > R && NSLOT - NFW - NIWS > 0, "K block too short for the pipeline");
     constexpr int LPS = (NIW + (NSLOT - NFW - NIWS) - 1) / (NSLOT - NFW - NIWS);   // strip loads per slot
-    constexpr int NILS = (NIW + LPS - 1) / LPS;               // slots that load strip words
-    static_assert(NSLOT - NFW - NIWS > 0 && NFW + NIWS + NILS <= NSLOT, "staging work must fit before the barrier");
+    constexpr int NILS = (NIW + LPS - 1) / LPS;                                      // slots that load strip words
+    static_assert(NFW + NIWS + NILS <= NSLOT, "staging work must fit before the barrier");
+
+    float a[R], b[R];
+    // operands of step i (0 <= i < NM) of a block, from LDS stage st, into ring slot i % R
+    auto lds_op = [&](int st, int i) {
+        const int g = i / KHW, t = i % KHW;
+        const int u = t % HF, v = t / HF;   // window order: v outer, u inner; the filter is stored (u,v)
+        // volatile: keeps these as single-dword LDS reads with 16-bit immediate
+        // offsets (merged two-address reads have 8-bit offsets and would need a VALU
+        // add each -- and VALU work comes out of the MFMA rate).
+        a[i % R] = *(const volatile lds_float *)(ap0 + st * STAGE + 2 * g * KHW + u * WF + v);
+        b[i % R] = *(const volatile lds_float *)(bp0 + st * STAGE + 2 * g * SS + t);
+    };
+
     const int nkb = P.Ci / CB;
     auto block = [&](int kb, auto stc, auto has1c, auto has2c) {
         constexpr int ST = decltype(stc)::value;
         constexpr bool HAS1 = decltype(has1c)::value, HAS2 = decltype(has2c)::value;
 #pragma unroll
         for (int i = 0; i < NM; ++i) {
-            const int g = i / KHW, t = i % KHW;
             if (HAS1 && i == NSLOT) __syncthreads();
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[g & 1][t], b[g & 1][t], acc, 0, 0, 0);
-            if (g + 1 < NG) lds_op(ST, g + 1, (g + 1) & 1, t);
-            else if (HAS1) lds_op(ST ^ 1, 0, 0, t);
-            if (i < NFW) {                       // filter chunk i/2: store a half, then reload it
-                if (HAS1) store_f(ST ^ 1, i / 2, i & 1);
-                if (HAS2 && (i & 1)) load_f(kb + 2, i / 2);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i % R], b[i % R], acc, 0, 0, 0);
+            // ring slot i % R is free again: fetch the operands of step i + R (of this
+            // block, or of the next one out of the other stage)
+            if (i + R < NM) lds_op(ST, i + R);
+            else if (HAS1) lds_op(ST ^ 1, i + R - NM);
+            if (i < NFW) {                       // filter chunk i/HPC: store a half, then reload it
+                if (HAS1) store_f(ST ^ 1, i / HPC, i % HPC);
+                if (HAS2 && (i % HPC == HPC - 1)) load_f(kb + 2, i / HPC);
             } else if (i < NFW + NIWS) {   // strip words of block kb+1: two stores per slot
                 if (HAS1) {
                     const int w = 2 * (i - NFW);
@@ -227,7 +263,9 @@ __global__ __launch_bounds__(256, 3) void conv_mfma_fast_kernel(MfmaParams P)
 #pragma unroll
     for (int w = 0; w < NIW; ++w) load_i(0, 0, w / JX, w % JX);
 #pragma unroll
-    for (int j = 0; j < JF; ++j) { store_f(0, j, 0); store_f(0, j, 1); }
+    for (int j = 0; j < JF; ++j)
+#pragma unroll
+        for (int hh = 0; hh < HPC; ++hh) store_f(0, j, hh);
 #pragma unroll
     for (int w = 0; w < NIW; ++w) store_i(0, 0, w / JX, w % JX);
     if (nkb > 1) {
@@ -238,7 +276,7 @@ __global__ __launch_bounds__(256, 3) void conv_mfma_fast_kernel(MfmaParams P)
     }
     __syncthreads();
 #pragma unroll
-    for (int t = 0; t < KHW; ++t) lds_op(0, 0, 0, t);
+    for (int i = 0; i < R; ++i) lds_op(0, i);
 
     int kb = 0;
     for (; kb + 3 < nkb; kb += 2) {   // unrolled by two so that the stage is a constant
@@ -260,31 +298,43 @@ __global__ __launch_bounds__(256, 3) void conv_mfma_fast_kernel(MfmaParams P)
     store_tile(P, acc, P0, Pend, m0, wm, wn, h, l32);
 }
 
-template <int HF, int WF, int CB, int JX>
+template <int HF, int WF, int CB, int JX, int CW, int OCC>
 static hipError_t launch_fast_t(const MfmaParams &P, uint32_t blocks, hipStream_t st)
 {
     constexpr int KB = CB * HF * WF;
     constexpr int PF = KB | 1;
     constexpr size_t lds = 2u * 4u * (size_t)(((MB * PF + 3) & ~3) + CB * 256 * JX);
+    auto kern = &conv_mfma_fast_kernel<HF, WF, CB, JX, CW, OCC>;
     if (lds > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_mfma_fast_kernel<HF, WF, CB, JX>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL((conv_mfma_fast_kernel<HF, WF, CB, JX>), dim3(blocks), dim3(256), lds, st, P);
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3(256), lds, st, P);
     return hipGetLastError();
 }
 
 // Returns hipErrorNotSupported when the layer does not meet the fast path's conditions.
 hipError_t launch_conv_mfma_fast(MfmaParams P, const Shape &sh, uint32_t blocks, hipStream_t st)
 {
-    const bool aligned = (reinterpret_cast<uintptr_t>(P.flt) & 15u) == 0 && (sh.K % 4 == 0);
-    if (!aligned) return hipErrorNotSupported;
-    // strip words are addressed with 32-bit byte offsets from the start of the im2win tensor
-    if ((unsigned long long)sh.N * sh.Ci * sh.Ho * (unsigned long long)sh.rowlen * 4ull >= (1ull << 32)) return hipErrorNotSupported;
-    if (sh.Hf == 3 && sh.Wf == 3 && sh.Ci % 8 == 0) {
-        if (P.S <= 256) return launch_fast_t<3, 3, 8, 1>(P, blocks, st);
-        if (P.S <= 512) return launch_fast_t<3, 3, 8, 2>(P, blocks, st);
+    const uintptr_t fa = reinterpret_cast<uintptr_t>(P.flt);
+    const bool al16 = (fa & 15u) == 0 && (sh.K % 4 == 0);   // filter rows readable as aligned float4
+    const bool al8 = (fa & 7u) == 0 && (sh.K % 2 == 0);     // ... as aligned float2
+    // Strip words are addressed with 32-bit byte offsets from the tile's first strip word:
+    // the rows of a tile (at most P.rmax of them, in at most that many images) must span < 4 GiB.
+    const unsigned long long img_bytes = (unsigned long long)sh.Ci * sh.Ho * (unsigned long long)sh.rowlen * 4ull;
+    if (img_bytes * (unsigned long long)(P.rmax + 1) >= (1ull << 32)) return hipErrorNotSupported;
+    if (sh.Hf == 3 && sh.Wf == 3 && sh.Ci % 8 == 0 && al16) {
+        if (P.S <= 256) return launch_fast_t<3, 3, 8, 1, 4, 3>(P, blocks, st);
+        if (P.S <= 512) return launch_fast_t<3, 3, 8, 2, 4, 3>(P, blocks, st);
+    }
+    if (sh.Hf == 5 && sh.Wf == 5 && sh.Ci % 4 == 0 && al16) {
+        if (P.S <= 256) return launch_fast_t<5, 5, 4, 1, 4, 2>(P, blocks, st);
+        if (P.S <= 512) return launch_fast_t<5, 5, 4, 2, 4, 2>(P, blocks, st);
+    }
+    if (sh.Hf == 7 && sh.Wf == 7 && sh.Ci % 2 == 0 && al8) {
+        if (P.S <= 512) return launch_fast_t<7, 7, 2, 2, 2, 2>(P, blocks, st);
+        if (P.S <= 1024) return launch_fast_t<7, 7, 2, 4, 2, 2>(P, blocks, st);
     }
     return hipErrorNotSupported;
 }

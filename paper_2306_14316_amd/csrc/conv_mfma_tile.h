@@ -19,6 +19,7 @@ struct MfmaParams {
     uint32_t npix, howo, chan_stride;
     int cb;          // channels per K block
     int S;           // LDS floats reserved per channel strip
+    int rmax;        // output rows a tile may touch
     int fullseg;     // ((Wo-1)*s + Wf)*Hf : strip floats of a fully covered output row
     int tiles_m;
     int vec4;        // filter rows can be read as aligned float4 in every K block

@@ -36,6 +36,12 @@ EDGE_SHAPES = [
     (1, 4, 6, 70, 8, 1, 9, 1, 0),      # 1x9 filter: 9-element windows from one row
     (1, 4, 70, 6, 8, 9, 1, 1, 0),      # 9x1 filter
     (1, 2, 4, 300, 4, 3, 3, 1, 1),     # one very wide row
+    # multi-channel 5x5 and 7x7 layers: the pipelined kernel's other instances
+    (2, 8, 12, 12, 40, 5, 5, 1, 2),
+    (1, 12, 24, 24, 70, 5, 5, 1, 0),
+    (2, 4, 16, 100, 64, 7, 7, 2, 0),
+    (1, 2, 9, 140, 8, 7, 7, 2, 3),
+    (1, 6, 30, 70, 33, 7, 7, 2, 3),
     # three-channel layers with wide rows: the filter-stationary kernel
     (2, 3, 70, 150, 40, 7, 7, 2, 3),   # 7x7 s2, Co not a multiple of 32
     (3, 3, 20, 140, 64, 7, 7, 2, 0),
