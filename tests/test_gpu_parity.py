@@ -164,6 +164,33 @@ def test_transform_copies_bit_patterns():
         assert_bitwise_equal(dW, oracle.im2win(I.numpy(), Hf, Wf, s, p))
 
 
+# (N, Ci, Hi, Wi, Hf, s, p): tall windows over wide rows, the LDS-staged transform
+TALL_WINDOW_SHAPES = [
+    (2, 3, 37, 65, 5, 1, 0),     # odd row length: workgroup ranges start at every word offset mod 4
+    (1, 2, 50, 71, 7, 2, 3),     # Ho not a multiple of the rows per workgroup
+    (3, 1, 23, 64, 5, 6, 0),     # stride wider than the window: input rows skipped
+    (1, 2, 9, 90, 9, 1, 0),      # one output row per plane
+    (1, 1, 30, 500, 11, 4, 5),   # wide rows: few output rows fit the strip
+    (1, 1, 12, 1100, 9, 1, 1),   # a row too wide for any strip: falls back to the gather
+    (1, 1, 5, 64, 5, 1, 0),      # a single output row, fewer words than threads
+]
+
+
+@pytest.mark.parametrize("shape", TALL_WINDOW_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_transform_tall_windows(shape):
+    N, Ci, Hi, Wi, Hf, s, p = shape
+    I, _ = workloads.random_layer_inputs(8000 + sum(shape), N, Ci, Hi, Wi, 1, Hf, 1)
+    print("transform shape", shape, flush=True)
+    Ho, _ = im2win.im2win_out_shape(Hi, Wi, Hf, 1, s, p)
+    n = N * Ci * Ho * (Wi + 2 * p) * Hf
+    buf = torch.full((n + 64,), float("nan"), dtype=torch.float32, device="cuda")
+    win = buf[32:32 + n]                                   # 128-byte offset: stays 16-byte aligned
+    im2win.im2win_transform(I.cuda(), win, N, Ci, Hi, Wi, Hf, 1, s, p)
+    torch.cuda.synchronize()
+    assert_bitwise_equal(win.reshape(N, Ci, Ho, -1), oracle.im2win(I.numpy(), Hf, 1, s, p))
+    assert torch.isnan(buf[:32]).all() and torch.isnan(buf[32 + n:]).all()   # nothing written outside
+
+
 def test_transform_unaligned_output_pointer():
     """A window buffer that is only 4-byte aligned takes the scalar-store path."""
     N, Ci, Hi, Wi, Hf, Wf, s, p = 2, 3, 9, 10, 3, 3, 1, 1
