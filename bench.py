@@ -50,6 +50,9 @@ def parse_args():
                     help="also time the twelve layers of the paper's Table 2 at batch 128 (listed under 'table2')")
     ap.add_argument("--ablation", action="store_true",
                     help="also time the ablation variants of the convolution on the 3x3 layers (listed under 'ablation')")
+    ap.add_argument("--baselines", action="store_true",
+                    help="also time the comparison baselines (direct convolution; im2col + GEMM) on the five layers "
+                         "(listed under 'baselines')")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (known traffic) so that a rocprofv3 --pmc "
@@ -119,6 +122,18 @@ def time_layer(L, steps, warmup):
                 conv_alg_bytes=ws + 4 * Co * Ci * Hf * Wf + 4 * N * Co * L.Ho * L.Wo)
 
 
+def kernel_names(L):
+    """(convolution kernel, transform kernel) the library picks for a layer with aligned buffers."""
+    if L.Ci == 3 and (L.Hf, L.Wf) in ((3, 3), (7, 7), (11, 11)) and L.Wp * L.Hf >= 256:
+        conv = "conv_mfma_shallow_kernel"
+    elif (L.Hf, L.Wf) == (3, 3) and L.Ci % 8 == 0 or (L.Hf, L.Wf) == (5, 5) and L.Ci % 4 == 0 \
+            or (L.Hf, L.Wf) == (7, 7) and L.Ci % 2 == 0:
+        conv = "conv_mfma_fast_kernel"
+    else:
+        conv = "conv_mfma_kernel"
+    return conv, ("transform_lds_kernel" if L.Hf >= 5 and L.Wp >= 64 else "transform_kernel")
+
+
 def layer_report(L, t):
     fl = L.flops
     return {
@@ -168,6 +183,68 @@ def time_variants(L, steps):
         ms = e0.elapsed_time(e1) / k
         out[name] = {"conv_ms": ms, "conv_tflops": L.flops / (ms * 1e-3) / 1e12}
     return {"workload": L.name, "variants": out}
+
+
+def _ramp(fn, seconds=0.05):
+    import torch
+    t = time.perf_counter()
+    while time.perf_counter() - t < seconds:
+        for _ in range(5):
+            fn()
+        torch.cuda.synchronize()
+
+
+def _event_ms(fn, k):
+    import torch
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(k):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / k
+
+
+def time_baselines(L, steps):
+    """The comparison baselines on one layer, beside the im2win path (HIP events, average of
+    `steps` launches each): the direct convolution, and im2col followed by a GEMM."""
+    import torch
+    import paper_2306_14316_amd as im2win
+    from paper_2306_14316_amd import workloads
+    N, Ci, Hi, Wi, Co, Hf, Wf, s, p = L.dims
+    I, F = workloads.make_inputs(L)
+    dI, dF = I.cuda(), F.cuda()
+    dO = torch.empty((N, Co, L.Ho, L.Wo), dtype=torch.float32, device="cuda")
+    dW = torch.empty((N, Ci, L.Ho, L.Wp * Hf), dtype=torch.float32, device="cuda")
+    colb = im2win.im2col_footprint_bytes(N, Ci, Hi, Wi, Hf, Wf, s, p)
+    res = {"workload": L.name, "im2win_workspace_bytes": dW.numel() * 4, "im2col_workspace_bytes": colb}
+
+    def tf(ms):
+        return L.flops / (ms * 1e-3) / 1e12
+
+    f_t = lambda: im2win.im2win_transform(dI, dW, N, Ci, Hi, Wi, Hf, Wf, s, p)
+    f_c = lambda: im2win.conv2d_im2win_fwd(dW, dF, dO, N, Ci, Hi, Wi, Co, Hf, Wf, s, p)
+    f_t()
+    _ramp(f_c)
+    t_ms, c_ms = _event_ms(f_t, steps), _event_ms(f_c, steps)
+    res["im2win"] = {"transform_ms": t_ms, "conv_ms": c_ms, "conv_tflops": tf(c_ms), "total_tflops": tf(t_ms + c_ms)}
+
+    col = torch.empty(colb // 4, dtype=torch.float32, device="cuda")
+    f_i = lambda: im2win.im2col_transform(dI, col, N, Ci, Hi, Wi, Hf, Wf, s, p)
+    f_g = lambda: im2win.conv2d_im2col_fwd(col, dF, dO, N, Ci, Hi, Wi, Co, Hf, Wf, s, p)
+    f_i()
+    _ramp(f_g)
+    i_ms, g_ms = _event_ms(f_i, steps), _event_ms(f_g, steps)
+    res["im2col_gemm"] = {"transform_ms": i_ms, "conv_ms": g_ms, "conv_tflops": tf(g_ms), "total_tflops": tf(i_ms + g_ms)}
+    del col
+
+    f_d = lambda: im2win.conv2d_direct_fwd(dI, dF, dO, N, Ci, Hi, Wi, Co, Hf, Wf, s, p)
+    f_d()
+    d_ms = _event_ms(f_d, max(2, steps // 10))
+    res["direct"] = {"conv_ms": d_ms, "total_tflops": tf(d_ms)}
+    res["im2win_speedup_total"] = {"vs_im2col_gemm": (i_ms + g_ms) / (t_ms + c_ms), "vs_direct": d_ms / (t_ms + c_ms)}
+    return res
 
 
 def cpu_baseline(L):
@@ -229,11 +306,11 @@ def main():
         "workspace_bytes": t["workspace_bytes"], "im2col_bytes": t["im2col_bytes"],
         "conv_only_tflops": conv_tflops, "conv_only_tflops_best_of_steps": rep["conv_tflops_best"],
         "transform_gbs": rep["transform_gbs_avg"],
-        "roofline": {"kernel": "conv_mfma_fast_kernel" if (L.Hf == 3 and L.Wf == 3 and L.Ci % 8 == 0) else "conv_mfma_kernel", "bound": "mfma", "achieved": conv_tflops,
+        "roofline": {"kernel": kernel_names(L)[0], "bound": "mfma", "achieved": conv_tflops,
                      "peak": PEAK_FP32_MATRIX_TFLOPS, "unit": "TFLOP/s",
                      "frac": conv_tflops / PEAK_FP32_MATRIX_TFLOPS, "traffic": traffic,
                      "flops_per_launch": L.flops, "avg_launch_ms": t["conv_ms_avg"]},
-        "roofline_transform": {"kernel": "transform_kernel", "bound": "hbm", "achieved": rep["transform_gbs_avg"],
+        "roofline_transform": {"kernel": kernel_names(L)[1], "bound": "hbm", "achieved": rep["transform_gbs_avg"],
                                "peak": PEAK_HBM_GBS, "unit": "GB/s",
                                "frac": rep["transform_gbs_avg"] / PEAK_HBM_GBS,
                                "traffic": MEASURED_TRANSFORM_TRAFFIC_BYTES.get(L.name),
@@ -252,6 +329,8 @@ def main():
         out["layers"] = reps
     if a.ablation:
         out["ablation"] = [time_variants(workloads.layer(i), max(5, min(a.steps, 30))) for i in (2, 3)]
+    if a.baselines:
+        out["baselines"] = [time_baselines(l, max(5, min(a.steps, 20))) for l in workloads.LAYERS[1:]]
     if a.table2:
         out["table2"] = [layer_report(t2, time_layer(t2, max(5, min(a.steps, 20)), 3)) for t2 in workloads.TABLE2]
     if not a.no_cpu_baseline:

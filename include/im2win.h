@@ -25,7 +25,8 @@
  *     Calls only enqueue work on it and never synchronise.
  *   - Outputs are overwritten in full (no accumulation into them).
  *   - Errors are returned, never thrown; on any error nothing is launched.
- *   - Every tensor must have fewer than 2^31 elements (IM2WIN_ERR_OVERFLOW).
+ *   - Every tensor must have fewer than 2^31 elements (IM2WIN_ERR_OVERFLOW);
+ *     the baselines' im2col matrix alone may be larger (see there).
  */
 #ifndef IM2WIN_H_
 #define IM2WIN_H_
@@ -120,6 +121,35 @@ im2win_status conv2d_im2win_fwd_variant(const float *window_dev, const float *fi
                                         float *output_dev,
                                         int N, int Ci, int Hi, int Wi, int Co, int Hf, int Wf,
                                         int stride, int pad, int variant, void *stream);
+
+/*
+ * Comparison baselines (not part of the im2win path; same conventions).
+ *
+ * conv2d_direct_fwd: the direct convolution of Section 2.2 -- one thread per
+ * output element evaluates Eq. 1 from the NCHW input with no workspace.
+ *   input_dev   device, N*Ci*Hi*Wi floats, read only
+ *   filter_dev  device, Co*Ci*Hf*Wf floats, [Co][Ci][Hf][Wf]
+ *   output_dev  device, N*Co*Ho*Wo floats, fully overwritten
+ *
+ * im2col_transform + conv2d_im2col_fwd: the GEMM-based convolution of
+ * Section 2.3.  The im2col matrices of all images are stacked into
+ *   col[(i*Ho + m)*Wo + n][(r*Hf + u)*Wf + v] = Ipad(i, r, m*stride + u, n*stride + v),
+ * N*Ho*Wo rows of K = Ci*Hf*Wf floats, dense (im2col_footprint_bytes gives its
+ * size, which may pass 2^31 elements: the limit is 2^31 groups of four floats,
+ * IM2WIN_ERR_OVERFLOW beyond).  conv2d_im2col_fwd multiplies it with the filter
+ * matrix on the fp32 matrix cores and writes NCHW output.
+ *   col_dev     device, N*Ho*Wo*Ci*Hf*Wf floats; written by im2col_transform,
+ *               read by conv2d_im2col_fwd
+ */
+im2win_status conv2d_direct_fwd(const float *input_dev, const float *filter_dev, float *output_dev,
+                                int N, int Ci, int Hi, int Wi, int Co, int Hf, int Wf,
+                                int stride, int pad, void *stream);
+im2win_status im2col_transform(const float *input_dev, float *col_dev,
+                               int N, int Ci, int Hi, int Wi, int Hf, int Wf,
+                               int stride, int pad, void *stream);
+im2win_status conv2d_im2col_fwd(const float *col_dev, const float *filter_dev, float *output_dev,
+                                int N, int Ci, int Hi, int Wi, int Co, int Hf, int Wf,
+                                int stride, int pad, void *stream);
 
 /* Static description of a status code (never NULL). */
 const char *im2win_status_str(int status);

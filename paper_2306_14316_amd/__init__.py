@@ -7,6 +7,8 @@ is no CPU fallback: if the library is missing or no GPU is present, calls fail.
 """
 from .binding import (  # noqa: F401
     Im2winError,
+    conv2d_direct_fwd,
+    conv2d_im2col_fwd,
     conv2d_im2win_fwd,
     conv2d_im2win_fwd_basic,
     conv2d_im2win_fwd_variant,
@@ -14,6 +16,7 @@ from .binding import (  # noqa: F401
     VARIANT_NO_PIPELINE,
     VARIANT_NO_MFMA,
     im2col_footprint_bytes,
+    im2col_transform,
     im2win_out_shape,
     im2win_transform,
     im2win_workspace_bytes,

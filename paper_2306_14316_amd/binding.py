@@ -20,6 +20,9 @@ EXPORTS = (
     "conv2d_im2win_fwd",
     "conv2d_im2win_fwd_basic",
     "conv2d_im2win_fwd_variant",
+    "conv2d_direct_fwd",
+    "im2col_transform",
+    "conv2d_im2col_fwd",
     "im2win_status_str",
 )
 
@@ -50,9 +53,10 @@ def load_library():
         for name in ("im2win_workspace_bytes", "im2col_footprint_bytes"):
             getattr(lib, name).restype = i
             getattr(lib, name).argtypes = [i] * 8 + [sp]
-        lib.im2win_transform.restype = i
-        lib.im2win_transform.argtypes = [vp, vp] + [i] * 8 + [vp]
-        for name in ("conv2d_im2win_fwd", "conv2d_im2win_fwd_basic"):
+        for name in ("im2win_transform", "im2col_transform"):
+            getattr(lib, name).restype = i
+            getattr(lib, name).argtypes = [vp, vp] + [i] * 8 + [vp]
+        for name in ("conv2d_im2win_fwd", "conv2d_im2win_fwd_basic", "conv2d_direct_fwd", "conv2d_im2col_fwd"):
             getattr(lib, name).restype = i
             getattr(lib, name).argtypes = [vp, vp, vp] + [i] * 9 + [vp]
         lib.conv2d_im2win_fwd_variant.restype = i
@@ -151,3 +155,32 @@ def conv2d_im2win_fwd_variant(window, filter, output, N, Ci, Hi, Wi, Co, Hf, Wf,
     _check(load_library().conv2d_im2win_fwd_variant(w, f, o, N, Ci, Hi, Wi, Co, Hf, Wf, stride, pad,
                                                      int(variant), _stream(stream)),
            "conv2d_im2win_fwd_variant")
+
+
+def conv2d_direct_fwd(input, filter, output, N, Ci, Hi, Wi, Co, Hf, Wf, stride, pad, stream=None):
+    """output <- the direct convolution (baseline): one thread per output, no workspace."""
+    Ho, Wo = im2win_out_shape(Hi, Wi, Hf, Wf, stride, pad)
+    a = _dev_ptr(input, "input", N * Ci * Hi * Wi)
+    f = _dev_ptr(filter, "filter", Co * Ci * Hf * Wf)
+    o = _dev_ptr(output, "output", N * Co * Ho * Wo)
+    _check(load_library().conv2d_direct_fwd(a, f, o, N, Ci, Hi, Wi, Co, Hf, Wf, stride, pad, _stream(stream)),
+           "conv2d_direct_fwd")
+
+
+def im2col_transform(input, col, N, Ci, Hi, Wi, Hf, Wf, stride, pad, stream=None):
+    """col <- the stacked im2col matrices (baseline), N*Ho*Wo rows of Ci*Hf*Wf floats."""
+    Ho, Wo = im2win_out_shape(Hi, Wi, Hf, Wf, stride, pad)
+    a = _dev_ptr(input, "input", N * Ci * Hi * Wi)
+    c = _dev_ptr(col, "col", N * Ho * Wo * Ci * Hf * Wf)
+    _check(load_library().im2col_transform(a, c, N, Ci, Hi, Wi, Hf, Wf, stride, pad, _stream(stream)),
+           "im2col_transform")
+
+
+def conv2d_im2col_fwd(col, filter, output, N, Ci, Hi, Wi, Co, Hf, Wf, stride, pad, stream=None):
+    """output <- GEMM of the im2col matrix with the filter matrix (baseline)."""
+    Ho, Wo = im2win_out_shape(Hi, Wi, Hf, Wf, stride, pad)
+    c = _dev_ptr(col, "col", N * Ho * Wo * Ci * Hf * Wf)
+    f = _dev_ptr(filter, "filter", Co * Ci * Hf * Wf)
+    o = _dev_ptr(output, "output", N * Co * Ho * Wo)
+    _check(load_library().conv2d_im2col_fwd(c, f, o, N, Ci, Hi, Wi, Co, Hf, Wf, stride, pad, _stream(stream)),
+           "conv2d_im2col_fwd")

@@ -44,6 +44,13 @@ struct Shape {
 hipError_t launch_transform(const float *in, float *win, const Shape &sh, hipStream_t st);
 hipError_t launch_conv_basic(const float *win, const float *flt, float *out, const Shape &sh,
                              hipStream_t st);
+// Comparison baselines: direct convolution on the NCHW input; im2col matrix and GEMM over it.
+// The im2col launchers return hipErrorInvalidValue when the matrix has 2^31 or more 16-byte groups.
+hipError_t launch_conv_direct(const float *in, const float *flt, float *out, const Shape &sh,
+                              hipStream_t st);
+hipError_t launch_im2col(const float *in, float *col, const Shape &sh, hipStream_t st);
+hipError_t launch_gemm_im2col(const float *col, const float *flt, float *out, const Shape &sh,
+                              hipStream_t st);
 // Kernel selection for the MFMA convolution (the values of the public
 // IM2WIN_VARIANT_* constants).
 enum ConvVariant { kVariantDefault = 0, kVariantNoPipeline = 1, kVariantNoMfma = 2 };

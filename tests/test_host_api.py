@@ -90,6 +90,12 @@ def test_null_pointers_and_overflow(lib):
     # 2^31 or more elements in the im2win tensor / the output
     assert lib.im2win_transform(one, one, 4096, 64, 224, 224, 7, 7, 2, 0, None) == -3
     assert lib.conv2d_im2win_fwd(one, one, one, 128, 3, 1024, 1024, 64, 1, 1, 1, 0, None) == -3
+    # the baselines: NULL pointers, and an im2col matrix of 2^31 or more groups of four floats
+    assert lib.conv2d_direct_fwd(one, None, one, 1, 1, 4, 4, 1, 2, 2, 1, 0, None) == -1
+    assert lib.im2col_transform(one, None, 1, 1, 4, 4, 2, 2, 1, 0, None) == -1
+    assert lib.conv2d_im2col_fwd(None, one, one, 1, 1, 4, 4, 1, 2, 2, 1, 0, None) == -1
+    assert lib.im2col_transform(one, one, 512, 256, 112, 112, 3, 3, 1, 1, None) == -3
+    assert lib.conv2d_im2col_fwd(one, one, one, 512, 256, 112, 112, 8, 3, 3, 1, 1, None) == -3
     b = ctypes.c_size_t()
     assert lib.im2win_workspace_bytes(4096, 64, 224, 224, 7, 7, 2, 0, ctypes.byref(b)) == -3
     for code in (0, -1, -2, -3, -4, -5, 77):
