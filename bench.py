@@ -31,11 +31,15 @@ PEAK_HBM_GBS = 8000.0             # MI355X HBM3E
 # HBM traffic of one launch of each kernel, bytes, keyed by layer name: measured
 # with two rocprofv3 --pmc runs (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch)
 # of this script and scaled by what the same counters read for a plain 256 MiB
-# device copy (factors 2.000 and 1.000).  The summary with the commands is in
-# profiles/conv_mfma_fast_and_transform_cfg2_3x3_c64_56.md.  Layers that were
-# not measured report null.
-MEASURED_CONV_TRAFFIC_BYTES = {"cfg2_3x3_c64_56": 107315805}
-MEASURED_TRANSFORM_TRAFFIC_BYTES = {"cfg2_3x3_c64_56": 116533631}
+# device copy (factors 2.000 and 1.000).  The summaries with the commands are
+# profiles/conv_mfma_fast_and_transform_cfg2_3x3_c64_56.md (headline layer) and
+# profiles/all_layers_default_bench.md.  Layers that were not measured report null.
+MEASURED_CONV_TRAFFIC_BYTES = {
+    "cfg1_tiny_3x3": 202745, "cfg2_3x3_c64_56": 107272580, "cfg3_3x3_c256_14": 166375424,
+    "cfg4_7x7_s2_c3_224": 688753801, "cfg5_11x11_s4_c3_227": 643304105}
+MEASURED_TRANSFORM_TRAFFIC_BYTES = {
+    "cfg1_tiny_3x3": 68092, "cfg2_3x3_c64_56": 116521019, "cfg3_3x3_c256_14": 119028340,
+    "cfg4_7x7_s2_c3_224": 376826916, "cfg5_11x11_s4_c3_227": 322816558}
 
 
 def parse_args():
