@@ -197,6 +197,7 @@ hipError_t launch_conv_mfma(const float *win, const float *flt, float *out, cons
     P.npix = (uint32_t)sh.npix;
     P.howo = (uint32_t)(sh.Ho * sh.Wo);
     P.chan_stride = (uint32_t)((size_t)sh.Ho * sh.rowlen);
+    P.win_elems = (size_t)sh.N * sh.Ci * sh.Ho * (size_t)sh.rowlen;
     P.fullseg = ((sh.Wo - 1) * sh.s + sh.Wf) * sh.Hf;
     P.tiles_m = (sh.Co + MB - 1) / MB;
 

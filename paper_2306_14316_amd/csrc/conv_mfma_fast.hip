@@ -22,6 +22,8 @@
 namespace im2win {
 
 typedef __attribute__((address_space(3))) float lds_float;   // a float in LDS
+typedef float float4v __attribute__((ext_vector_type(4)));
+typedef float float2v __attribute__((ext_vector_type(2)));
 
 // MFMA operands are read from LDS R steps ahead, through a ring of R register
 // pairs; R divides the MFMAs per K block so that ring positions line up from one
@@ -157,24 +159,31 @@ __global__ __launch_bounds__(256, OCC) void conv_mfma_fast_kernel(MfmaParams P)
     // one and a half K blocks to arrive).
     float fr[JF][CW];
     float ir[2][CB * JX];
-    // Wave-uniform bases (kept in scalar registers) plus per-thread 32-bit byte
-    // offsets that never change: the K loop spends no vector ALU work on addresses.
-    const char *gf = reinterpret_cast<const char *>(P.flt + (size_t)m0 * P.K);
-    const char *gw = reinterpret_cast<const char *>(P.win + tile_base);
-    const size_t plane_bytes = (size_t)P.chan_stride * 4u;
+    // Global loads go through buffer descriptors: a wave-uniform base held in scalar
+    // registers (the filter rows of this M tile; the tile's first strip word), the
+    // thread's constant 32-bit byte offset, and a scalar offset that selects the K
+    // block and channel.  The K loop spends no vector ALU work on addresses.
+    // (The host has checked that a tile's strips lie within 4 GiB of its first word.)
+    const size_t flt_left = ((size_t)P.Co - (size_t)m0) * (size_t)P.K * 4u;
+    const size_t win_left = (P.win_elems - tile_base) * 4u;
+    const __amdgpu_buffer_rsrc_t rf = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float *>(P.flt + (size_t)m0 * P.K), 0, flt_left < 0xffffffffull ? flt_left : 0xffffffffull, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float *>(P.win + tile_base), 0, win_left < 0xffffffffull ? win_left : 0xffffffffull, 0x00020000);
+    const uint32_t plane_bytes = P.chan_stride * 4u;
 
     auto load_f = [&](int kb, int j) {
-        const char *src = gf + (size_t)kb * (KB * 4) + goffb[j];
         if (CW == 4) {
-            const float4 w = *reinterpret_cast<const float4 *>(src);
+            const float4v w = __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(rf, goffb[j], kb * (KB * 4), 0));
             fr[j][0] = w.x; fr[j][1] = w.y; fr[j][CW - 2] = w.z; fr[j][CW - 1] = w.w;
         } else {
-            const float2 w = *reinterpret_cast<const float2 *>(src);
+            const float2v w = __builtin_bit_cast(float2v, __builtin_amdgcn_raw_buffer_load_b64(rf, goffb[j], kb * (KB * 4), 0));
             fr[j][0] = w.x; fr[j][1] = w.y;
         }
     };
     auto load_i = [&](int kb, int set, int c, int j) {
-        ir[set][c * JX + j] = *reinterpret_cast<const float *>(gw + ((size_t)kb * CB + c) * plane_bytes + soffb[j]);
+        ir[set][c * JX + j] = __builtin_bit_cast(
+            float, __builtin_amdgcn_raw_buffer_load_b32(rw, soffb[j], (uint32_t)(kb * CB + c) * plane_bytes, 0));
     };
     auto store_f = [&](int st, int j, int half) {   // words 2*half, 2*half+1 of chunk j
         lds_float *d = (lds_float *)lds + st * STAGE + loff[j] + 2 * half;

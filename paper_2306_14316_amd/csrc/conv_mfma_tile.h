@@ -17,6 +17,7 @@ struct MfmaParams {
     int Ci, Ho, Wo, Co, Hf, Wf, s;
     int rowlen, khw, K;
     uint32_t npix, howo, chan_stride;
+    size_t win_elems;   // floats in the whole im2win tensor
     int cb;          // channels per K block
     int S;           // LDS floats reserved per channel strip
     int rmax;        // output rows a tile may touch
