@@ -49,6 +49,7 @@ struct ShallowParams {
     uint32_t npix, howo, chan_stride, ntiles;
     int fullseg;      // ((Wo-1)*s + Wf)*Hf
     int img_stride;   // Ci*Ho*rowlen : floats between the same row of consecutive images
+    size_t win_elems, out_elems;   // floats in the im2win tensor / the output
     FastDiv d_wo, d_ho, d_howo;
 };
 
@@ -77,7 +78,8 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
     extern __shared__ __align__(16) unsigned char smem[];
     lds_f32 *lds = (lds_f32 *)reinterpret_cast<float *>(smem);   // [2][STAGE] then the exchange area
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: kept in a scalar register
     const int ks = wave % KS, wm = (wave / KS) % WM, wn = wave / (KS * WM);
     const int h = lane >> 5, l32 = lane & 31;
     const int mrow = (int)blockIdx.y * (WM * 32) + wm * 32 + l32;   // this lane's filter row
@@ -137,11 +139,18 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
     uint32_t noff[JX];      // per thread: byte offset of its strip words from nbase
     float ir[NIW];          // per thread: the strip words in flight
     int nwpos = 0;          // per lane: LDS position of its window
-    float *no = P.out;      // per lane: output address of (pixel, first channel of the lane)
+    // Output stores go through a buffer descriptor whose base is wave-uniform (first
+    // channel of the wave, image of the tile's first pixel); the lane adds a 32-bit
+    // byte offset (its pixel, its first channel) and each store a scalar channel offset.
+    size_t nobase = 0;      // uniform: float offset of that base in the output
+    uint32_t nooff = 0;     // per lane: byte offset from the base
     int nroom = 0;          // per lane: number of channels it may store (<= 0: none)
+    bool nfull = false;     // uniform: every lane of the wave stores all of its channels
     // state of the tile being computed ("c") and of the one before it ("p")
     int cwpos = 0, croom = 0, proom = 0;
-    float *co = P.out, *po = P.out;
+    size_t cobase = 0, pobase = 0;
+    uint32_t cooff = 0, pooff = 0;
+    bool cfull = false, pfull = false;
     floatx16 acc[2];
     float own[8];           // (KS == 2) this wave's partial sums of that half, kept from the previous tile
 
@@ -149,7 +158,9 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
     const uint32_t tile0 = blockIdx.x * per;
     const uint32_t tile_end = min(tile0 + per, P.ntiles);
     if (tile0 >= tile_end) return;   // whole workgroup: no barrier is skipped by part of it
-    const int jl = (int)blockIdx.y * (WM * 32) + wm * 32 + 4 * h;   // first channel of this lane
+    const int jw = (int)blockIdx.y * (WM * 32) + wm * 32;   // first channel of this wave
+    const int jl = jw + 4 * h;                               // first channel of this lane
+    const uint32_t howo4 = P.howo * 4u;
 
     // One piece of the work for tile `t` (pieces are numbered in dependency order).
     auto piece = [&](auto pc, uint32_t t, int st_next, const floatx16 &pacc, int xpar) {
@@ -187,10 +198,14 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
             d = xc < nt2 ? d : nd2;
             noff[j] = (uint32_t)(xc + d) * 4u;
         } else if constexpr (p >= P_LD && p < P_WPOS) {
-            const char *gb = reinterpret_cast<const char *>(P.win + nbase);
+            // descriptor on the tile's first strip word; the channel is a scalar offset
+            const size_t left = (P.win_elems - nbase) * 4u;
+            const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(
+                const_cast<float *>(P.win + nbase), 0, left < 0xffffffffull ? left : 0xffffffffull, 0x00020000);
 #pragma unroll
             for (int w = 2 * (p - P_LD); w < 2 * (p - P_LD) + 2 && w < NIW; ++w)
-                ir[w] = *reinterpret_cast<const float *>(gb + (size_t)(w / JX) * P.chan_stride * 4u + noff[w % JX]);
+                ir[w] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+                                                      rw, noff[w % JX], (uint32_t)(w / JX) * P.chan_stride * 4u, 0));
         } else if constexpr (p == P_WPOS) {
             const uint32_t Pl = min(nP0 + (uint32_t)(wn * 32 + l32), nPend);
             const uint32_t ql = fdiv(Pl, P.d_wo);
@@ -202,21 +217,31 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
             const uint32_t Pc = min(Pm, nPend);
             const uint32_t img = fdiv(Pc, P.d_howo);
             const uint32_t pin = Pc - img * P.howo;
-            no = P.out + ((size_t)img * P.Co + jl) * P.howo + pin;
+            const uint32_t img0 = fdiv(nP0, P.d_howo);   // uniform
+            nobase = ((size_t)img0 * P.Co + jw) * P.howo;
+            nooff = ((img - img0) * (uint32_t)P.Co * P.howo + pin) * 4u + (uint32_t)(4 * h) * howo4;
             nroom = Pm <= nPend ? P.Co - jl : 0;
+            nfull = (nP0 + (uint32_t)(wn * 32 + 31) <= nPend) && (P.Co - jw >= 32);
         } else if constexpr (p >= P_ST && p < P_LDS) {
             // one output store of the previous tile
             constexpr int q = p - P_ST;
+            const size_t left = (P.out_elems - pobase) * 4u;
+            const __amdgpu_buffer_rsrc_t ro = __builtin_amdgcn_make_buffer_rsrc(
+                P.out + pobase, 0, left < 0xffffffffull ? left : 0xffffffffull, 0x00020000);
+            float val;
+            int dj;
             if (KS == 2) {
                 // add the partner's partial sum to this wave's (kept in own[]) first
                 const lds_f32 *theirs = lds + 2 * STAGE + xpar * (WM * 2 * 2 * 512) + ((wn * WM + wm) * 2 + (ks ^ 1)) * 512 + lane;
-                const float sum = own[q] + *(const volatile lds_f32 *)(theirs + q * 64);
-                const int dj = (ks ? 16 : 0) + 8 * (q >> 2) + (q & 3);
-                if (dj < proom) po[(size_t)dj * P.howo] = sum;
+                val = own[q] + *(const volatile lds_f32 *)(theirs + q * 64);
+                dj = (ks ? 16 : 0) + 8 * (q >> 2) + (q & 3);
             } else {
-                constexpr int dj = 8 * (q >> 2) + (q & 3);
-                if (dj < proom) po[(size_t)dj * P.howo] = pacc[q];
+                val = pacc[q];
+                dj = 8 * (q >> 2) + (q & 3);
             }
+            // pfull is wave-uniform: the common case takes no per-lane compare
+            if (pfull || dj < proom)
+                __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, val), ro, pooff, (uint32_t)dj * howo4, 0);
         } else if constexpr (p >= P_LDS && p < NP) {
             lds_f32 *d = lds + st_next * STAGE + tid;
 #pragma unroll
@@ -248,7 +273,7 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
         constexpr int PAR = decltype(parc)::value;      // tile parity: LDS stage, accumulator set
         constexpr int AP = (KS == 2) ? 0 : PAR;         // with KS == 2 only 8 sums outlive the chain (own[])
         // the fetched tile becomes the computed tile
-        cwpos = nwpos; co = no; croom = nroom;
+        cwpos = nwpos; cobase = nobase; cooff = nooff; croom = nroom; cfull = nfull;
         const uint32_t nxt = min(tile + 1, tile_end - 1);   // the last tile refetches itself (unused)
         const lds_f32 *sbase = lds + PAR * STAGE;
         const lds_f32 *bpair = sbase + cwpos + h * SS;
@@ -287,21 +312,24 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
                 pieces(std::integral_constant<int, plo>{}, std::integral_constant<int, phi>{}, nxt, PAR ^ 1, acc[AP ^ 1], PAR ^ 1);
                 __builtin_amdgcn_sched_barrier(0);
             });
+            if (KS == 2) {
+                // hand the partner the half of this tile's accumulators that it owns, keep the other
+                // (register indices are compile-time constants here: KSI is this wave's K share)
+                lds_f32 *mine = lds + 2 * STAGE + PAR * (WM * 2 * 2 * 512) + ((wn * WM + wm) * 2 + KSI) * 512 + lane;
+#pragma unroll
+                for (int v = 0; v < 8; ++v) mine[v * 64] = acc[0][KSI ? v : 8 + v];
+#pragma unroll
+                for (int v = 0; v < 8; ++v) own[v] = acc[0][KSI ? 8 + v : v];
+            }
         };
         if (KS == 1) {
             run(std::integral_constant<int, 0>{});
         } else {
             if (ks == 0) run(std::integral_constant<int, 0>{});
             else run(std::integral_constant<int, KS - 1>{});
-            // hand the partner the half of this tile's accumulators that it owns
-            lds_f32 *mine = lds + 2 * STAGE + PAR * (WM * 2 * 2 * 512) + ((wn * WM + wm) * 2 + ks) * 512 + lane;
-#pragma unroll
-            for (int v = 0; v < 8; ++v) mine[v * 64] = ks ? acc[0][v] : acc[0][8 + v];
-#pragma unroll
-            for (int v = 0; v < 8; ++v) own[v] = ks ? acc[0][8 + v] : acc[0][v];
         }
         // the computed tile becomes the previous tile
-        po = co; proom = croom;
+        pobase = cobase; pooff = cooff; proom = croom; pfull = cfull;
         __syncthreads();
     };
 
@@ -360,6 +388,8 @@ hipError_t launch_conv_mfma_shallow(const float *win, const float *flt, float *o
     // 32-bit strip offsets: the rows of one tile must lie within 2 GiB of each other
     const long long span = (long long)sh.Ci * sh.Ho * sh.rowlen * 4LL * (rmax + 1);
     if (span >= (1LL << 31)) return hipErrorNotSupported;
+    // 32-bit output offsets from (image of the tile's first pixel, wave's first channel): up to two images ahead
+    if (((long long)sh.Co * (SH_RMAX + 1) + 64) * sh.Ho * sh.Wo * 4LL >= (1LL << 32)) return hipErrorNotSupported;
 
     ShallowParams P;
     P.win = win; P.flt = flt; P.out = out;
@@ -371,6 +401,8 @@ hipError_t launch_conv_mfma_shallow(const float *win, const float *flt, float *o
     P.ntiles = (P.npix + NB - 1) / NB;
     P.fullseg = ((sh.Wo - 1) * sh.s + sh.Wf) * sh.Hf;
     P.img_stride = sh.Ci * sh.Ho * sh.rowlen;
+    P.win_elems = (size_t)sh.N * P.img_stride;
+    P.out_elems = (size_t)sh.npix * sh.Co;
     P.d_wo = make_fastdiv((uint32_t)sh.Wo);
     P.d_ho = make_fastdiv((uint32_t)sh.Ho);
     P.d_howo = make_fastdiv(P.howo);
