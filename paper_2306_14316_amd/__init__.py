@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     conv2d_im2win_fwd,
     conv2d_im2win_fwd_basic,
     conv2d_im2win_fwd_variant,
+    conv2d_im2win_implicit_fwd,
     VARIANT_DEFAULT,
     VARIANT_NO_PIPELINE,
     VARIANT_NO_MFMA,

@@ -20,6 +20,7 @@ EXPORTS = (
     "conv2d_im2win_fwd",
     "conv2d_im2win_fwd_basic",
     "conv2d_im2win_fwd_variant",
+    "conv2d_im2win_implicit_fwd",
     "conv2d_direct_fwd",
     "im2col_transform",
     "conv2d_im2col_fwd",
@@ -56,7 +57,8 @@ def load_library():
         for name in ("im2win_transform", "im2col_transform"):
             getattr(lib, name).restype = i
             getattr(lib, name).argtypes = [vp, vp] + [i] * 8 + [vp]
-        for name in ("conv2d_im2win_fwd", "conv2d_im2win_fwd_basic", "conv2d_direct_fwd", "conv2d_im2col_fwd"):
+        for name in ("conv2d_im2win_fwd", "conv2d_im2win_fwd_basic", "conv2d_direct_fwd", "conv2d_im2col_fwd",
+                     "conv2d_im2win_implicit_fwd"):
             getattr(lib, name).restype = i
             getattr(lib, name).argtypes = [vp, vp, vp] + [i] * 9 + [vp]
         lib.conv2d_im2win_fwd_variant.restype = i
@@ -155,6 +157,18 @@ def conv2d_im2win_fwd_variant(window, filter, output, N, Ci, Hi, Wi, Co, Hf, Wf,
     _check(load_library().conv2d_im2win_fwd_variant(w, f, o, N, Ci, Hi, Wi, Co, Hf, Wf, stride, pad,
                                                      int(variant), _stream(stream)),
            "conv2d_im2win_fwd_variant")
+
+
+def conv2d_im2win_implicit_fwd(input, filter, output, N, Ci, Hi, Wi, Co, Hf, Wf, stride, pad, stream=None):
+    """output <- the im2win convolution straight from the NCHW input (no workspace); raises
+    Im2winError (status -4) for layers outside the workspace-free kernel's shapes."""
+    Ho, Wo = im2win_out_shape(Hi, Wi, Hf, Wf, stride, pad)
+    a = _dev_ptr(input, "input", N * Ci * Hi * Wi)
+    f = _dev_ptr(filter, "filter", Co * Ci * Hf * Wf)
+    o = _dev_ptr(output, "output", N * Co * Ho * Wo)
+    _check(load_library().conv2d_im2win_implicit_fwd(a, f, o, N, Ci, Hi, Wi, Co, Hf, Wf, stride, pad,
+                                                      _stream(stream)),
+           "conv2d_im2win_implicit_fwd")
 
 
 def conv2d_direct_fwd(input, filter, output, N, Ci, Hi, Wi, Co, Hf, Wf, stride, pad, stream=None):

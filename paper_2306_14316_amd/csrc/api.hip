@@ -130,6 +130,19 @@ im2win_status conv2d_im2win_fwd_basic(const float *window_dev, const float *filt
     return e == hipSuccess ? IM2WIN_OK : IM2WIN_ERR_HIP;
 }
 
+im2win_status conv2d_im2win_implicit_fwd(const float *input_dev, const float *filter_dev, float *output_dev,
+                                         int N, int Ci, int Hi, int Wi, int Co, int Hf, int Wf, int stride, int pad,
+                                         void *stream)
+{
+    if (!input_dev || !filter_dev || !output_dev) return IM2WIN_ERR_NULL;
+    Shape sh;
+    im2win_status st = derive(N, Ci, Hi, Wi, Co, Hf, Wf, stride, pad, &sh);
+    if (st != IM2WIN_OK) return st;
+    hipError_t e = im2win::launch_conv_implicit(input_dev, filter_dev, output_dev, sh, (hipStream_t)stream);
+    if (e == hipErrorNotSupported || e == hipErrorInvalidConfiguration) return IM2WIN_ERR_UNSUPPORTED;
+    return e == hipSuccess ? IM2WIN_OK : IM2WIN_ERR_HIP;
+}
+
 im2win_status conv2d_direct_fwd(const float *input_dev, const float *filter_dev, float *output_dev,
                                 int N, int Ci, int Hi, int Wi, int Co, int Hf, int Wf, int stride, int pad,
                                 void *stream)
@@ -175,7 +188,7 @@ const char *im2win_status_str(int status)
         case IM2WIN_ERR_NULL: return "a required pointer is NULL";
         case IM2WIN_ERR_SHAPE: return "invalid shape: non-positive dimension, stride < 1, pad < 0 or filter larger than padded input";
         case IM2WIN_ERR_OVERFLOW: return "a tensor has 2^31 or more elements (im2col matrix: 2^31 or more groups of four)";
-        case IM2WIN_ERR_UNSUPPORTED: return "not supported: tile does not fit in LDS, or unknown kernel variant";
+        case IM2WIN_ERR_UNSUPPORTED: return "not supported: tile does not fit in LDS, unknown kernel variant, or layer outside the workspace-free kernel's shapes";
         case IM2WIN_ERR_HIP: return "HIP runtime error at launch";
         default: return "unknown status";
     }

@@ -51,6 +51,10 @@ hipError_t launch_conv_direct(const float *in, const float *flt, float *out, con
 hipError_t launch_im2col(const float *in, float *col, const Shape &sh, hipStream_t st);
 hipError_t launch_gemm_im2col(const float *col, const float *flt, float *out, const Shape &sh,
                               hipStream_t st);
+// Workspace-free convolution from the NCHW input; hipErrorNotSupported when the layer is not one the
+// pipelined kernel takes.
+hipError_t launch_conv_implicit(const float *in, const float *flt, float *out, const Shape &sh,
+                                hipStream_t st);
 // Kernel selection for the MFMA convolution (the values of the public
 // IM2WIN_VARIANT_* constants).
 enum ConvVariant { kVariantDefault = 0, kVariantNoPipeline = 1, kVariantNoMfma = 2 };

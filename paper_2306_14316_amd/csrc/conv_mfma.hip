@@ -186,11 +186,9 @@ static hipError_t launch_t(const MfmaParams &P, size_t lds, uint32_t blocks, hip
     return hipGetLastError();
 }
 
-hipError_t launch_conv_mfma(const float *win, const float *flt, float *out, const Shape &sh,
-                            hipStream_t st, int variant)
+// Tile-independent kernel parameters of a layer (everything but the generic kernel's K block).
+static void fill_params(MfmaParams &P, const float *win, const float *flt, float *out, const Shape &sh)
 {
-    if (variant == kVariantNoMfma) return launch_conv_basic(win, flt, out, sh, st);
-    MfmaParams P;
     P.win = win; P.flt = flt; P.out = out;
     P.Ci = sh.Ci; P.Ho = sh.Ho; P.Wo = sh.Wo; P.Co = sh.Co; P.Hf = sh.Hf; P.Wf = sh.Wf; P.s = sh.s;
     P.rowlen = sh.rowlen; P.khw = sh.khw; P.K = sh.K;
@@ -198,6 +196,8 @@ hipError_t launch_conv_mfma(const float *win, const float *flt, float *out, cons
     P.howo = (uint32_t)(sh.Ho * sh.Wo);
     P.chan_stride = (uint32_t)((size_t)sh.Ho * sh.rowlen);
     P.win_elems = (size_t)sh.N * sh.Ci * sh.Ho * (size_t)sh.rowlen;
+    P.Hi = sh.Hi; P.Wi = sh.Wi; P.p = sh.p;
+    P.in_plane = (uint32_t)(sh.Hi * sh.Wi);
     P.fullseg = ((sh.Wo - 1) * sh.s + sh.Wf) * sh.Hf;
     P.tiles_m = (sh.Co + MB - 1) / MB;
 
@@ -207,6 +207,34 @@ hipError_t launch_conv_mfma(const float *win, const float *flt, float *out, cons
     const int over = sh.Wf > sh.s ? sh.Wf - sh.s : 0;
     P.S = (NB * sh.s + rmax * over) * sh.Hf + 1;
     P.rmax = rmax;
+    P.cb = 0;
+    P.vec4 = 0;
+    P.d_wo = make_fastdiv((uint32_t)sh.Wo);
+    P.d_ho = make_fastdiv((uint32_t)sh.Ho);
+    P.d_howo = make_fastdiv(P.howo);
+    P.d_khw = make_fastdiv((uint32_t)sh.khw);
+    P.d_wf = make_fastdiv((uint32_t)sh.Wf);
+    P.d_cpr = make_fastdiv(1);
+    P.d_tm = make_fastdiv((uint32_t)P.tiles_m);
+}
+
+// Workspace-free convolution straight from the NCHW input (pipelined kernel only).
+hipError_t launch_conv_implicit(const float *in, const float *flt, float *out, const Shape &sh,
+                                hipStream_t st)
+{
+    MfmaParams P;
+    fill_params(P, in, flt, out, sh);
+    P.win_elems = (size_t)sh.N * sh.Ci * sh.Hi * (size_t)sh.Wi;   // the tensor P.win points at is the input
+    const uint32_t blocks = ((P.npix + NB - 1) / NB) * (uint32_t)P.tiles_m;
+    return launch_conv_mfma_fast(P, sh, blocks, st, true);
+}
+
+hipError_t launch_conv_mfma(const float *win, const float *flt, float *out, const Shape &sh,
+                            hipStream_t st, int variant)
+{
+    if (variant == kVariantNoMfma) return launch_conv_basic(win, flt, out, sh, st);
+    MfmaParams P;
+    fill_params(P, win, flt, out, sh);
 
     const size_t lds_max = 160 * 1024;
     int cb = sh.Ci < 8 ? sh.Ci : 8;
@@ -217,13 +245,7 @@ hipError_t launch_conv_mfma(const float *win, const float *flt, float *out, cons
 
     P.vec4 = (sh.Ci % cb == 0) && ((cb * sh.khw) % 4 == 0) && (sh.K % 4 == 0) &&
              ((reinterpret_cast<uintptr_t>(flt) & 15u) == 0);
-    P.d_wo = make_fastdiv((uint32_t)sh.Wo);
-    P.d_ho = make_fastdiv((uint32_t)sh.Ho);
-    P.d_howo = make_fastdiv(P.howo);
-    P.d_khw = make_fastdiv((uint32_t)sh.khw);
-    P.d_wf = make_fastdiv((uint32_t)sh.Wf);
     P.d_cpr = make_fastdiv((uint32_t)((cb * sh.khw) / 4 > 0 ? (cb * sh.khw) / 4 : 1));
-    P.d_tm = make_fastdiv((uint32_t)P.tiles_m);
 
     const uint32_t tiles_n = (P.npix + NB - 1) / NB;
     const uint32_t blocks = tiles_n * (uint32_t)P.tiles_m;

@@ -38,7 +38,11 @@ constexpr int pick_ring(int nm)
 
 // CW: floats per filter staging chunk (4: 16-byte loads, 2: 8-byte loads).
 // OCC: workgroups per CU the register allocation should leave room for.
-template <int HF, int WF, int CB, int JX, int CW, int OCC>
+// IMP: workspace-free variant.  P.win is the NCHW input; the tile's im2win strips
+// (Section 3.1) are built directly in LDS -- same LDS layout, same MFMA loop -- by
+// gathering input rows: strip word k*HF + u of output row m comes from input row
+// m*s + u - p, column k - p (zero outside the image).
+template <int HF, int WF, int CB, int JX, int CW, int OCC, bool IMP>
 __global__ __launch_bounds__(256, OCC) void conv_mfma_fast_kernel(MfmaParams P)
 {
     constexpr int KHW = HF * WF;
@@ -77,15 +81,23 @@ __global__ __launch_bounds__(256, OCC) void conv_mfma_fast_kernel(MfmaParams P)
     const int sHf = P.s * HF;
     const int len0 = (((q1 == q0) ? (int)(Pend - P0) : (P.Wo - 1 - nlo0)) * P.s + WF) * HF;
     // float offset, in channel plane 0, of the first strip word of the tile
+    // (workspace-free variant: of the tile's first image in the input)
     const uint32_t img0 = fdiv(q0, P.d_ho);
-    const size_t tile_base = ((size_t)img0 * P.Ci * P.Ho + (q0 - img0 * (uint32_t)P.Ho)) * (size_t)P.rowlen +
-                             (size_t)(nlo0 * sHf);
+    const size_t tile_base =
+        IMP ? (size_t)img0 * P.Ci * P.in_plane
+            : ((size_t)img0 * P.Ci * P.Ho + (q0 - img0 * (uint32_t)P.Ho)) * (size_t)P.rowlen + (size_t)(nlo0 * sHf);
 
     // Byte offset (from tile_base, same channel) of strip word tid + 256*j.  Words
     // past the tile's segments are never used as operands; they reload word 0.
+    // Workspace-free variant: thread word tid + 256*j of a segment is taken row by
+    // row of the input (u outer, column inner: neighbouring lanes read neighbouring
+    // input words) and lands at LDS strip position loffI; words that fall in the
+    // zero padding (and unused ones) load word 0 and store +0.0.
     uint32_t soffb[JX];
+    int loffI[JX];
+    bool zero[JX];
 #pragma unroll
-    for (int j = 0; j < JX; ++j) soffb[j] = 0;
+    for (int j = 0; j < JX; ++j) { soffb[j] = 0; loffI[j] = tid + 256 * j; zero[j] = IMP; }
     for (uint32_t q = q0; q <= q1; ++q) {
         const int rho = (int)(q - q0);
         const int nlo = rho == 0 ? nlo0 : 0;
@@ -94,12 +106,32 @@ __global__ __launch_bounds__(256, OCC) void conv_mfma_fast_kernel(MfmaParams P)
         const int segoff = rho == 0 ? 0 : len0 + (rho - 1) * P.fullseg;
         const uint32_t img = fdiv(q, P.d_ho);
         const int mq = (int)(q - img * (uint32_t)P.Ho);
-        const size_t src = ((size_t)img * P.Ci * P.Ho + (size_t)mq) * (size_t)P.rowlen + (size_t)(nlo * sHf);
-        const uint32_t rel = (uint32_t)(src - tile_base);   // the host checked that a tile's rows span < 4 GiB
+        if (!IMP) {
+            const size_t src = ((size_t)img * P.Ci * P.Ho + (size_t)mq) * (size_t)P.rowlen + (size_t)(nlo * sHf);
+            const uint32_t rel = (uint32_t)(src - tile_base);   // the host checked that a tile's rows span < 4 GiB
 #pragma unroll
-        for (int j = 0; j < JX; ++j) {
-            const int x = tid + 256 * j - segoff;
-            if (x >= 0 && x < seglen) soffb[j] = (rel + (uint32_t)x) * 4u;
+            for (int j = 0; j < JX; ++j) {
+                const int x = tid + 256 * j - segoff;
+                if (x >= 0 && x < seglen) soffb[j] = (rel + (uint32_t)x) * 4u;
+            }
+        } else {
+            const int ncol = (nhi - nlo) * P.s + WF;
+            const uint32_t rel = (img - img0) * (uint32_t)P.Ci * P.in_plane;   // host: a tile's images span < 4 GiB
+#pragma unroll
+            for (int j = 0; j < JX; ++j) {
+                const int x = tid + 256 * j - segoff;
+                if (x >= 0 && x < seglen) {
+                    int u = 0;
+#pragma unroll
+                    for (int t = 1; t < HF; ++t) u += (x >= t * ncol) ? 1 : 0;
+                    const int kk = x - u * ncol;
+                    const int hh = mq * P.s + u - P.p, ww = nlo * P.s + kk - P.p;
+                    const bool inside = (hh >= 0) & (hh < P.Hi) & (ww >= 0) & (ww < P.Wi);
+                    loffI[j] = segoff + kk * HF + u;
+                    zero[j] = !inside;
+                    soffb[j] = inside ? (rel + (uint32_t)(hh * P.Wi + ww)) * 4u : 0u;
+                }
+            }
         }
     }
 
@@ -165,12 +197,12 @@ __global__ __launch_bounds__(256, OCC) void conv_mfma_fast_kernel(MfmaParams P)
     // block and channel.  The K loop spends no vector ALU work on addresses.
     // (The host has checked that a tile's strips lie within 4 GiB of its first word.)
     const size_t flt_left = ((size_t)P.Co - (size_t)m0) * (size_t)P.K * 4u;
-    const size_t win_left = (P.win_elems - tile_base) * 4u;
+    const size_t win_left = (P.win_elems - tile_base) * 4u;   // (P.win_elems: floats in the tensor P.win points at)
     const __amdgpu_buffer_rsrc_t rf = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<float *>(P.flt + (size_t)m0 * P.K), 0, flt_left < 0xffffffffull ? flt_left : 0xffffffffull, 0x00020000);
     const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<float *>(P.win + tile_base), 0, win_left < 0xffffffffull ? win_left : 0xffffffffull, 0x00020000);
-    const uint32_t plane_bytes = P.chan_stride * 4u;
+    const uint32_t plane_bytes = (IMP ? P.in_plane : P.chan_stride) * 4u;
 
     auto load_f = [&](int kb, int j) {
         if (CW == 4) {
@@ -191,7 +223,10 @@ __global__ __launch_bounds__(256, OCC) void conv_mfma_fast_kernel(MfmaParams P)
         d[1] = fr[j][2 * half + 1];
     };
     auto store_i = [&](int st, int set, int c, int j) {
-        ((lds_float *)wI0)[st * STAGE + c * SS + 256 * j] = ir[set][c * JX + j];
+        if (IMP)
+            ((lds_float *)lds)[SF_FLOATS + loffI[j] + st * STAGE + c * SS] = zero[j] ? 0.0f : ir[set][c * JX + j];
+        else
+            ((lds_float *)wI0)[st * STAGE + c * SS + 256 * j] = ir[set][c * JX + j];
     };
 
     // ---- one K block --------------------------------------------------------------
@@ -308,12 +343,15 @@ __global__ __launch_bounds__(256, OCC) void conv_mfma_fast_kernel(MfmaParams P)
 }
 
 template <int HF, int WF, int CB, int JX, int CW, int OCC>
+static hipError_t launch_fast_i(const MfmaParams &P, uint32_t blocks, hipStream_t st, bool implicit);
+
+template <int HF, int WF, int CB, int JX, int CW, int OCC, bool IMP = false>
 static hipError_t launch_fast_t(const MfmaParams &P, uint32_t blocks, hipStream_t st)
 {
     constexpr int KB = CB * HF * WF;
     constexpr int PF = KB | 1;
     constexpr size_t lds = 2u * 4u * (size_t)(((MB * PF + 3) & ~3) + CB * 256 * JX);
-    auto kern = &conv_mfma_fast_kernel<HF, WF, CB, JX, CW, OCC>;
+    auto kern = &conv_mfma_fast_kernel<HF, WF, CB, JX, CW, OCC, IMP>;
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -323,27 +361,38 @@ static hipError_t launch_fast_t(const MfmaParams &P, uint32_t blocks, hipStream_
     return hipGetLastError();
 }
 
+template <int HF, int WF, int CB, int JX, int CW, int OCC>
+static hipError_t launch_fast_i(const MfmaParams &P, uint32_t blocks, hipStream_t st, bool implicit)
+{
+    return implicit ? launch_fast_t<HF, WF, CB, JX, CW, OCC, true>(P, blocks, st)
+                    : launch_fast_t<HF, WF, CB, JX, CW, OCC, false>(P, blocks, st);
+}
+
 // Returns hipErrorNotSupported when the layer does not meet the fast path's conditions.
-hipError_t launch_conv_mfma_fast(MfmaParams P, const Shape &sh, uint32_t blocks, hipStream_t st)
+// implicit: P.win is the NCHW input (P.Hi, P.Wi, P.p, P.in_plane set; P.win_elems = its size).
+hipError_t launch_conv_mfma_fast(MfmaParams P, const Shape &sh, uint32_t blocks, hipStream_t st, bool implicit)
 {
     const uintptr_t fa = reinterpret_cast<uintptr_t>(P.flt);
     const bool al16 = (fa & 15u) == 0 && (sh.K % 4 == 0);   // filter rows readable as aligned float4
     const bool al8 = (fa & 7u) == 0 && (sh.K % 2 == 0);     // ... as aligned float2
-    // Strip words are addressed with 32-bit byte offsets from the tile's first strip word:
-    // the rows of a tile (at most P.rmax of them, in at most that many images) must span < 4 GiB.
-    const unsigned long long img_bytes = (unsigned long long)sh.Ci * sh.Ho * (unsigned long long)sh.rowlen * 4ull;
+    // Strip words are addressed with 32-bit byte offsets from the tile's first strip word (from
+    // its first image in the workspace-free variant): the rows of a tile (at most P.rmax of
+    // them, in at most that many images) must span < 4 GiB.
+    const unsigned long long img_bytes =
+        implicit ? (unsigned long long)sh.Ci * sh.Hi * (unsigned long long)sh.Wi * 4ull
+                 : (unsigned long long)sh.Ci * sh.Ho * (unsigned long long)sh.rowlen * 4ull;
     if (img_bytes * (unsigned long long)(P.rmax + 1) >= (1ull << 32)) return hipErrorNotSupported;
     if (sh.Hf == 3 && sh.Wf == 3 && sh.Ci % 8 == 0 && al16) {
-        if (P.S <= 256) return launch_fast_t<3, 3, 8, 1, 4, 3>(P, blocks, st);
-        if (P.S <= 512) return launch_fast_t<3, 3, 8, 2, 4, 3>(P, blocks, st);
+        if (P.S <= 256) return launch_fast_i<3, 3, 8, 1, 4, 3>(P, blocks, st, implicit);
+        if (P.S <= 512) return launch_fast_i<3, 3, 8, 2, 4, 3>(P, blocks, st, implicit);
     }
     if (sh.Hf == 5 && sh.Wf == 5 && sh.Ci % 4 == 0 && al16) {
-        if (P.S <= 256) return launch_fast_t<5, 5, 4, 1, 4, 2>(P, blocks, st);
-        if (P.S <= 512) return launch_fast_t<5, 5, 4, 2, 4, 2>(P, blocks, st);
+        if (P.S <= 256) return launch_fast_i<5, 5, 4, 1, 4, 2>(P, blocks, st, implicit);
+        if (P.S <= 512) return launch_fast_i<5, 5, 4, 2, 4, 2>(P, blocks, st, implicit);
     }
     if (sh.Hf == 7 && sh.Wf == 7 && sh.Ci % 2 == 0 && al8) {
-        if (P.S <= 512) return launch_fast_t<7, 7, 2, 2, 2, 2>(P, blocks, st);
-        if (P.S <= 1024) return launch_fast_t<7, 7, 2, 4, 2, 2>(P, blocks, st);
+        if (P.S <= 512) return launch_fast_i<7, 7, 2, 2, 2, 2>(P, blocks, st, implicit);
+        if (P.S <= 1024) return launch_fast_i<7, 7, 2, 4, 2, 2>(P, blocks, st, implicit);
     }
     return hipErrorNotSupported;
 }

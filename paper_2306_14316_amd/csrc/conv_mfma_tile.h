@@ -18,6 +18,9 @@ struct MfmaParams {
     int rowlen, khw, K;
     uint32_t npix, howo, chan_stride;
     size_t win_elems;   // floats in the whole im2win tensor
+    // workspace-free variant only: `win` is then the NCHW input itself
+    int Hi, Wi, p;
+    uint32_t in_plane;  // Hi*Wi
     int cb;          // channels per K block
     int S;           // LDS floats reserved per channel strip
     int rmax;        // output rows a tile may touch
@@ -60,7 +63,8 @@ __device__ __forceinline__ void store_tile(const MfmaParams &P, const floatx16 &
     }
 }
 
-hipError_t launch_conv_mfma_fast(MfmaParams P, const Shape &sh, uint32_t blocks, hipStream_t st);
+hipError_t launch_conv_mfma_fast(MfmaParams P, const Shape &sh, uint32_t blocks, hipStream_t st,
+                                 bool implicit = false);
 hipError_t launch_conv_mfma_shallow(const float *win, const float *flt, float *out, const Shape &sh,
                                     hipStream_t st);
 
