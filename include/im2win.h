@@ -43,9 +43,8 @@ typedef enum {
     IM2WIN_ERR_SHAPE = -2,       /* a dimension <= 0, stride < 1, pad < 0, or the filter */
                                  /* is larger than the padded input                      */
     IM2WIN_ERR_OVERFLOW = -3,    /* a tensor has 2^31 or more elements                   */
-    IM2WIN_ERR_UNSUPPORTED = -4, /* shape needs more LDS than one workgroup can hold, an  */
-                                 /* unknown kernel variant was requested, or the layer   */
-                                 /* is outside what the workspace-free variant takes     */
+    IM2WIN_ERR_UNSUPPORTED = -4, /* shape needs more LDS than one workgroup can hold, or */
+                                 /* an unknown kernel variant was requested              */
     IM2WIN_ERR_HIP = -5          /* the HIP runtime refused the launch                   */
 } im2win_status;
 
@@ -128,10 +127,11 @@ im2win_status conv2d_im2win_fwd_variant(const float *window_dev, const float *fi
  * input.  Each workgroup builds the im2win strips of its tile (Section 3.1, Eq. 2)
  * in LDS instead of reading them from an im2win tensor, so no workspace and no
  * transform call are needed; the MFMA loop and the result are those of
- * conv2d_im2win_fwd.  Available for the layers the pipelined kernel takes --
- * 3x3 filters with Ci a multiple of 8, 5x5 with Ci a multiple of 4, 7x7 with Ci
- * even, filter_dev 16-byte aligned, a 64-pixel tile spanning at most ~1000
- * strip floats -- and IM2WIN_ERR_UNSUPPORTED otherwise (nothing is launched).
+ * conv2d_im2win_fwd.  Any layer is accepted.  Layers the pipelined kernel takes
+ * (3x3 filters with Ci a multiple of 8, 5x5 with Ci a multiple of 4, 7x7 with
+ * Ci even, filter_dev 16-byte aligned) run at the speed of conv2d_im2win_fwd
+ * alone; the others (three-channel stem layers among them) take the generic,
+ * unpipelined kernel and are slower than the two-call path.
  *   input_dev   device, N*Ci*Hi*Wi floats, read only
  *   filter_dev  device, Co*Ci*Hf*Wf floats, [Co][Ci][Hf][Wf]
  *   output_dev  device, N*Co*Ho*Wo floats, fully overwritten

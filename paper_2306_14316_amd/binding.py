@@ -160,8 +160,7 @@ def conv2d_im2win_fwd_variant(window, filter, output, N, Ci, Hi, Wi, Co, Hf, Wf,
 
 
 def conv2d_im2win_implicit_fwd(input, filter, output, N, Ci, Hi, Wi, Co, Hf, Wf, stride, pad, stream=None):
-    """output <- the im2win convolution straight from the NCHW input (no workspace); raises
-    Im2winError (status -4) for layers outside the workspace-free kernel's shapes."""
+    """output <- the im2win convolution straight from the NCHW input (no workspace)."""
     Ho, Wo = im2win_out_shape(Hi, Wi, Hf, Wf, stride, pad)
     a = _dev_ptr(input, "input", N * Ci * Hi * Wi)
     f = _dev_ptr(filter, "filter", Co * Ci * Hf * Wf)

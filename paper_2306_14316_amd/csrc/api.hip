@@ -188,7 +188,7 @@ const char *im2win_status_str(int status)
         case IM2WIN_ERR_NULL: return "a required pointer is NULL";
         case IM2WIN_ERR_SHAPE: return "invalid shape: non-positive dimension, stride < 1, pad < 0 or filter larger than padded input";
         case IM2WIN_ERR_OVERFLOW: return "a tensor has 2^31 or more elements (im2col matrix: 2^31 or more groups of four)";
-        case IM2WIN_ERR_UNSUPPORTED: return "not supported: tile does not fit in LDS, unknown kernel variant, or layer outside the workspace-free kernel's shapes";
+        case IM2WIN_ERR_UNSUPPORTED: return "not supported: tile does not fit in LDS, or unknown kernel variant";
         case IM2WIN_ERR_HIP: return "HIP runtime error at launch";
         default: return "unknown status";
     }

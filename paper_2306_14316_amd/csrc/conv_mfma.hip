@@ -67,8 +67,21 @@ __global__ __launch_bounds__(256) void conv_mfma_kernel(MfmaParams P)
         const int segoff = rho == 0 ? 0 : len0 + (rho - 1) * P.fullseg;
         const uint32_t img = fdiv(q, P.d_ho);
         const int mq = (int)(q - img * (uint32_t)P.Ho);
-        const int srcbase = (int)((img * (uint32_t)P.Ci * (uint32_t)P.Ho + (uint32_t)mq) * (uint32_t)P.rowlen) + nlo * sHf;
-        for (int x = tid; x < seglen; x += 256) tbl[segoff + x] = srcbase + x;
+        if (!P.implicit) {
+            const int srcbase = (int)((img * (uint32_t)P.Ci * (uint32_t)P.Ho + (uint32_t)mq) * (uint32_t)P.rowlen) + nlo * sHf;
+            for (int x = tid; x < seglen; x += 256) tbl[segoff + x] = srcbase + x;
+        } else {
+            // Workspace-free variant: P.win is the NCHW input.  Strip word kk*Hf + u of this
+            // row is input row mq*s + u - p, column nlo*s + kk - p (Eq. 2), or zero padding.
+            const int ncol = (nhi - nlo) * P.s + P.Wf;
+            const int imgbase = (int)(img * (uint32_t)P.Ci * P.in_plane);
+            for (int x = tid; x < seglen; x += 256) {
+                const int u = x / ncol, kk = x - u * ncol;
+                const int hh = mq * P.s + u - P.p, ww = nlo * P.s + kk - P.p;
+                const bool inside = (hh >= 0) & (hh < P.Hi) & (ww >= 0) & (ww < P.Wi);
+                tbl[segoff + kk * P.Hf + u] = inside ? imgbase + hh * P.Wi + ww : -1;
+            }
+        }
         filled = segoff + seglen;
     }
     for (int x = filled + tid; x < S; x += 256) tbl[x] = -1;
@@ -103,7 +116,7 @@ __global__ __launch_bounds__(256) void conv_mfma_kernel(MfmaParams P)
 
         // ---- stage the im2win strips of nch channels ----
         for (int c = wave; c < nch; c += 4) {
-            const float *g = P.win + (size_t)(c0 + c) * P.chan_stride;
+            const float *g = P.win + (size_t)(c0 + c) * (P.implicit ? P.in_plane : P.chan_stride);
             float *d = sI + c * S;
             for (int x = lane; x < S; x += 64) {
                 const int off = tbl[x];
@@ -196,6 +209,7 @@ static void fill_params(MfmaParams &P, const float *win, const float *flt, float
     P.howo = (uint32_t)(sh.Ho * sh.Wo);
     P.chan_stride = (uint32_t)((size_t)sh.Ho * sh.rowlen);
     P.win_elems = (size_t)sh.N * sh.Ci * sh.Ho * (size_t)sh.rowlen;
+    P.implicit = 0;
     P.Hi = sh.Hi; P.Wi = sh.Wi; P.p = sh.p;
     P.in_plane = (uint32_t)(sh.Hi * sh.Wi);
     P.fullseg = ((sh.Wo - 1) * sh.s + sh.Wf) * sh.Hf;
@@ -218,15 +232,39 @@ static void fill_params(MfmaParams &P, const float *win, const float *flt, float
     P.d_tm = make_fastdiv((uint32_t)P.tiles_m);
 }
 
-// Workspace-free convolution straight from the NCHW input (pipelined kernel only).
+// The generic kernel: picks the channels per K block that fit in LDS and launches.
+static hipError_t launch_generic(MfmaParams &P, const Shape &sh, uint32_t blocks, hipStream_t st)
+{
+    const size_t lds_max = 160 * 1024;
+    int cb = sh.Ci < 8 ? sh.Ci : 8;
+    while (cb > 1 && lds_bytes(cb, P.S, sh.khw) > lds_max) cb = (cb > 2) ? (((cb / 2) & ~1) < 2 ? 2 : ((cb / 2) & ~1)) : 1;
+    if (lds_bytes(cb, P.S, sh.khw) > lds_max) return hipErrorInvalidConfiguration;
+    P.cb = cb;
+    const size_t lds = lds_bytes(cb, P.S, sh.khw);
+    P.vec4 = (sh.Ci % cb == 0) && ((cb * sh.khw) % 4 == 0) && (sh.K % 4 == 0) &&
+             ((reinterpret_cast<uintptr_t>(P.flt) & 15u) == 0);
+    P.d_cpr = make_fastdiv((uint32_t)((cb * sh.khw) / 4 > 0 ? (cb * sh.khw) / 4 : 1));
+    switch (sh.khw) {
+        case 9:   return launch_t<9>(P, lds, blocks, st);
+        case 49:  return launch_t<49>(P, lds, blocks, st);
+        case 121: return launch_t<121>(P, lds, blocks, st);
+        default:  return launch_t<0>(P, lds, blocks, st);
+    }
+}
+
+// Workspace-free convolution straight from the NCHW input: the pipelined kernel where the
+// layer fits it, the generic kernel otherwise.
 hipError_t launch_conv_implicit(const float *in, const float *flt, float *out, const Shape &sh,
                                 hipStream_t st)
 {
     MfmaParams P;
     fill_params(P, in, flt, out, sh);
+    P.implicit = 1;
     P.win_elems = (size_t)sh.N * sh.Ci * sh.Hi * (size_t)sh.Wi;   // the tensor P.win points at is the input
     const uint32_t blocks = ((P.npix + NB - 1) / NB) * (uint32_t)P.tiles_m;
-    return launch_conv_mfma_fast(P, sh, blocks, st, true);
+    hipError_t fe = launch_conv_mfma_fast(P, sh, blocks, st, true);
+    if (fe != hipErrorNotSupported) return fe;
+    return launch_generic(P, sh, blocks, st);
 }
 
 hipError_t launch_conv_mfma(const float *win, const float *flt, float *out, const Shape &sh,
@@ -236,17 +274,6 @@ hipError_t launch_conv_mfma(const float *win, const float *flt, float *out, cons
     MfmaParams P;
     fill_params(P, win, flt, out, sh);
 
-    const size_t lds_max = 160 * 1024;
-    int cb = sh.Ci < 8 ? sh.Ci : 8;
-    while (cb > 1 && lds_bytes(cb, P.S, sh.khw) > lds_max) cb = (cb > 2) ? (((cb / 2) & ~1) < 2 ? 2 : ((cb / 2) & ~1)) : 1;
-    if (lds_bytes(cb, P.S, sh.khw) > lds_max) return hipErrorInvalidConfiguration;
-    P.cb = cb;
-    const size_t lds = lds_bytes(cb, P.S, sh.khw);
-
-    P.vec4 = (sh.Ci % cb == 0) && ((cb * sh.khw) % 4 == 0) && (sh.K % 4 == 0) &&
-             ((reinterpret_cast<uintptr_t>(flt) & 15u) == 0);
-    P.d_cpr = make_fastdiv((uint32_t)((cb * sh.khw) / 4 > 0 ? (cb * sh.khw) / 4 : 1));
-
     const uint32_t tiles_n = (P.npix + NB - 1) / NB;
     const uint32_t blocks = tiles_n * (uint32_t)P.tiles_m;
     if (variant == kVariantDefault) {
@@ -255,12 +282,7 @@ hipError_t launch_conv_mfma(const float *win, const float *flt, float *out, cons
         fe = launch_conv_mfma_fast(P, sh, blocks, st);
         if (fe != hipErrorNotSupported) return fe;
     }
-    switch (sh.khw) {
-        case 9:   return launch_t<9>(P, lds, blocks, st);
-        case 49:  return launch_t<49>(P, lds, blocks, st);
-        case 121: return launch_t<121>(P, lds, blocks, st);
-        default:  return launch_t<0>(P, lds, blocks, st);
-    }
+    return launch_generic(P, sh, blocks, st);
 }
 
 }  // namespace im2win

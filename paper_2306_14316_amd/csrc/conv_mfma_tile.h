@@ -19,6 +19,7 @@ struct MfmaParams {
     uint32_t npix, howo, chan_stride;
     size_t win_elems;   // floats in the whole im2win tensor
     // workspace-free variant only: `win` is then the NCHW input itself
+    int implicit;       // 1: workspace-free variant
     int Hi, Wi, p;
     uint32_t in_plane;  // Hi*Wi
     int cb;          // channels per K block

@@ -84,14 +84,41 @@ def test_implicit_table2_layers_small_batch(L):
     assert_conv_close(dO.cpu().numpy(), O_ref, B_ref)
 
 
-def test_implicit_rejects_layers_it_does_not_take():
-    for shape in [(1, 3, 32, 32, 16, 3, 3, 1, 0), (1, 8, 16, 16, 8, 3, 2, 1, 0), (1, 8, 40, 40, 8, 11, 11, 4, 0)]:
-        N, Ci, Hi, Wi, Co, Hf, Wf, s, p = shape
-        I, F = workloads.random_layer_inputs(3, N, Ci, Hi, Wi, Co, Hf, Wf)
-        Ho, Wo = im2win.im2win_out_shape(Hi, Wi, Hf, Wf, s, p)
-        dO = torch.full((N, Co, Ho, Wo), POISON, dtype=torch.float32, device="cuda")
-        with pytest.raises(im2win.Im2winError) as e:
-            im2win.conv2d_im2win_implicit_fwd(I.cuda(), F.cuda(), dO, N, Ci, Hi, Wi, Co, Hf, Wf, s, p)
-        assert e.value.status == -4
-        torch.cuda.synchronize()
-        assert torch.isnan(dO).all()      # nothing was launched
+# layers outside the pipelined kernel's shapes: the generic kernel builds the strips from the input
+OTHER_SHAPES = [
+    (1, 1, 5, 5, 1, 3, 3, 1, 0),
+    (2, 3, 7, 9, 4, 3, 2, 1, 0),       # asymmetric filter, odd channel count
+    (2, 3, 9, 7, 5, 2, 3, 2, 1),
+    (1, 2, 11, 13, 3, 5, 3, 3, 3),     # pad as large as the filter allows
+    (3, 4, 12, 10, 2, 4, 1, 4, 0),     # stride wider than the filter
+    (1, 5, 6, 8, 3, 6, 2, 1, 0),       # Hf == Hi
+    (2, 2, 6, 6, 3, 8, 8, 1, 1),       # filter == padded input
+    (1, 3, 10, 10, 6, 1, 1, 2, 0),     # 1x1 strided
+    (3, 13, 12, 12, 96, 3, 3, 1, 0),   # Ci not a multiple of the K block
+    (70, 4, 3, 3, 8, 3, 3, 1, 0),      # one pixel per image
+    (1, 3, 40, 40, 16, 7, 7, 2, 3),    # three-channel 7x7 stride 2
+    (2, 3, 35, 35, 96, 11, 11, 4, 0),  # three-channel 11x11 stride 4
+    (1, 4, 6, 70, 8, 1, 9, 1, 0),      # 1x9
+    (1, 4, 70, 6, 8, 9, 1, 1, 2),      # 9x1, padded
+]
+
+
+@pytest.mark.parametrize("shape", OTHER_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_implicit_other_shapes(shape):
+    N, Ci, Hi, Wi, Co, Hf, Wf, s, p = shape
+    I, F = workloads.random_layer_inputs(5500 + sum(shape), N, Ci, Hi, Wi, Co, Hf, Wf)
+    print("implicit (generic)", shape, flush=True)
+    dO = _run(I, F, s, p)
+    O_ref, B_ref = oracle.conv2d_direct(I.numpy(), F.numpy(), s, p)
+    assert_conv_close(dO.cpu().numpy(), O_ref, B_ref)
+
+
+def test_implicit_three_channel_layers_small_batch():
+    for idx in (1, 4, 5):
+        L = workloads.layer(idx)
+        Ls = workloads.with_batch(L, min(L.N, 2))
+        I, F = workloads.make_inputs(Ls)
+        print("implicit", Ls.name, flush=True)
+        dO = _run(I, F, Ls.stride, Ls.pad)
+        O_ref, B_ref = oracle.conv2d_direct(I.numpy(), F.numpy(), Ls.stride, Ls.pad)
+        assert_conv_close(dO.cpu().numpy(), O_ref, B_ref)
