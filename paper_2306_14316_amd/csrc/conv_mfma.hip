@@ -262,7 +262,9 @@ hipError_t launch_conv_implicit(const float *in, const float *flt, float *out, c
     P.implicit = 1;
     P.win_elems = (size_t)sh.N * sh.Ci * sh.Hi * (size_t)sh.Wi;   // the tensor P.win points at is the input
     const uint32_t blocks = ((P.npix + NB - 1) / NB) * (uint32_t)P.tiles_m;
-    hipError_t fe = launch_conv_mfma_fast(P, sh, blocks, st, true);
+    hipError_t fe = launch_conv_mfma_shallow(in, flt, out, sh, st, true);
+    if (fe != hipErrorNotSupported) return fe;
+    fe = launch_conv_mfma_fast(P, sh, blocks, st, true);
     if (fe != hipErrorNotSupported) return fe;
     return launch_generic(P, sh, blocks, st);
 }

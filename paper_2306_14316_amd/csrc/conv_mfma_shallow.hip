@@ -49,7 +49,10 @@ struct ShallowParams {
     uint32_t npix, howo, chan_stride, ntiles;
     int fullseg;      // ((Wo-1)*s + Wf)*Hf
     int img_stride;   // Ci*Ho*rowlen : floats between the same row of consecutive images
-    size_t win_elems, out_elems;   // floats in the im2win tensor / the output
+    size_t win_elems, out_elems;   // floats in the tensor `win` points at / in the output
+    // workspace-free variant only: `win` is then the NCHW input itself
+    int Hi, Wi, p;
+    int in_plane, in_img;   // Hi*Wi, Ci*Hi*Wi
     FastDiv d_wo, d_ho, d_howo;
 };
 
@@ -63,7 +66,11 @@ struct Steps {
     __host__ __device__ static constexpr int filt_pos(int t) { return (t % HF) * WF + (t / HF); }
 };
 
-template <int HF, int WF, int CI, int WM, int KS, int JX>
+// IMP: workspace-free variant.  P.win is the NCHW input and each tile's im2win strips
+// (Eq. 2) are gathered from it: strip word kk*HF + u of a row segment is input row
+// m*s + u - p, column (first column of the segment) + kk - p, or zero padding.  The
+// LDS layout, the MFMA chain and the results are the same.
+template <int HF, int WF, int CI, int WM, int KS, int JX, bool IMP>
 __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(ShallowParams P)
 {
     using St = Steps<HF, WF, CI>;
@@ -137,6 +144,13 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
     int nnlo0 = 0, nlen0 = 0, nm0r = 0, nt1 = 0, nt2 = 0, nd1 = 0, nd2 = 0, nfilled = 1;
     size_t nbase = 0;
     uint32_t noff[JX];      // per thread: byte offset of its strip words from nbase
+    int nlpos[JX];          // (IMP) per thread: LDS strip position of each of its words
+    uint32_t nzero = 0;     // (IMP) per thread: bit j set when word j is zero padding (or unused)
+    // (IMP) per row segment r of the tile, wave-uniform: columns, their reciprocal, float offset
+    // of (row m*s - p, column nlo*s - p) from nbase, and those two coordinates
+    int gncol0 = 1, gncol1 = 1, gncol2 = 1, ggb0 = 0, ggb1 = 0, ggb2 = 0;
+    int ghb0 = 0, ghb1 = 0, ghb2 = 0, gwb0 = 0, gwb1 = 0, gwb2 = 0;
+    float grcp0 = 1.f, grcp1 = 1.f, grcp2 = 1.f;
     float ir[NIW];          // per thread: the strip words in flight
     int nwpos = 0;          // per lane: LDS position of its window
     // Output stores go through a buffer descriptor whose base is wave-uniform (first
@@ -163,7 +177,7 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
     const uint32_t howo4 = P.howo * 4u;
 
     // One piece of the work for tile `t` (pieces are numbered in dependency order).
-    auto piece = [&](auto pc, uint32_t t, int st_next, const floatx16 &pacc, int xpar) {
+    auto piece = [&](auto pc, uint32_t t, int st_next, const floatx16 &pacc, int xpar) __attribute__((always_inline)) {
         constexpr int p = decltype(pc)::value;
         if constexpr (p == P_GEO) {
             nP0 = t * NB;
@@ -175,7 +189,16 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
         } else if constexpr (p == P_GEO + 1) {
             nimg0 = fdiv(nq0, P.d_ho);
             nm0r = (int)(nq0 - nimg0 * (uint32_t)P.Ho);
-            nbase = ((size_t)nimg0 * P.img_stride) + (size_t)nm0r * P.rowlen + (size_t)(nnlo0 * sHf);
+            if (IMP) {
+                nbase = (size_t)nimg0 * P.in_img;
+                gncol0 = nlen0 / HF;
+                grcp0 = __builtin_amdgcn_rcpf((float)gncol0);
+                ghb0 = nm0r * P.s - P.p;
+                gwb0 = nnlo0 * P.s - P.p;
+                ggb0 = ghb0 * P.Wi + gwb0;
+            } else {
+                nbase = ((size_t)nimg0 * P.img_stride) + (size_t)nm0r * P.rowlen + (size_t)(nnlo0 * sHf);
+            }
             nfilled = nlen0;
         } else if constexpr (p == P_GEO + 2 || p == P_GEO + 3) {
             // row r = 1 or 2 of the tile: LDS position where it starts, and
@@ -190,13 +213,48 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
             const int d = (int)(img - nimg0) * P.img_stride + (mq - nm0r) * P.rowlen - nnlo0 * sHf - pos;
             if (r == 1) { nt1 = has ? pos : 0x3fffffff; nd1 = has ? d : 0; }
             else        { nt2 = has ? pos : 0x3fffffff; nd2 = has ? d : 0; }
+            if (IMP) {
+                const int nc = nhi * P.s + WF, hb = mq * P.s - P.p;
+                const float rc = __builtin_amdgcn_rcpf((float)nc);
+                const int gb = (int)(img - nimg0) * P.in_img + hb * P.Wi - P.p;
+                if (r == 1) { gncol1 = nc; grcp1 = rc; ghb1 = hb; gwb1 = -P.p; ggb1 = gb; }
+                else        { gncol2 = nc; grcp2 = rc; ghb2 = hb; gwb2 = -P.p; ggb2 = gb; }
+            }
             nfilled += has ? (nhi * P.s + WF) * HF : 0;
         } else if constexpr (p >= P_OFF && p < P_LD) {
             constexpr int j = p - P_OFF;
-            const int xc = min(tid + NT * j, nfilled - 1);   // words past the strips are never operands
-            int d = xc < nt1 ? 0 : nd1;
-            d = xc < nt2 ? d : nd2;
-            noff[j] = (uint32_t)(xc + d) * 4u;
+            if (IMP) {
+                // word g of the tile's gather list: segment, then (u, kk) with u outer so that
+                // neighbouring lanes read neighbouring input words
+                const int g = tid + NT * j;
+                const bool in1 = g >= nt1, in2 = g >= nt2;
+                // (plain values first: selects are taken between values, not between references)
+                const int t1 = nt1, t2 = nt2, c0 = gncol0, c1 = gncol1, c2 = gncol2;
+                const float r0 = grcp0, r1 = grcp1, r2 = grcp2;
+                const int b0 = ggb0, b1 = ggb1, b2 = ggb2, h0 = ghb0, h1 = ghb1, h2 = ghb2;
+                const int w0 = gwb0, w1 = gwb1, w2 = gwb2;
+                const int segoff = in2 ? t2 : (in1 ? t1 : 0);
+                const int ncol = in2 ? c2 : (in1 ? c1 : c0);
+                const float rcp = in2 ? r2 : (in1 ? r1 : r0);
+                const int gb = in2 ? b2 : (in1 ? b1 : b0);
+                const int hb = in2 ? h2 : (in1 ? h1 : h0);
+                const int wb = in2 ? w2 : (in1 ? w1 : w0);
+                const int x = g - segoff;
+                // x / ncol: (x + 0.5) / ncol is at least 0.5/ncol away from an integer, far more
+                // than the rounding error of the two float operations
+                const int u = (int)(((float)x + 0.5f) * rcp);
+                const int kk = x - u * ncol;
+                const bool used = g < nfilled;
+                const bool inside = used & ((uint32_t)(hb + u) < (uint32_t)P.Hi) & ((uint32_t)(wb + kk) < (uint32_t)P.Wi);
+                noff[j] = inside ? (uint32_t)(gb + u * P.Wi + kk) * 4u : 0u;
+                nlpos[j] = used ? segoff + kk * HF + u : g;
+                nzero = inside ? (nzero & ~(1u << j)) : (nzero | (1u << j));
+            } else {
+                const int xc = min(tid + NT * j, nfilled - 1);   // words past the strips are never operands
+                int d = xc < nt1 ? 0 : nd1;
+                d = xc < nt2 ? d : nd2;
+                noff[j] = (uint32_t)(xc + d) * 4u;
+            }
         } else if constexpr (p >= P_LD && p < P_WPOS) {
             // descriptor on the tile's first strip word; the channel is a scalar offset
             const size_t left = (P.win_elems - nbase) * 4u;
@@ -205,7 +263,7 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
 #pragma unroll
             for (int w = 2 * (p - P_LD); w < 2 * (p - P_LD) + 2 && w < NIW; ++w)
                 ir[w] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
-                                                      rw, noff[w % JX], (uint32_t)(w / JX) * P.chan_stride * 4u, 0));
+                                                      rw, noff[w % JX], (uint32_t)(w / JX) * (IMP ? (uint32_t)P.in_plane : P.chan_stride) * 4u, 0));
         } else if constexpr (p == P_WPOS) {
             const uint32_t Pl = min(nP0 + (uint32_t)(wn * 32 + l32), nPend);
             const uint32_t ql = fdiv(Pl, P.d_wo);
@@ -245,14 +303,16 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
         } else if constexpr (p >= P_LDS && p < NP) {
             lds_f32 *d = lds + st_next * STAGE + tid;
 #pragma unroll
-            for (int w = 2 * (p - P_LDS); w < 2 * (p - P_LDS) + 2 && w < NIW; ++w)
-                d[(w / JX) * SS + NT * (w % JX)] = ir[w];
+            for (int w = 2 * (p - P_LDS); w < 2 * (p - P_LDS) + 2 && w < NIW; ++w) {
+                if (IMP) lds[st_next * STAGE + (w / JX) * SS + nlpos[w % JX]] = ((nzero >> (w % JX)) & 1u) ? 0.0f : ir[w];
+                else d[(w / JX) * SS + NT * (w % JX)] = ir[w];
+            }
         }
     };
     // pieces lo..hi-1
-    auto pieces = [&](auto loc, auto hic, uint32_t t, int st_next, const floatx16 &pacc, int xpar) {
+    auto pieces = [&](auto loc, auto hic, uint32_t t, int st_next, const floatx16 &pacc, int xpar) __attribute__((always_inline)) {
         constexpr int lo = decltype(loc)::value, hi = decltype(hic)::value;
-        static_for<hi - lo>([&](auto k) { piece(std::integral_constant<int, lo + decltype(k)::value>{}, t, st_next, pacc, xpar); });
+        static_for<hi - lo>([&](auto k) __attribute__((always_inline)) { piece(std::integral_constant<int, lo + decltype(k)::value>{}, t, st_next, pacc, xpar); });
     };
 
     if (tid < 8) { lds[CI * SS + (tid & 3) + (tid >> 2) * STAGE] = 0.0f; }   // zero slots of both stages
@@ -269,7 +329,7 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
     __syncthreads();
 
     // ---- one tile: the MFMA chain with the pieces in its shadow -------------------
-    auto tile_body = [&](auto parc, uint32_t tile) {
+    auto tile_body = [&](auto parc, uint32_t tile) __attribute__((always_inline)) {
         constexpr int PAR = decltype(parc)::value;      // tile parity: LDS stage, accumulator set
         constexpr int AP = (KS == 2) ? 0 : PAR;         // with KS == 2 only 8 sums outlive the chain (own[])
         // the fetched tile becomes the computed tile
@@ -279,9 +339,9 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
         const lds_f32 *bpair = sbase + cwpos + h * SS;
         const lds_f32 *bsplit = sbase + cwpos + (CI - 1) * SS + h * KH2;
         const lds_f32 *bzero = (h && (KHW & 1)) ? sbase + CI * SS : bsplit + (KH2 - 1);
-        auto run = [&](auto ksc) {
+        auto run = [&](auto ksc) __attribute__((always_inline)) {
             constexpr int KSI = decltype(ksc)::value;
-            auto bread = [&](int ii) -> float {
+            auto bread = [&](int ii) __attribute__((always_inline)) -> float {
                 const int i = KSI * TW + ii;   // global step index (compile-time after unrolling)
                 if (St::is_pair(i)) {
                     const int pp = i / KHW, t = i % KHW;
@@ -296,7 +356,7 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
             for (int e = 0; e < SH_G; ++e)
                 if (e < TW) b[e] = bread(e);
             __builtin_amdgcn_sched_barrier(0);
-            static_for<TW>([&](auto ic) {
+            static_for<TW>([&](auto ic) __attribute__((always_inline)) {
                 constexpr int ii = decltype(ic)::value;
                 if (ii == 0) {
                     floatx16 z;
@@ -346,14 +406,14 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
     else pieces(std::integral_constant<int, P_ST>{}, std::integral_constant<int, P_LDS>{}, 0u, 0, acc[1], 1);
 }
 
-template <int HF, int WF, int CI, int WM, int KS, int JX>
-static hipError_t launch_shallow_t(const ShallowParams &P, int mgroups, hipStream_t st)
+template <int HF, int WF, int CI, int WM, int KS, int JX, bool IMP>
+static hipError_t launch_shallow_k(const ShallowParams &P, int mgroups, hipStream_t st)
 {
     constexpr int NT = 64 * WM * 2 * KS;
     constexpr int SS = JX * NT;
     constexpr int STAGE = CI * SS + 4;
     constexpr size_t lds = 4u * (size_t)(2 * STAGE + (KS == 2 ? 2 * WM * 2 * 2 * 8 * 64 : 0));
-    auto kern = &conv_mfma_shallow_kernel<HF, WF, CI, WM, KS, JX>;
+    auto kern = &conv_mfma_shallow_kernel<HF, WF, CI, WM, KS, JX, IMP>;
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -375,9 +435,17 @@ static hipError_t launch_shallow_t(const ShallowParams &P, int mgroups, hipStrea
     return hipGetLastError();
 }
 
+template <int HF, int WF, int CI, int WM, int KS, int JX>
+static hipError_t launch_shallow_t(const ShallowParams &P, int mgroups, hipStream_t st, bool implicit)
+{
+    return implicit ? launch_shallow_k<HF, WF, CI, WM, KS, JX, true>(P, mgroups, st)
+                    : launch_shallow_k<HF, WF, CI, WM, KS, JX, false>(P, mgroups, st);
+}
+
 // Returns hipErrorNotSupported when the layer does not meet this kernel's conditions.
+// implicit: `win` is the NCHW input (workspace-free variant).
 hipError_t launch_conv_mfma_shallow(const float *win, const float *flt, float *out, const Shape &sh,
-                                    hipStream_t st)
+                                    hipStream_t st, bool implicit)
 {
     // strip floats per channel for a 64-pixel tile, and the rows it may touch
     int rmax = (NB + sh.Wo - 2) / sh.Wo + 1;
@@ -386,7 +454,7 @@ hipError_t launch_conv_mfma_shallow(const float *win, const float *flt, float *o
     const int over = sh.Wf > sh.s ? sh.Wf - sh.s : 0;
     const int S = (NB * sh.s + rmax * over) * sh.Hf + 1;
     // 32-bit strip offsets: the rows of one tile must lie within 2 GiB of each other
-    const long long span = (long long)sh.Ci * sh.Ho * sh.rowlen * 4LL * (rmax + 1);
+    const long long span = (implicit ? (long long)sh.Ci * sh.Hi * sh.Wi : (long long)sh.Ci * sh.Ho * sh.rowlen) * 4LL * (rmax + 1);
     if (span >= (1LL << 31)) return hipErrorNotSupported;
     // 32-bit output offsets from (image of the tile's first pixel, wave's first channel): up to two images ahead
     if (((long long)sh.Co * (SH_RMAX + 1) + 64) * sh.Ho * sh.Wo * 4LL >= (1LL << 32)) return hipErrorNotSupported;
@@ -401,7 +469,10 @@ hipError_t launch_conv_mfma_shallow(const float *win, const float *flt, float *o
     P.ntiles = (P.npix + NB - 1) / NB;
     P.fullseg = ((sh.Wo - 1) * sh.s + sh.Wf) * sh.Hf;
     P.img_stride = sh.Ci * sh.Ho * sh.rowlen;
-    P.win_elems = (size_t)sh.N * P.img_stride;
+    P.win_elems = implicit ? (size_t)sh.N * sh.Ci * sh.Hi * (size_t)sh.Wi : (size_t)sh.N * P.img_stride;
+    P.Hi = sh.Hi; P.Wi = sh.Wi; P.p = sh.p;
+    P.in_plane = sh.Hi * sh.Wi;
+    P.in_img = sh.Ci * sh.Hi * sh.Wi;
     P.out_elems = (size_t)sh.npix * sh.Co;
     P.d_wo = make_fastdiv((uint32_t)sh.Wo);
     P.d_ho = make_fastdiv((uint32_t)sh.Ho);
@@ -411,18 +482,18 @@ hipError_t launch_conv_mfma_shallow(const float *win, const float *flt, float *o
     const int wm = sh.Co <= 32 ? 1 : (sh.Co <= 64 ? 2 : 3);
     const int mgroups = (sh.Co + wm * 32 - 1) / (wm * 32);
     if (sh.Hf == 7 && sh.Wf == 7) {
-        if (wm == 1 && S <= 4 * 128) return launch_shallow_t<7, 7, 3, 1, 1, 4>(P, mgroups, st);
-        if (wm == 1 && S <= 8 * 128) return launch_shallow_t<7, 7, 3, 1, 1, 8>(P, mgroups, st);
-        if (wm == 2 && S <= 4 * 256) return launch_shallow_t<7, 7, 3, 2, 1, 4>(P, mgroups, st);
-        if (wm == 3 && S <= 3 * 384) return launch_shallow_t<7, 7, 3, 3, 1, 3>(P, mgroups, st);
+        if (wm == 1 && S <= 4 * 128) return launch_shallow_t<7, 7, 3, 1, 1, 4>(P, mgroups, st, implicit);
+        if (wm == 1 && S <= 8 * 128) return launch_shallow_t<7, 7, 3, 1, 1, 8>(P, mgroups, st, implicit);
+        if (wm == 2 && S <= 4 * 256) return launch_shallow_t<7, 7, 3, 2, 1, 4>(P, mgroups, st, implicit);
+        if (wm == 3 && S <= 3 * 384) return launch_shallow_t<7, 7, 3, 3, 1, 3>(P, mgroups, st, implicit);
     } else if (sh.Hf == 11 && sh.Wf == 11) {
-        if (wm == 1 && S <= 12 * 256) return launch_shallow_t<11, 11, 3, 1, 2, 12>(P, mgroups, st);
-        if (wm == 2 && S <= 6 * 512) return launch_shallow_t<11, 11, 3, 2, 2, 6>(P, mgroups, st);
-        if (wm == 3 && S <= 4 * 768) return launch_shallow_t<11, 11, 3, 3, 2, 4>(P, mgroups, st);
+        if (wm == 1 && S <= 12 * 256) return launch_shallow_t<11, 11, 3, 1, 2, 12>(P, mgroups, st, implicit);
+        if (wm == 2 && S <= 6 * 512) return launch_shallow_t<11, 11, 3, 2, 2, 6>(P, mgroups, st, implicit);
+        if (wm == 3 && S <= 4 * 768) return launch_shallow_t<11, 11, 3, 3, 2, 4>(P, mgroups, st, implicit);
     } else if (sh.Hf == 3 && sh.Wf == 3) {
-        if (wm == 1 && S <= 2 * 128) return launch_shallow_t<3, 3, 3, 1, 1, 2>(P, mgroups, st);
-        if (wm == 2 && S <= 1 * 256) return launch_shallow_t<3, 3, 3, 2, 1, 1>(P, mgroups, st);
-        if (wm == 3 && S <= 1 * 384) return launch_shallow_t<3, 3, 3, 3, 1, 1>(P, mgroups, st);
+        if (wm == 1 && S <= 2 * 128) return launch_shallow_t<3, 3, 3, 1, 1, 2>(P, mgroups, st, implicit);
+        if (wm == 2 && S <= 1 * 256) return launch_shallow_t<3, 3, 3, 2, 1, 1>(P, mgroups, st, implicit);
+        if (wm == 3 && S <= 1 * 384) return launch_shallow_t<3, 3, 3, 3, 1, 1>(P, mgroups, st, implicit);
     }
     return hipErrorNotSupported;
 }

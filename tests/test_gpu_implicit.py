@@ -99,6 +99,17 @@ OTHER_SHAPES = [
     (1, 3, 40, 40, 16, 7, 7, 2, 3),    # three-channel 7x7 stride 2
     (2, 3, 35, 35, 96, 11, 11, 4, 0),  # three-channel 11x11 stride 4
     (1, 4, 6, 70, 8, 1, 9, 1, 0),      # 1x9
+    # three-channel layers with wide rows: the filter-stationary kernel gathers from the input
+    (2, 3, 70, 150, 40, 7, 7, 2, 3),
+    (3, 3, 20, 140, 64, 7, 7, 2, 0),
+    (1, 3, 40, 260, 96, 7, 7, 2, 3),
+    (1, 3, 9, 400, 8, 7, 7, 2, 3),
+    (1, 3, 100, 300, 96, 11, 11, 4, 0),
+    (1, 3, 60, 300, 20, 11, 11, 4, 2),
+    (2, 3, 50, 290, 64, 11, 11, 4, 0),
+    (1, 3, 30, 200, 16, 3, 3, 1, 1),
+    (1, 3, 36, 280, 100, 3, 3, 1, 1),
+    (4, 3, 3, 70, 8, 3, 3, 1, 1),      # short images: a tile spans three images
     (1, 4, 70, 6, 8, 9, 1, 1, 2),      # 9x1, padded
 ]
 
