@@ -35,11 +35,11 @@ PEAK_HBM_GBS = 8000.0             # MI355X HBM3E
 # profiles/conv_mfma_fast_and_transform_cfg2_3x3_c64_56.md (headline layer) and
 # profiles/all_layers_default_bench.md.  Layers that were not measured report null.
 MEASURED_CONV_TRAFFIC_BYTES = {
-    "cfg1_tiny_3x3": 202745, "cfg2_3x3_c64_56": 107272580, "cfg3_3x3_c256_14": 166375424,
-    "cfg4_7x7_s2_c3_224": 688753801, "cfg5_11x11_s4_c3_227": 643304105}
+    "cfg1_tiny_3x3": 205816, "cfg2_3x3_c64_56": 107132879, "cfg3_3x3_c256_14": 195828136,
+    "cfg4_7x7_s2_c3_224": 688746893, "cfg5_11x11_s4_c3_227": 415750701}
 MEASURED_TRANSFORM_TRAFFIC_BYTES = {
-    "cfg1_tiny_3x3": 68092, "cfg2_3x3_c64_56": 116521019, "cfg3_3x3_c256_14": 119028340,
-    "cfg4_7x7_s2_c3_224": 376826916, "cfg5_11x11_s4_c3_227": 322816558}
+    "cfg1_tiny_3x3": 68092, "cfg2_3x3_c64_56": 116520913, "cfg3_3x3_c256_14": 119028325,
+    "cfg4_7x7_s2_c3_224": 376829411, "cfg5_11x11_s4_c3_227": 322812870}
 
 
 def parse_args():
@@ -188,6 +188,7 @@ def time_variants(L, steps):
     im2win.im2win_transform(dI, dW, N, Ci, Hi, Wi, Hf, Wf, s, p)
     names = {0: "default", 1: "no_pipeline (one LDS stage, no prefetch)", 2: "no_mfma (one thread per output)"}
     out = {}
+    _ramp(lambda: im2win.conv2d_im2win_fwd(dW, dF, dO, N, Ci, Hi, Wi, Co, Hf, Wf, s, p))
     for v, name in names.items():
         k = steps if v != 2 else max(2, steps // 10)
         try:
