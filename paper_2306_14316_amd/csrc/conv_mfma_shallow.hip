@@ -186,6 +186,9 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
             nq1 = fdiv(nPend, P.d_wo);
             nnlo0 = (int)(nP0 - nq0 * (uint32_t)P.Wo);
             nlen0 = (((nq1 == nq0) ? (int)(nPend - nP0) : (P.Wo - 1 - nnlo0)) * P.s + WF) * HF;
+            // The scalar results are made opaque here so that the optimiser leaves this
+            // arithmetic in its own MFMA slot instead of sinking all of it to the first use.
+            asm volatile("" : "+s"(nq0), "+s"(nq1), "+s"(nnlo0), "+s"(nlen0));
         } else if constexpr (p == P_GEO + 1) {
             nimg0 = fdiv(nq0, P.d_ho);
             nm0r = (int)(nq0 - nimg0 * (uint32_t)P.Ho);
@@ -200,6 +203,7 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
                 nbase = ((size_t)nimg0 * P.img_stride) + (size_t)nm0r * P.rowlen + (size_t)(nnlo0 * sHf);
             }
             nfilled = nlen0;
+            asm volatile("" : "+s"(nimg0), "+s"(nm0r), "+s"(nbase));
         } else if constexpr (p == P_GEO + 2 || p == P_GEO + 3) {
             // row r = 1 or 2 of the tile: LDS position where it starts, and
             // (source float offset relative to nbase) - (LDS position)
@@ -221,6 +225,8 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
                 else        { gncol2 = nc; grcp2 = rc; ghb2 = hb; gwb2 = -P.p; ggb2 = gb; }
             }
             nfilled += has ? (nhi * P.s + WF) * HF : 0;
+            if (r == 1) asm volatile("" : "+s"(nt1), "+s"(nd1), "+s"(nfilled));
+            else asm volatile("" : "+s"(nt2), "+s"(nd2), "+s"(nfilled));
         } else if constexpr (p >= P_OFF && p < P_LD) {
             constexpr int j = p - P_OFF;
             if (IMP) {
