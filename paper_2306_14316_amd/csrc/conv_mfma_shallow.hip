@@ -70,7 +70,11 @@ struct Steps {
 // (Eq. 2) are gathered from it: strip word kk*HF + u of a row segment is input row
 // m*s + u - p, column (first column of the segment) + kk - p, or zero padding.  The
 // LDS layout, the MFMA chain and the results are the same.
-template <int HF, int WF, int CI, int WM, int KS, int JX, bool IMP>
+// G: a tile is G groups of 64 pixels.  Each wave then advances G independent 32x32 blocks with
+// the same filter registers (step by step, G MFMAs per step), and the per-tile work (geometry,
+// barrier, state hand-over) is paid once per 64*G pixels -- what layers with a very short K
+// (3x3x3 = 14 MFMA steps) need.
+template <int HF, int WF, int CI, int WM, int KS, int JX, bool IMP, int G>
 __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(ShallowParams P)
 {
     using St = Steps<HF, WF, CI>;
@@ -80,7 +84,9 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
     constexpr int SS = JX * NT;                // LDS floats per channel strip
     constexpr int STAGE = CI * SS + 4;         // one LDS stage: CI strips + a zero slot
     constexpr int SH_G = (KS == 2) ? 4 : SH_G_MAX;   // shorter ring where registers are scarce
+    constexpr int NBT = NB * G;                // pixels per tile
     static_assert(T % KS == 0, "K steps must split evenly between the waves of a block");
+    static_assert(G == 1 || KS == 1, "pixel groups are not combined with a split K");
 
     extern __shared__ __align__(16) unsigned char smem[];
     lds_f32 *lds = (lds_f32 *)reinterpret_cast<float *>(smem);   // [2][STAGE] then the exchange area
@@ -136,8 +142,8 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
     constexpr int NIW = CI * JX;                 // strip words per thread and tile
     constexpr int NL = (NIW + 1) / 2;            // pieces that load / store two words each
     constexpr int NE = (KS == 2) ? 8 : 16;       // output-store pieces
-    constexpr int P_GEO = 0, P_OFF = 4, P_LD = P_OFF + JX, P_WPOS = P_LD + NL, P_OPTR = P_WPOS + 1,
-                  P_ST = P_OPTR + 1, P_LDS = P_ST + NE, NP = P_LDS + NL;
+    constexpr int P_GEO = 0, P_OFF = 4, P_LD = P_OFF + JX, P_WPOS = P_LD + NL, P_OPTR = P_WPOS + G,
+                  P_ST = P_OPTR + G, P_LDS = P_ST + NE * G, NP = P_LDS + NL;
 
     // state of the tile being fetched ("n": next) -- wave-uniform unless noted
     uint32_t nP0 = 0, nPend = 0, nq0 = 0, nq1 = 0, nimg0 = 0;
@@ -152,20 +158,22 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
     int ghb0 = 0, ghb1 = 0, ghb2 = 0, gwb0 = 0, gwb1 = 0, gwb2 = 0;
     float grcp0 = 1.f, grcp1 = 1.f, grcp2 = 1.f;
     float ir[NIW];          // per thread: the strip words in flight
-    int nwpos = 0;          // per lane: LDS position of its window
+    int nwpos[G];           // per lane and pixel group: LDS position of its window
     // Output stores go through a buffer descriptor whose base is wave-uniform (first
     // channel of the wave, image of the tile's first pixel); the lane adds a 32-bit
     // byte offset (its pixel, its first channel) and each store a scalar channel offset.
     size_t nobase = 0;      // uniform: float offset of that base in the output
-    uint32_t nooff = 0;     // per lane: byte offset from the base
-    int nroom = 0;          // per lane: number of channels it may store (<= 0: none)
-    bool nfull = false;     // uniform: every lane of the wave stores all of its channels
+    uint32_t nooff[G];      // per lane and group: byte offset from the base
+    int nroom[G];           // per lane and group: number of channels it may store (<= 0: none)
+    uint32_t nfull = 0;     // uniform, bit g: every lane of the wave stores all of its channels of group g
     // state of the tile being computed ("c") and of the one before it ("p")
-    int cwpos = 0, croom = 0, proom = 0;
+    int cwpos[G], croom[G], proom[G];
     size_t cobase = 0, pobase = 0;
-    uint32_t cooff = 0, pooff = 0;
-    bool cfull = false, pfull = false;
-    floatx16 acc[2];
+    uint32_t cooff[G], pooff[G];
+    uint32_t cfull = 0, pfull = 0;
+#pragma unroll
+    for (int g = 0; g < G; ++g) { nwpos[g] = 0; nooff[g] = 0; nroom[g] = 0; cwpos[g] = 0; croom[g] = 0; proom[g] = 0; cooff[g] = 0; pooff[g] = 0; }
+    floatx16 acc[2][G];
     float own[8];           // (KS == 2) this wave's partial sums of that half, kept from the previous tile
 
     const uint32_t per = (P.ntiles + gridDim.x - 1) / gridDim.x;
@@ -176,19 +184,59 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
     const int jl = jw + 4 * h;                               // first channel of this lane
     const uint32_t howo4 = P.howo * 4u;
 
+    // A wave-uniform 32-bit value made opaque to the optimiser, in a scalar register.  (In the
+    // multi-group instances the compiler does not always prove the value uniform, hence the
+    // explicit first-lane read there.)
+    auto pin = [](auto &x) __attribute__((always_inline)) {
+        if constexpr (G == 1) {
+            asm volatile("" : "+s"(x));
+        } else {
+            int v = __builtin_amdgcn_readfirstlane((int)x);
+            asm volatile("" : "+s"(v));
+            x = (std::remove_reference_t<decltype(x)>)v;
+        }
+    };
+    // Buffer descriptor over `elems` floats from `base`, its size saturated to 4 GiB - 1 with
+    // word-sized scalar operations (a 64-bit compare would go to the vector ALU).
+    auto make_desc = [](float *base, size_t elems) __attribute__((always_inline)) {
+        const size_t left = elems * 4u;
+        const uint32_t lo = (uint32_t)left, hi = (uint32_t)(left >> 32);
+        const uint32_t num = lo | (0u - (uint32_t)(hi != 0u));
+        return __builtin_amdgcn_make_buffer_rsrc(base, 0, num, 0x00020000);
+    };
+    // Descriptor over the output from float offset `obase` to its end.
+    auto out_desc = [&](size_t obase) __attribute__((always_inline)) { return make_desc(P.out + obase, P.out_elems - obase); };
+    __amdgpu_buffer_rsrc_t cdesc = out_desc(0), pdesc = out_desc(0);   // descriptors of the computed / previous tile
+    // One output store: accumulator register q of a lane's block (channel offset dj from the
+    // lane's first channel) through the tile's descriptor.  `full` is wave-uniform (every lane
+    // of the wave stores all of its channels).  With a long chain per tile the common case is a
+    // scalar branch and one buffer store, with no per-lane compare, and the rare partial tile
+    // takes plain guarded stores; with short chains the single exec-masked form measured faster.
+    auto store_one = [&](float val, int q, const __amdgpu_buffer_rsrc_t &ro, size_t obase, uint32_t ooff, int room,
+                         uint32_t full) __attribute__((always_inline)) {
+        const int dj = 8 * (q >> 2) + (q & 3);
+        if (TW < 32) {
+            if (full || dj < room)
+                __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, val), ro, ooff, (uint32_t)dj * howo4, 0);
+        } else if (full) {
+            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, val), ro, ooff, (uint32_t)dj * howo4, 0);
+        } else if (dj < room) {
+            P.out[obase + (ooff >> 2) + (size_t)dj * P.howo] = val;
+        }
+    };
     // One piece of the work for tile `t` (pieces are numbered in dependency order).
-    auto piece = [&](auto pc, uint32_t t, int st_next, const floatx16 &pacc, int xpar) __attribute__((always_inline)) {
+    auto piece = [&](auto pc, uint32_t t, int st_next, const floatx16 (&pacc)[G], int xpar) __attribute__((always_inline)) {
         constexpr int p = decltype(pc)::value;
         if constexpr (p == P_GEO) {
-            nP0 = t * NB;
-            nPend = min(nP0 + NB - 1, P.npix - 1);
+            nP0 = t * NBT;
+            nPend = min(nP0 + NBT - 1, P.npix - 1);
             nq0 = fdiv(nP0, P.d_wo);
             nq1 = fdiv(nPend, P.d_wo);
             nnlo0 = (int)(nP0 - nq0 * (uint32_t)P.Wo);
             nlen0 = (((nq1 == nq0) ? (int)(nPend - nP0) : (P.Wo - 1 - nnlo0)) * P.s + WF) * HF;
             // The scalar results are made opaque here so that the optimiser leaves this
             // arithmetic in its own MFMA slot instead of sinking all of it to the first use.
-            asm volatile("" : "+s"(nq0), "+s"(nq1), "+s"(nnlo0), "+s"(nlen0));
+            pin(nq0); pin(nq1); pin(nnlo0); pin(nlen0);
         } else if constexpr (p == P_GEO + 1) {
             nimg0 = fdiv(nq0, P.d_ho);
             nm0r = (int)(nq0 - nimg0 * (uint32_t)P.Ho);
@@ -203,7 +251,7 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
                 nbase = ((size_t)nimg0 * P.img_stride) + (size_t)nm0r * P.rowlen + (size_t)(nnlo0 * sHf);
             }
             nfilled = nlen0;
-            asm volatile("" : "+s"(nimg0), "+s"(nm0r), "+s"(nbase));
+            pin(nimg0); pin(nm0r);
         } else if constexpr (p == P_GEO + 2 || p == P_GEO + 3) {
             // row r = 1 or 2 of the tile: LDS position where it starts, and
             // (source float offset relative to nbase) - (LDS position)
@@ -225,8 +273,8 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
                 else        { gncol2 = nc; grcp2 = rc; ghb2 = hb; gwb2 = -P.p; ggb2 = gb; }
             }
             nfilled += has ? (nhi * P.s + WF) * HF : 0;
-            if (r == 1) asm volatile("" : "+s"(nt1), "+s"(nd1), "+s"(nfilled));
-            else asm volatile("" : "+s"(nt2), "+s"(nd2), "+s"(nfilled));
+            if (r == 1) { pin(nt1); pin(nd1); } else { pin(nt2); pin(nd2); }
+            pin(nfilled);
         } else if constexpr (p >= P_OFF && p < P_LD) {
             constexpr int j = p - P_OFF;
             if (IMP) {
@@ -263,49 +311,47 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
             }
         } else if constexpr (p >= P_LD && p < P_WPOS) {
             // descriptor on the tile's first strip word; the channel is a scalar offset
-            const size_t left = (P.win_elems - nbase) * 4u;
-            const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(
-                const_cast<float *>(P.win + nbase), 0, left < 0xffffffffull ? left : 0xffffffffull, 0x00020000);
+            const __amdgpu_buffer_rsrc_t rw = make_desc(const_cast<float *>(P.win + nbase), P.win_elems - nbase);
 #pragma unroll
             for (int w = 2 * (p - P_LD); w < 2 * (p - P_LD) + 2 && w < NIW; ++w)
                 ir[w] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
                                                       rw, noff[w % JX], (uint32_t)(w / JX) * (IMP ? (uint32_t)P.in_plane : P.chan_stride) * 4u, 0));
-        } else if constexpr (p == P_WPOS) {
-            const uint32_t Pl = min(nP0 + (uint32_t)(wn * 32 + l32), nPend);
+        } else if constexpr (p >= P_WPOS && p < P_OPTR) {
+            constexpr int g = p - P_WPOS;
+            const uint32_t Pl = min(nP0 + (uint32_t)(g * NB + wn * 32 + l32), nPend);
             const uint32_t ql = fdiv(Pl, P.d_wo);
             const int nl = (int)(Pl - ql * (uint32_t)P.Wo);
             const int rho = (int)(ql - nq0);
-            nwpos = rho == 0 ? (nl - nnlo0) * sHf : nlen0 + (rho - 1) * P.fullseg + nl * sHf;
-        } else if constexpr (p == P_OPTR) {
-            const uint32_t Pm = nP0 + (uint32_t)(wn * 32 + l32);
+            nwpos[g] = rho == 0 ? (nl - nnlo0) * sHf : nlen0 + (rho - 1) * P.fullseg + nl * sHf;
+        } else if constexpr (p >= P_OPTR && p < P_ST) {
+            constexpr int g = p - P_OPTR;
+            const uint32_t Pm = nP0 + (uint32_t)(g * NB + wn * 32 + l32);
             const uint32_t Pc = min(Pm, nPend);
             const uint32_t img = fdiv(Pc, P.d_howo);
             const uint32_t pin = Pc - img * P.howo;
             const uint32_t img0 = fdiv(nP0, P.d_howo);   // uniform
             nobase = ((size_t)img0 * P.Co + jw) * P.howo;
-            nooff = ((img - img0) * (uint32_t)P.Co * P.howo + pin) * 4u + (uint32_t)(4 * h) * howo4;
-            nroom = Pm <= nPend ? P.Co - jl : 0;
-            nfull = (nP0 + (uint32_t)(wn * 32 + 31) <= nPend) && (P.Co - jw >= 32);
+            nooff[g] = ((img - img0) * (uint32_t)P.Co * P.howo + pin) * 4u + (uint32_t)(4 * h) * howo4;
+            nroom[g] = Pm <= nPend ? P.Co - jl : 0;
+            const bool full = (nP0 + (uint32_t)(g * NB + wn * 32 + 31) <= nPend) && (P.Co - jw >= 32);
+            nfull = full ? (nfull | (1u << g)) : (nfull & ~(1u << g));
         } else if constexpr (p >= P_ST && p < P_LDS) {
-            // one output store of the previous tile
-            constexpr int q = p - P_ST;
-            const size_t left = (P.out_elems - pobase) * 4u;
-            const __amdgpu_buffer_rsrc_t ro = __builtin_amdgcn_make_buffer_rsrc(
-                P.out + pobase, 0, left < 0xffffffffull ? left : 0xffffffffull, 0x00020000);
-            float val;
-            int dj;
-            if (KS == 2) {
-                // add the partner's partial sum to this wave's (kept in own[]) first
+            // one output store of the previous tile (pixel group g, register q of its block)
+            constexpr int g = (p - P_ST) / NE, q = (p - P_ST) % NE;
+            if constexpr (KS == 2) {
+                // add the partner's partial sum to this wave's (kept in own[]) first; these
+                // instances are short of scalar registers and rebuild the descriptor here
                 const lds_f32 *theirs = lds + 2 * STAGE + xpar * (WM * 2 * 2 * 512) + ((wn * WM + wm) * 2 + (ks ^ 1)) * 512 + lane;
-                val = own[q] + *(const volatile lds_f32 *)(theirs + q * 64);
-                dj = (ks ? 16 : 0) + 8 * (q >> 2) + (q & 3);
+                const float val = own[q] + *(const volatile lds_f32 *)(theirs + q * 64);
+                const size_t left = (P.out_elems - pobase) * 4u;
+                const __amdgpu_buffer_rsrc_t ro = __builtin_amdgcn_make_buffer_rsrc(
+                    P.out + pobase, 0, left < 0xffffffffull ? left : 0xffffffffull, 0x00020000);
+                const int dj = (ks ? 16 : 0) + 8 * (q >> 2) + (q & 3);
+                if (pfull || dj < proom[0])
+                    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, val), ro, pooff[0], (uint32_t)dj * howo4, 0);
             } else {
-                val = pacc[q];
-                dj = 8 * (q >> 2) + (q & 3);
+                store_one(pacc[g][q], q, pdesc, pobase, pooff[g], proom[g], (pfull >> g) & 1u);
             }
-            // pfull is wave-uniform: the common case takes no per-lane compare
-            if (pfull || dj < proom)
-                __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, val), ro, pooff, (uint32_t)dj * howo4, 0);
         } else if constexpr (p >= P_LDS && p < NP) {
             lds_f32 *d = lds + st_next * STAGE + tid;
 #pragma unroll
@@ -316,7 +362,7 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
         }
     };
     // pieces lo..hi-1
-    auto pieces = [&](auto loc, auto hic, uint32_t t, int st_next, const floatx16 &pacc, int xpar) __attribute__((always_inline)) {
+    auto pieces = [&](auto loc, auto hic, uint32_t t, int st_next, const floatx16 (&pacc)[G], int xpar) __attribute__((always_inline)) {
         constexpr int lo = decltype(loc)::value, hi = decltype(hic)::value;
         static_for<hi - lo>([&](auto k) __attribute__((always_inline)) { piece(std::integral_constant<int, lo + decltype(k)::value>{}, t, st_next, pacc, xpar); });
     };
@@ -328,9 +374,10 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
         floatx16 z;
 #pragma unroll
         for (int v = 0; v < 16; ++v) z[v] = 0.0f;
-        acc[0] = z; acc[1] = z;
-        pieces(std::integral_constant<int, P_GEO>{}, std::integral_constant<int, P_ST>{}, tile0, 0, z, 0);
-        pieces(std::integral_constant<int, P_LDS>{}, std::integral_constant<int, NP>{}, tile0, 0, z, 0);
+#pragma unroll
+        for (int g = 0; g < G; ++g) { acc[0][g] = z; acc[1][g] = z; }
+        pieces(std::integral_constant<int, P_GEO>{}, std::integral_constant<int, P_ST>{}, tile0, 0, acc[0], 0);
+        pieces(std::integral_constant<int, P_LDS>{}, std::integral_constant<int, NP>{}, tile0, 0, acc[0], 0);
     }
     __syncthreads();
 
@@ -339,40 +386,52 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
         constexpr int PAR = decltype(parc)::value;      // tile parity: LDS stage, accumulator set
         constexpr int AP = (KS == 2) ? 0 : PAR;         // with KS == 2 only 8 sums outlive the chain (own[])
         // the fetched tile becomes the computed tile
-        cwpos = nwpos; cobase = nobase; cooff = nooff; croom = nroom; cfull = nfull;
+        cobase = nobase; cfull = nfull;
+        if (KS == 1) cdesc = out_desc(cobase);
+#pragma unroll
+        for (int g = 0; g < G; ++g) { cwpos[g] = nwpos[g]; cooff[g] = nooff[g]; croom[g] = nroom[g]; }
         const uint32_t nxt = min(tile + 1, tile_end - 1);   // the last tile refetches itself (unused)
         const lds_f32 *sbase = lds + PAR * STAGE;
-        const lds_f32 *bpair = sbase + cwpos + h * SS;
-        const lds_f32 *bsplit = sbase + cwpos + (CI - 1) * SS + h * KH2;
-        const lds_f32 *bzero = (h && (KHW & 1)) ? sbase + CI * SS : bsplit + (KH2 - 1);
+        const lds_f32 *bpair[G], *bsplit[G], *bzero[G];
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            bpair[g] = sbase + cwpos[g] + h * SS;
+            bsplit[g] = sbase + cwpos[g] + (CI - 1) * SS + h * KH2;
+            bzero[g] = (h && (KHW & 1)) ? sbase + CI * SS : bsplit[g] + (KH2 - 1);
+        }
         auto run = [&](auto ksc) __attribute__((always_inline)) {
             constexpr int KSI = decltype(ksc)::value;
-            auto bread = [&](int ii) __attribute__((always_inline)) -> float {
+            auto bread = [&](int ii, int g) __attribute__((always_inline)) -> float {
                 const int i = KSI * TW + ii;   // global step index (compile-time after unrolling)
                 if (St::is_pair(i)) {
                     const int pp = i / KHW, t = i % KHW;
-                    return *(const volatile lds_f32 *)(bpair + 2 * pp * SS + t);
+                    return *(const volatile lds_f32 *)(bpair[g] + 2 * pp * SS + t);
                 }
                 const int t = i - NPAIR * KHW;
-                if (t == KH2 - 1) return *(const volatile lds_f32 *)bzero;
-                return *(const volatile lds_f32 *)(bsplit + t);
+                if (t == KH2 - 1) return *(const volatile lds_f32 *)bzero[g];
+                return *(const volatile lds_f32 *)(bsplit[g] + t);
             };
-            float b[SH_G];   // ring of B operands, SH_G steps ahead of the MFMAs
+            float b[G][SH_G];   // rings of B operands, SH_G steps ahead of the MFMAs
 #pragma unroll
             for (int e = 0; e < SH_G; ++e)
-                if (e < TW) b[e] = bread(e);
+#pragma unroll
+                for (int g = 0; g < G; ++g)
+                    if (e < TW) b[g][e] = bread(e, g);
             __builtin_amdgcn_sched_barrier(0);
             static_for<TW>([&](auto ic) __attribute__((always_inline)) {
                 constexpr int ii = decltype(ic)::value;
-                if (ii == 0) {
-                    floatx16 z;
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) z[v] = 0.0f;
-                    acc[AP] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[0], b[0], z, 0, 0, 0);
-                } else {
-                    acc[AP] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[ii], b[ii % SH_G], acc[AP], 0, 0, 0);
+                for (int g = 0; g < G; ++g) {
+                    if (ii == 0) {
+                        floatx16 z;
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) z[v] = 0.0f;
+                        acc[AP][g] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[0], b[g][0], z, 0, 0, 0);
+                    } else {
+                        acc[AP][g] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[ii], b[g][ii % SH_G], acc[AP][g], 0, 0, 0);
+                    }
+                    if (ii + SH_G < TW) b[g][ii % SH_G] = bread(ii + SH_G, g);
                 }
-                if (ii + SH_G < TW) b[ii % SH_G] = bread(ii + SH_G);
                 // pieces whose slot is this MFMA: piece p rides behind MFMA p*TW/NP
                 constexpr int plo = (ii * NP + TW - 1) / TW, phi = ((ii + 1) * NP + TW - 1) / TW;
                 pieces(std::integral_constant<int, plo>{}, std::integral_constant<int, phi>{}, nxt, PAR ^ 1, acc[AP ^ 1], PAR ^ 1);
@@ -383,9 +442,9 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
                 // (register indices are compile-time constants here: KSI is this wave's K share)
                 lds_f32 *mine = lds + 2 * STAGE + PAR * (WM * 2 * 2 * 512) + ((wn * WM + wm) * 2 + KSI) * 512 + lane;
 #pragma unroll
-                for (int v = 0; v < 8; ++v) mine[v * 64] = acc[0][KSI ? v : 8 + v];
+                for (int v = 0; v < 8; ++v) mine[v * 64] = acc[0][0][KSI ? v : 8 + v];
 #pragma unroll
-                for (int v = 0; v < 8; ++v) own[v] = acc[0][KSI ? 8 + v : v];
+                for (int v = 0; v < 8; ++v) own[v] = acc[0][0][KSI ? 8 + v : v];
             }
         };
         if (KS == 1) {
@@ -395,7 +454,10 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
             else run(std::integral_constant<int, KS - 1>{});
         }
         // the computed tile becomes the previous tile
-        pobase = cobase; pooff = cooff; proom = croom; pfull = cfull;
+        pobase = cobase; pfull = cfull;
+        if (KS == 1) pdesc = cdesc;
+#pragma unroll
+        for (int g = 0; g < G; ++g) { pooff[g] = cooff[g]; proom[g] = croom[g]; }
         __syncthreads();
     };
 
@@ -412,14 +474,15 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
     else pieces(std::integral_constant<int, P_ST>{}, std::integral_constant<int, P_LDS>{}, 0u, 0, acc[1], 1);
 }
 
-template <int HF, int WF, int CI, int WM, int KS, int JX, bool IMP>
-static hipError_t launch_shallow_k(const ShallowParams &P, int mgroups, hipStream_t st)
+template <int HF, int WF, int CI, int WM, int KS, int JX, bool IMP, int G>
+static hipError_t launch_shallow_k(ShallowParams P, int mgroups, hipStream_t st)
 {
+    P.ntiles = (P.npix + NB * G - 1) / (NB * G);
     constexpr int NT = 64 * WM * 2 * KS;
     constexpr int SS = JX * NT;
     constexpr int STAGE = CI * SS + 4;
     constexpr size_t lds = 4u * (size_t)(2 * STAGE + (KS == 2 ? 2 * WM * 2 * 2 * 8 * 64 : 0));
-    auto kern = &conv_mfma_shallow_kernel<HF, WF, CI, WM, KS, JX, IMP>;
+    auto kern = &conv_mfma_shallow_kernel<HF, WF, CI, WM, KS, JX, IMP, G>;
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -441,11 +504,11 @@ static hipError_t launch_shallow_k(const ShallowParams &P, int mgroups, hipStrea
     return hipGetLastError();
 }
 
-template <int HF, int WF, int CI, int WM, int KS, int JX>
+template <int HF, int WF, int CI, int WM, int KS, int JX, int G = 1>
 static hipError_t launch_shallow_t(const ShallowParams &P, int mgroups, hipStream_t st, bool implicit)
 {
-    return implicit ? launch_shallow_k<HF, WF, CI, WM, KS, JX, true>(P, mgroups, st)
-                    : launch_shallow_k<HF, WF, CI, WM, KS, JX, false>(P, mgroups, st);
+    return implicit ? launch_shallow_k<HF, WF, CI, WM, KS, JX, true, G>(P, mgroups, st)
+                    : launch_shallow_k<HF, WF, CI, WM, KS, JX, false, G>(P, mgroups, st);
 }
 
 // Returns hipErrorNotSupported when the layer does not meet this kernel's conditions.
@@ -453,14 +516,21 @@ static hipError_t launch_shallow_t(const ShallowParams &P, int mgroups, hipStrea
 hipError_t launch_conv_mfma_shallow(const float *win, const float *flt, float *out, const Shape &sh,
                                     hipStream_t st, bool implicit)
 {
-    // strip floats per channel for a 64-pixel tile, and the rows it may touch
-    int rmax = (NB + sh.Wo - 2) / sh.Wo + 1;
-    if (rmax > NB) rmax = NB;
-    if (rmax > SH_RMAX) return hipErrorNotSupported;
-    const int over = sh.Wf > sh.s ? sh.Wf - sh.s : 0;
-    const int S = (NB * sh.s + rmax * over) * sh.Hf + 1;
+    // rows a tile of 64*g pixels may touch, and its strip floats per channel (0: too many rows)
+    auto rows_of = [&](int g) {
+        int r = (NB * g + sh.Wo - 2) / sh.Wo + 1;
+        return r > NB * g ? NB * g : r;
+    };
+    auto strip_of = [&](int g) {
+        const int r = rows_of(g);
+        if (r > SH_RMAX) return 0;
+        const int over = sh.Wf > sh.s ? sh.Wf - sh.s : 0;
+        return (NB * g * sh.s + r * over) * sh.Hf + 1;
+    };
+    const int S = strip_of(1);
+    if (S == 0) return hipErrorNotSupported;
     // 32-bit strip offsets: the rows of one tile must lie within 2 GiB of each other
-    const long long span = (implicit ? (long long)sh.Ci * sh.Hi * sh.Wi : (long long)sh.Ci * sh.Ho * sh.rowlen) * 4LL * (rmax + 1);
+    const long long span = (implicit ? (long long)sh.Ci * sh.Hi * sh.Wi : (long long)sh.Ci * sh.Ho * sh.rowlen) * 4LL * (SH_RMAX + 1);
     if (span >= (1LL << 31)) return hipErrorNotSupported;
     // 32-bit output offsets from (image of the tile's first pixel, wave's first channel): up to two images ahead
     if (((long long)sh.Co * (SH_RMAX + 1) + 64) * sh.Ho * sh.Wo * 4LL >= (1LL << 32)) return hipErrorNotSupported;
@@ -497,6 +567,14 @@ hipError_t launch_conv_mfma_shallow(const float *win, const float *flt, float *o
         if (wm == 2 && S <= 6 * 512) return launch_shallow_t<11, 11, 3, 2, 2, 6>(P, mgroups, st, implicit);
         if (wm == 3 && S <= 4 * 768) return launch_shallow_t<11, 11, 3, 3, 2, 4>(P, mgroups, st, implicit);
     } else if (sh.Hf == 3 && sh.Wf == 3) {
+        // K = 27 is 14 MFMA steps: tiles of four pixel groups where the layer has enough of them
+        const int S4 = strip_of(4);
+        const bool many = P.npix >= 4u * NB * 4u * 768u;
+        if (many && S4 > 0) {
+            if (wm == 1 && S4 <= 7 * 128) return launch_shallow_t<3, 3, 3, 1, 1, 7, 4>(P, mgroups, st, implicit);
+            if (wm == 2 && S4 <= 4 * 256) return launch_shallow_t<3, 3, 3, 2, 1, 4, 4>(P, mgroups, st, implicit);
+            if (wm == 3 && S4 <= 3 * 384) return launch_shallow_t<3, 3, 3, 3, 1, 3, 4>(P, mgroups, st, implicit);
+        }
         if (wm == 1 && S <= 2 * 128) return launch_shallow_t<3, 3, 3, 1, 1, 2>(P, mgroups, st, implicit);
         if (wm == 2 && S <= 1 * 256) return launch_shallow_t<3, 3, 3, 2, 1, 1>(P, mgroups, st, implicit);
         if (wm == 3 && S <= 1 * 384) return launch_shallow_t<3, 3, 3, 3, 1, 1>(P, mgroups, st, implicit);

@@ -83,6 +83,15 @@ def test_table2_layers_small_batch(L):
     check_layer(I, F, Ls.stride, Ls.pad, basic=False, twice=False)
 
 
+@pytest.mark.parametrize("Co,pad", [(64, 0), (20, 1), (96, 1)])
+def test_three_channel_3x3_layer_with_many_pixels(Co, pad):
+    """Table 2's Conv7 shape at batch 16: enough pixels for the tiles of four 64-pixel groups
+    (one, two and three 32-channel blocks per workgroup; ragged last tile with padding)."""
+    I, F = workloads.random_layer_inputs(7700 + Co, 16, 3, 224, 224 - pad, Co, 3, 3)
+    print("conv7-like", Co, pad, flush=True)
+    check_layer(I, F, 1, pad, basic=False, twice=False)
+
+
 def test_im2win_tensor_larger_than_4_gib():
     """A 5 GB im2win tensor (byte offsets pass 2^32): images at both ends and in the
     middle are checked in full, plus sampled outputs anywhere."""
