@@ -1,0 +1,86 @@
+"""Seeded random layer shapes through every route of the library (two-call im2win path,
+workspace-free variant, im2col + GEMM, direct) against the CPU oracle.  The generator is
+biased towards the boundaries the kernels care about: channel counts around the K blocks,
+rows around the 64-pixel tile, three-channel wide rows, strides and paddings up to the
+filter size."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2306_14316_amd as im2win
+from paper_2306_14316_amd import workloads
+from parity_util import POISON, assert_bitwise_equal, assert_conv_close, run_conv, run_transform
+
+pytestmark = pytest.mark.gpu
+
+
+def _shapes(seed, count):
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        kind = rng.integers(0, 4)
+        if kind == 0:      # multi-channel square filters: the pipelined kernel's territory
+            Hf = Wf = int(rng.choice([3, 3, 5, 7]))
+            Ci = int(rng.choice([2, 4, 6, 8, 12, 16, 24, 40]))
+            Hi, Wi = int(rng.integers(Hf, 30)), int(rng.integers(Hf, 90))
+        elif kind == 1:    # three channels, wide rows: the filter-stationary kernel's territory
+            Hf = Wf = int(rng.choice([3, 7, 11]))
+            Ci = 3
+            Hi, Wi = int(rng.integers(Hf, 40)), int(rng.integers(120, 420))
+        elif kind == 2:    # anything: asymmetric filters, odd channel counts
+            Hf, Wf = int(rng.integers(1, 8)), int(rng.integers(1, 8))
+            Ci = int(rng.integers(1, 21))
+            Hi, Wi = int(rng.integers(Hf, 26)), int(rng.integers(Wf, 40))
+        else:              # tiny images, many of them: tiles straddle images
+            Hf = Wf = int(rng.choice([1, 2, 3]))
+            Ci = int(rng.choice([3, 8, 16]))
+            Hi, Wi = int(rng.integers(Hf, 8)), int(rng.integers(Wf, 8))
+        s = min(int(rng.choice([1, 1, 1, 2, 2, 3, 4])), min(Hf, Wf) + 1)
+        p = int(rng.integers(0, min(Hf, Wf) + 1))
+        N = int(rng.integers(1, 6)) if kind != 3 else int(rng.integers(8, 80))
+        Co = int(rng.choice([1, 5, 16, 31, 32, 33, 64, 65, 96, 100]))
+        Ho, Wo = (Hi + 2 * p - Hf) // s + 1, (Wi + 2 * p - Wf) // s + 1
+        if Ho < 1 or Wo < 1:
+            continue
+        if N * Co * Ho * Wo * Ci * Hf * Wf > 4e8:      # keep the oracle to a fraction of a second
+            continue
+        out.append((N, Ci, Hi, Wi, Co, Hf, Wf, s, p))
+    return out
+
+
+SHAPES = _shapes(20230614, 48)
+
+
+@pytest.mark.parametrize("shape", SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_random_shape_all_routes(shape):
+    N, Ci, Hi, Wi, Co, Hf, Wf, s, p = shape
+    I, F = workloads.random_layer_inputs(4000 + sum(shape), N, Ci, Hi, Wi, Co, Hf, Wf)
+    print("random shape", shape, flush=True)
+    In, Fn = I.numpy(), F.numpy()
+    O_ref, B_ref = oracle.conv2d_direct(In, Fn, s, p)
+    Ho, Wo = O_ref.shape[2:]
+    dI, dF = I.cuda(), F.cuda()
+
+    # the paper's path: transform, then convolution over the im2win tensor
+    dW = run_transform(I, Hf, Wf, s, p)
+    assert_bitwise_equal(dW, oracle.im2win(In, Hf, Wf, s, p))
+    dO = run_conv(dW, F, N, Ci, Hi, Wi, s, p)
+    assert_conv_close(dO.cpu().numpy(), O_ref, B_ref)
+
+    # workspace-free variant: same strips, same summation order -> same bits
+    dO2 = torch.full_like(dO, POISON)
+    im2win.conv2d_im2win_implicit_fwd(dI, dF, dO2, N, Ci, Hi, Wi, Co, Hf, Wf, s, p)
+    torch.cuda.synchronize()
+    assert torch.equal(dO.view(torch.int32), dO2.view(torch.int32))
+
+    # baselines
+    dO3 = torch.full_like(dO, POISON)
+    im2win.conv2d_direct_fwd(dI, dF, dO3, N, Ci, Hi, Wi, Co, Hf, Wf, s, p)
+    col = torch.full((N * Ho * Wo * Ci * Hf * Wf,), POISON, dtype=torch.float32, device="cuda")
+    dO4 = torch.full_like(dO, POISON)
+    im2win.im2col_transform(dI, col, N, Ci, Hi, Wi, Hf, Wf, s, p)
+    im2win.conv2d_im2col_fwd(col, dF, dO4, N, Ci, Hi, Wi, Co, Hf, Wf, s, p)
+    torch.cuda.synchronize()
+    assert_conv_close(dO3.cpu().numpy(), O_ref, B_ref)
+    assert_conv_close(dO4.cpu().numpy(), O_ref, B_ref)
