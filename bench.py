@@ -186,7 +186,8 @@ def time_variants(L, steps):
     dW = torch.empty((N, Ci, L.Ho, L.Wp * Hf), dtype=torch.float32, device="cuda")
     dO = torch.empty((N, Co, L.Ho, L.Wo), dtype=torch.float32, device="cuda")
     im2win.im2win_transform(dI, dW, N, Ci, Hi, Wi, Hf, Wf, s, p)
-    names = {0: "default", 1: "no_pipeline (one LDS stage, no prefetch)", 2: "no_mfma (one thread per output)"}
+    names = {0: "default", 3: "narrow_loads (8-byte instead of 16-byte filter fetches)",
+             1: "no_pipeline (one LDS stage, no prefetch)", 2: "no_mfma (one thread per output)"}
     out = {}
     _ramp(lambda: im2win.conv2d_im2win_fwd(dW, dF, dO, N, Ci, Hi, Wi, Co, Hf, Wf, s, p))
     for v, name in names.items():

@@ -110,12 +110,18 @@ im2win_status conv2d_im2win_fwd_basic(const float *window_dev, const float *filt
  *   IM2WIN_VARIANT_NO_PIPELINE       no double buffer / prefetch: one LDS stage,
  *                                    staging outside the MFMA chain (any layer);
  *   IM2WIN_VARIANT_NO_MFMA           no matrix cores, no register tile: one thread
- *                                    per output (Algorithm 2).
+ *                                    per output (Algorithm 2);
+ *   IM2WIN_VARIANT_NARROW_LOADS      the default kernel with the filter rows fetched in
+ *                                    8-byte instead of 16-byte pieces (the "vectorised
+ *                                    load" of Section 3.3 halved); only the pipelined 3x3
+ *                                    kernel has such an instance, other layers run the
+ *                                    default kernel.
  */
 enum {
     IM2WIN_VARIANT_DEFAULT = 0,
     IM2WIN_VARIANT_NO_PIPELINE = 1,
-    IM2WIN_VARIANT_NO_MFMA = 2
+    IM2WIN_VARIANT_NO_MFMA = 2,
+    IM2WIN_VARIANT_NARROW_LOADS = 3
 };
 im2win_status conv2d_im2win_fwd_variant(const float *window_dev, const float *filter_dev,
                                         float *output_dev,

@@ -16,6 +16,7 @@ from .binding import (  # noqa: F401
     VARIANT_DEFAULT,
     VARIANT_NO_PIPELINE,
     VARIANT_NO_MFMA,
+    VARIANT_NARROW_LOADS,
     im2col_footprint_bytes,
     im2col_transform,
     im2win_out_shape,

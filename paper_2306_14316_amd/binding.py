@@ -144,7 +144,7 @@ def conv2d_im2win_fwd_basic(window, filter, output, N, Ci, Hi, Wi, Co, Hf, Wf, s
     _conv("conv2d_im2win_fwd_basic", window, filter, output, N, Ci, Hi, Wi, Co, Hf, Wf, stride, pad, stream)
 
 
-VARIANT_DEFAULT, VARIANT_NO_PIPELINE, VARIANT_NO_MFMA = 0, 1, 2
+VARIANT_DEFAULT, VARIANT_NO_PIPELINE, VARIANT_NO_MFMA, VARIANT_NARROW_LOADS = 0, 1, 2, 3
 
 
 def conv2d_im2win_fwd_variant(window, filter, output, N, Ci, Hi, Wi, Co, Hf, Wf, stride, pad, variant,

@@ -109,7 +109,7 @@ im2win_status conv2d_im2win_fwd_variant(const float *window_dev, const float *fi
                                         int pad, int variant, void *stream)
 {
     if (!window_dev || !filter_dev || !output_dev) return IM2WIN_ERR_NULL;
-    if (variant < IM2WIN_VARIANT_DEFAULT || variant > IM2WIN_VARIANT_NO_MFMA) return IM2WIN_ERR_UNSUPPORTED;
+    if (variant < IM2WIN_VARIANT_DEFAULT || variant > IM2WIN_VARIANT_NARROW_LOADS) return IM2WIN_ERR_UNSUPPORTED;
     Shape sh;
     im2win_status st = derive(N, Ci, Hi, Wi, Co, Hf, Wf, stride, pad, &sh);
     if (st != IM2WIN_OK) return st;

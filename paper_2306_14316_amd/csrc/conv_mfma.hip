@@ -278,10 +278,10 @@ hipError_t launch_conv_mfma(const float *win, const float *flt, float *out, cons
 
     const uint32_t tiles_n = (P.npix + NB - 1) / NB;
     const uint32_t blocks = tiles_n * (uint32_t)P.tiles_m;
-    if (variant == kVariantDefault) {
+    if (variant == kVariantDefault || variant == kVariantNarrowLoads) {
         hipError_t fe = launch_conv_mfma_shallow(win, flt, out, sh, st);
         if (fe != hipErrorNotSupported) return fe;
-        fe = launch_conv_mfma_fast(P, sh, blocks, st);
+        fe = launch_conv_mfma_fast(P, sh, blocks, st, false, variant == kVariantNarrowLoads);
         if (fe != hipErrorNotSupported) return fe;
     }
     return launch_generic(P, sh, blocks, st);

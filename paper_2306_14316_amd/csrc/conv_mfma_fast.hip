@@ -370,7 +370,9 @@ static hipError_t launch_fast_i(const MfmaParams &P, uint32_t blocks, hipStream_
 
 // Returns hipErrorNotSupported when the layer does not meet the fast path's conditions.
 // implicit: P.win is the NCHW input (P.Hi, P.Wi, P.p, P.in_plane set; P.win_elems = its size).
-hipError_t launch_conv_mfma_fast(MfmaParams P, const Shape &sh, uint32_t blocks, hipStream_t st, bool implicit)
+// narrow: the ablation instance that fetches the filter in 8-byte pieces, where there is one.
+hipError_t launch_conv_mfma_fast(MfmaParams P, const Shape &sh, uint32_t blocks, hipStream_t st, bool implicit,
+                                 bool narrow)
 {
     const uintptr_t fa = reinterpret_cast<uintptr_t>(P.flt);
     const bool al16 = (fa & 15u) == 0 && (sh.K % 4 == 0);   // filter rows readable as aligned float4
@@ -382,6 +384,10 @@ hipError_t launch_conv_mfma_fast(MfmaParams P, const Shape &sh, uint32_t blocks,
         implicit ? (unsigned long long)sh.Ci * sh.Hi * (unsigned long long)sh.Wi * 4ull
                  : (unsigned long long)sh.Ci * sh.Ho * (unsigned long long)sh.rowlen * 4ull;
     if (img_bytes * (unsigned long long)(P.rmax + 1) >= (1ull << 32)) return hipErrorNotSupported;
+    if (narrow && !implicit && sh.Hf == 3 && sh.Wf == 3 && sh.Ci % 8 == 0 && al16) {   // ablation: 8-byte filter chunks
+        if (P.S <= 256) return launch_fast_t<3, 3, 8, 1, 2, 3, false>(P, blocks, st);
+        if (P.S <= 512) return launch_fast_t<3, 3, 8, 2, 2, 3, false>(P, blocks, st);
+    }
     if (sh.Hf == 3 && sh.Wf == 3 && sh.Ci % 8 == 0 && al16) {
         if (P.S <= 256) return launch_fast_i<3, 3, 8, 1, 4, 3>(P, blocks, st, implicit);
         if (P.S <= 512) return launch_fast_i<3, 3, 8, 2, 4, 3>(P, blocks, st, implicit);

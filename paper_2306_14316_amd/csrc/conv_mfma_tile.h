@@ -65,7 +65,7 @@ __device__ __forceinline__ void store_tile(const MfmaParams &P, const floatx16 &
 }
 
 hipError_t launch_conv_mfma_fast(MfmaParams P, const Shape &sh, uint32_t blocks, hipStream_t st,
-                                 bool implicit = false);
+                                 bool implicit = false, bool narrow = false);
 hipError_t launch_conv_mfma_shallow(const float *win, const float *flt, float *out, const Shape &sh,
                                     hipStream_t st, bool implicit = false);
 

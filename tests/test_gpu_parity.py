@@ -138,7 +138,7 @@ VARIANT_SHAPES = [
 
 
 @pytest.mark.parametrize("shape", VARIANT_SHAPES, ids=lambda s: "x".join(map(str, s)))
-@pytest.mark.parametrize("variant", [0, 1, 2])
+@pytest.mark.parametrize("variant", [0, 1, 2, 3])
 def test_ablation_variants(shape, variant):
     """Every ablation variant computes the same convolution."""
     N, Ci, Hi, Wi, Co, Hf, Wf, s, p = shape
@@ -157,7 +157,7 @@ def test_unknown_variant_is_rejected():
     I, F = workloads.random_layer_inputs(5, N, Ci, Hi, Wi, Co, Hf, Wf)
     dW = run_transform(I, Hf, Wf, s, p)
     dO = torch.zeros((N, Co, 4, 4), dtype=torch.float32, device="cuda")
-    for bad in (-1, 3, 99):
+    for bad in (-1, 4, 99):
         with pytest.raises(im2win.Im2winError):
             im2win.conv2d_im2win_fwd_variant(dW, F.cuda(), dO, N, Ci, Hi, Wi, Co, Hf, Wf, s, p, bad)
     assert not bool(dO.any())      # nothing was launched
