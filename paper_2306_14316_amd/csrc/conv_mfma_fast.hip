@@ -42,7 +42,9 @@ constexpr int pick_ring(int nm)
 // (Section 3.1) are built directly in LDS -- same LDS layout, same MFMA loop -- by
 // gathering input rows: strip word k*HF + u of output row m comes from input row
 // m*s + u - p, column k - p (zero outside the image).
-template <int HF, int WF, int CB, int JX, int CW, int OCC, bool IMP>
+// PER: the grid may hold fewer workgroups than tiles; a workgroup then takes tiles blockIdx.x,
+// + gridDim.x, ... and keeps the pipeline running across tile boundaries.
+template <int HF, int WF, int CB, int JX, int CW, int OCC, bool IMP, bool PER>
 __global__ __launch_bounds__(256, OCC) void conv_mfma_fast_kernel(MfmaParams P)
 {
     constexpr int KHW = HF * WF;
@@ -68,72 +70,105 @@ __global__ __launch_bounds__(256, OCC) void conv_mfma_fast_kernel(MfmaParams P)
     const int wm = wave & 1, wn = wave >> 1;
     const int h = lane >> 5, l32 = lane & 31;
 
-    const uint32_t lb = xcd_swizzle(blockIdx.x, gridDim.x);
-    const uint32_t tile_n = fdiv(lb, P.d_tm);
-    const uint32_t tile_m = lb - tile_n * (uint32_t)P.tiles_m;
-    const int m0 = (int)tile_m * MB;
-    const uint32_t P0 = tile_n * NB;
-    const uint32_t Pend = min(P0 + NB - 1, P.npix - 1);
-
-    // ---- strip geometry (rows q0..q1 of output pixels, q = i*Ho + m) ----
-    const uint32_t q0 = fdiv(P0, P.d_wo), q1 = fdiv(Pend, P.d_wo);
-    const int nlo0 = (int)(P0 - q0 * (uint32_t)P.Wo);
     const int sHf = P.s * HF;
-    const int len0 = (((q1 == q0) ? (int)(Pend - P0) : (P.Wo - 1 - nlo0)) * P.s + WF) * HF;
-    // float offset, in channel plane 0, of the first strip word of the tile
-    // (workspace-free variant: of the tile's first image in the input)
-    const uint32_t img0 = fdiv(q0, P.d_ho);
-    const size_t tile_base =
-        IMP ? (size_t)img0 * P.Ci * P.in_plane
-            : ((size_t)img0 * P.Ci * P.Ho + (q0 - img0 * (uint32_t)P.Ho)) * (size_t)P.rowlen + (size_t)(nlo0 * sHf);
+    const uint32_t ntiles = P.nblocks;   // all tiles of the layer; this workgroup takes blockIdx.x, + gridDim.x, ...
 
-    // Byte offset (from tile_base, same channel) of strip word tid + 256*j.  Words
-    // past the tile's segments are never used as operands; they reload word 0.
-    // Workspace-free variant: thread word tid + 256*j of a segment is taken row by
-    // row of the input (u outer, column inner: neighbouring lanes read neighbouring
-    // input words) and lands at LDS strip position loffI; words that fall in the
-    // zero padding (and unused ones) load word 0 and store +0.0.
-    uint32_t soffb[JX];
-    int loffI[JX];
-    bool zero[JX];
+    // ---- per-tile state: the tile being computed ("c") and the one after it ("n") ----
+    // P0/Pend: first and last pixel; m0: first output channel; bp: per-lane LDS base of the B
+    // operand (stage 0); soffb: byte offset (from the tile's descriptor base, same channel) of
+    // strip word tid + 256*j -- words past the tile's segments are never used as operands and
+    // reload word 0.  Workspace-free variant: thread word tid + 256*j of a segment is taken
+    // row by row of the input (u outer, column inner: neighbouring lanes read neighbouring
+    // input words) and lands at LDS strip position loffI; words that fall in the zero padding
+    // (and unused ones) load word 0 and store +0.0 (bit j of zero).
+    // rf / rw: buffer descriptors on the tile's filter rows / its first strip word (its first
+    // image in the workspace-free variant); the host has checked that a tile's strips lie
+    // within 4 GiB of that word.
+    uint32_t P0_c = 0, Pend_c = 0, P0_n = 0, Pend_n = 0;
+    int m0_c = 0, m0_n = 0;
+    const lds_float *bp_c = nullptr, *bp_n = nullptr;
+    uint32_t soffb_c[JX], soffb_n[JX];
+    int loffI_c[JX], loffI_n[JX];
+    uint32_t zero_c = 0, zero_n = 0;
+    auto desc = [](const float *base, size_t elems) __attribute__((always_inline)) {
+        const size_t left = elems * 4u;
+        return __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(base), 0,
+                                                 left < 0xffffffffull ? left : 0xffffffffull, 0x00020000);
+    };
+    __amdgpu_buffer_rsrc_t rf_c = desc(P.flt, 0), rf_n = desc(P.flt, 0), rw_c = desc(P.win, 0), rw_n = desc(P.win, 0);
+
+    auto tile_geometry = [&](uint32_t vb, uint32_t &P0, uint32_t &Pend, int &m0, const lds_float *&bp,
+                             uint32_t (&soffb)[JX], int (&loffI)[JX], uint32_t &zero,
+                             __amdgpu_buffer_rsrc_t &rf, __amdgpu_buffer_rsrc_t &rw) __attribute__((always_inline)) {
+        const uint32_t lb = xcd_swizzle(vb, ntiles);
+        const uint32_t tile_n = fdiv(lb, P.d_tm);
+        const uint32_t tile_m = lb - tile_n * (uint32_t)P.tiles_m;
+        m0 = (int)tile_m * MB;
+        P0 = tile_n * NB;
+        Pend = min(P0 + NB - 1, P.npix - 1);
+
+        // strip geometry (rows q0..q1 of output pixels, q = i*Ho + m)
+        const uint32_t q0 = fdiv(P0, P.d_wo), q1 = fdiv(Pend, P.d_wo);
+        const int nlo0 = (int)(P0 - q0 * (uint32_t)P.Wo);
+        const int len0 = (((q1 == q0) ? (int)(Pend - P0) : (P.Wo - 1 - nlo0)) * P.s + WF) * HF;
+        // float offset, in channel plane 0, of the first strip word of the tile
+        // (workspace-free variant: of the tile's first image in the input)
+        const uint32_t img0 = fdiv(q0, P.d_ho);
+        const size_t tile_base =
+            IMP ? (size_t)img0 * P.Ci * P.in_plane
+                : ((size_t)img0 * P.Ci * P.Ho + (q0 - img0 * (uint32_t)P.Ho)) * (size_t)P.rowlen + (size_t)(nlo0 * sHf);
+        rf = desc(P.flt + (size_t)m0 * P.K, ((size_t)P.Co - (size_t)m0) * (size_t)P.K);
+        rw = desc(P.win + tile_base, P.win_elems - tile_base);   // (P.win_elems: floats in the tensor P.win points at)
+
+        zero = 0;
 #pragma unroll
-    for (int j = 0; j < JX; ++j) { soffb[j] = 0; loffI[j] = tid + 256 * j; zero[j] = IMP; }
-    for (uint32_t q = q0; q <= q1; ++q) {
-        const int rho = (int)(q - q0);
-        const int nlo = rho == 0 ? nlo0 : 0;
-        const int nhi = (q == q1) ? (int)(Pend - q * (uint32_t)P.Wo) : P.Wo - 1;
-        const int seglen = ((nhi - nlo) * P.s + WF) * HF;
-        const int segoff = rho == 0 ? 0 : len0 + (rho - 1) * P.fullseg;
-        const uint32_t img = fdiv(q, P.d_ho);
-        const int mq = (int)(q - img * (uint32_t)P.Ho);
-        if (!IMP) {
-            const size_t src = ((size_t)img * P.Ci * P.Ho + (size_t)mq) * (size_t)P.rowlen + (size_t)(nlo * sHf);
-            const uint32_t rel = (uint32_t)(src - tile_base);   // the host checked that a tile's rows span < 4 GiB
+        for (int j = 0; j < JX; ++j) { soffb[j] = 0; loffI[j] = tid + 256 * j; if (IMP) zero |= 1u << j; }
+        for (uint32_t q = q0; q <= q1; ++q) {
+            const int rho = (int)(q - q0);
+            const int nlo = rho == 0 ? nlo0 : 0;
+            const int nhi = (q == q1) ? (int)(Pend - q * (uint32_t)P.Wo) : P.Wo - 1;
+            const int seglen = ((nhi - nlo) * P.s + WF) * HF;
+            const int segoff = rho == 0 ? 0 : len0 + (rho - 1) * P.fullseg;
+            const uint32_t img = fdiv(q, P.d_ho);
+            const int mq = (int)(q - img * (uint32_t)P.Ho);
+            if (!IMP) {
+                const size_t src = ((size_t)img * P.Ci * P.Ho + (size_t)mq) * (size_t)P.rowlen + (size_t)(nlo * sHf);
+                const uint32_t rel = (uint32_t)(src - tile_base);   // the host checked that a tile's rows span < 4 GiB
 #pragma unroll
-            for (int j = 0; j < JX; ++j) {
-                const int x = tid + 256 * j - segoff;
-                if (x >= 0 && x < seglen) soffb[j] = (rel + (uint32_t)x) * 4u;
-            }
-        } else {
-            const int ncol = (nhi - nlo) * P.s + WF;
-            const uint32_t rel = (img - img0) * (uint32_t)P.Ci * P.in_plane;   // host: a tile's images span < 4 GiB
+                for (int j = 0; j < JX; ++j) {
+                    const int x = tid + 256 * j - segoff;
+                    if (x >= 0 && x < seglen) soffb[j] = (rel + (uint32_t)x) * 4u;
+                }
+            } else {
+                const int ncol = (nhi - nlo) * P.s + WF;
+                const uint32_t rel = (img - img0) * (uint32_t)P.Ci * P.in_plane;   // host: a tile's images span < 4 GiB
 #pragma unroll
-            for (int j = 0; j < JX; ++j) {
-                const int x = tid + 256 * j - segoff;
-                if (x >= 0 && x < seglen) {
-                    int u = 0;
+                for (int j = 0; j < JX; ++j) {
+                    const int x = tid + 256 * j - segoff;
+                    if (x >= 0 && x < seglen) {
+                        int u = 0;
 #pragma unroll
-                    for (int t = 1; t < HF; ++t) u += (x >= t * ncol) ? 1 : 0;
-                    const int kk = x - u * ncol;
-                    const int hh = mq * P.s + u - P.p, ww = nlo * P.s + kk - P.p;
-                    const bool inside = (hh >= 0) & (hh < P.Hi) & (ww >= 0) & (ww < P.Wi);
-                    loffI[j] = segoff + kk * HF + u;
-                    zero[j] = !inside;
-                    soffb[j] = inside ? (rel + (uint32_t)(hh * P.Wi + ww)) * 4u : 0u;
+                        for (int t = 1; t < HF; ++t) u += (x >= t * ncol) ? 1 : 0;
+                        const int kk = x - u * ncol;
+                        const int hh = mq * P.s + u - P.p, ww = nlo * P.s + kk - P.p;
+                        const bool inside = (hh >= 0) & (hh < P.Hi) & (ww >= 0) & (ww < P.Wi);
+                        loffI[j] = segoff + kk * HF + u;
+                        zero = inside ? (zero & ~(1u << j)) : (zero | (1u << j));
+                        soffb[j] = inside ? (rel + (uint32_t)(hh * P.Wi + ww)) * 4u : 0u;
+                    }
                 }
             }
         }
-    }
+        // per-lane B operand base: the lane's window start in the LDS strip
+        const uint32_t Pl = min(P0 + (uint32_t)(wn * 32 + l32), Pend);
+        const uint32_t ql = fdiv(Pl, P.d_wo);
+        const int nl = (int)(Pl - ql * (uint32_t)P.Wo);
+        const int rhol = (int)(ql - q0);
+        const int b_base = rhol == 0 ? (nl - nlo0) * sHf : len0 + (rhol - 1) * P.fullseg + nl * sHf;
+        bp = (const lds_float *)lds + SF_FLOATS + b_base + h * SS;
+    };
+    tile_geometry(blockIdx.x, P0_c, Pend_c, m0_c, bp_c, soffb_c, loffI_c, zero_c, rf_c, rw_c);
+    const int m0 = m0_c;   // (filter staging below: with several tiles per workgroup every row of every tile is live)
 
     // ---- filter staging coordinates of this thread's chunks ----
     // The tile is MB rows x CPR chunks of CW floats.  Chunk columns are dealt out
@@ -169,17 +204,7 @@ __global__ __launch_bounds__(256, OCC) void conv_mfma_fast_kernel(MfmaParams P)
     // the same place), which keeps the staging code free of branches.
     if (tid + 256 * (JF - 1) >= NFC) { goffb[JF - 1] = goffb[0]; loff[JF - 1] = loff[0]; }
 
-    // ---- per-lane operand bases (stage 0) ----
-    int b_base;
-    {
-        const uint32_t Pl = min(P0 + (uint32_t)(wn * 32 + l32), Pend);
-        const uint32_t ql = fdiv(Pl, P.d_wo);
-        const int nl = (int)(Pl - ql * (uint32_t)P.Wo);
-        const int rho = (int)(ql - q0);
-        b_base = rho == 0 ? (nl - nlo0) * sHf : len0 + (rho - 1) * P.fullseg + nl * sHf;
-    }
     const lds_float *ap0 = (const lds_float *)lds + (wm * 32 + l32) * PF + h * KHW;
-    const lds_float *bp0 = (const lds_float *)lds + SF_FLOATS + b_base + h * SS;
     float *wI0 = lds + SF_FLOATS + tid;
 
     floatx16 acc;
@@ -191,20 +216,12 @@ __global__ __launch_bounds__(256, OCC) void conv_mfma_fast_kernel(MfmaParams P)
     // one and a half K blocks to arrive).
     float fr[JF][CW];
     float ir[2][CB * JX];
-    // Global loads go through buffer descriptors: a wave-uniform base held in scalar
-    // registers (the filter rows of this M tile; the tile's first strip word), the
-    // thread's constant 32-bit byte offset, and a scalar offset that selects the K
-    // block and channel.  The K loop spends no vector ALU work on addresses.
-    // (The host has checked that a tile's strips lie within 4 GiB of its first word.)
-    const size_t flt_left = ((size_t)P.Co - (size_t)m0) * (size_t)P.K * 4u;
-    const size_t win_left = (P.win_elems - tile_base) * 4u;   // (P.win_elems: floats in the tensor P.win points at)
-    const __amdgpu_buffer_rsrc_t rf = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<float *>(P.flt + (size_t)m0 * P.K), 0, flt_left < 0xffffffffull ? flt_left : 0xffffffffull, 0x00020000);
-    const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<float *>(P.win + tile_base), 0, win_left < 0xffffffffull ? win_left : 0xffffffffull, 0x00020000);
+    // Global loads go through the tiles' buffer descriptors: a wave-uniform base held in scalar
+    // registers, the thread's constant 32-bit byte offset, and a scalar offset that selects the
+    // K block and channel.  The K loop spends no vector ALU work on addresses.
     const uint32_t plane_bytes = (IMP ? P.in_plane : P.chan_stride) * 4u;
 
-    auto load_f = [&](int kb, int j) {
+    auto load_f = [&](int kb, int j, const __amdgpu_buffer_rsrc_t &rf) __attribute__((always_inline)) {
         if (CW == 4) {
             const float4v w = __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(rf, goffb[j], kb * (KB * 4), 0));
             fr[j][0] = w.x; fr[j][1] = w.y; fr[j][CW - 2] = w.z; fr[j][CW - 1] = w.w;
@@ -213,18 +230,18 @@ __global__ __launch_bounds__(256, OCC) void conv_mfma_fast_kernel(MfmaParams P)
             fr[j][0] = w.x; fr[j][1] = w.y;
         }
     };
-    auto load_i = [&](int kb, int set, int c, int j) {
+    auto load_i = [&](int kb, int set, int c, int j, const __amdgpu_buffer_rsrc_t &rw, const uint32_t (&soffb)[JX]) __attribute__((always_inline)) {
         ir[set][c * JX + j] = __builtin_bit_cast(
             float, __builtin_amdgcn_raw_buffer_load_b32(rw, soffb[j], (uint32_t)(kb * CB + c) * plane_bytes, 0));
     };
-    auto store_f = [&](int st, int j, int half) {   // words 2*half, 2*half+1 of chunk j
+    auto store_f = [&](int st, int j, int half) __attribute__((always_inline)) {   // words 2*half, 2*half+1 of chunk j
         lds_float *d = (lds_float *)lds + st * STAGE + loff[j] + 2 * half;
         d[0] = fr[j][2 * half];
         d[1] = fr[j][2 * half + 1];
     };
-    auto store_i = [&](int st, int set, int c, int j) {
+    auto store_i = [&](int st, int set, int c, int j, const int (&loffI)[JX], uint32_t zero) __attribute__((always_inline)) {
         if (IMP)
-            ((lds_float *)lds)[SF_FLOATS + loffI[j] + st * STAGE + c * SS] = zero[j] ? 0.0f : ir[set][c * JX + j];
+            ((lds_float *)lds)[SF_FLOATS + loffI[j] + st * STAGE + c * SS] = ((zero >> j) & 1u) ? 0.0f : ir[set][c * JX + j];
         else
             ((lds_float *)wI0)[st * STAGE + c * SS + 256 * j] = ir[set][c * JX + j];
     };
@@ -252,44 +269,57 @@ __global__ __launch_bounds__(256, OCC) void conv_mfma_fast_kernel(MfmaParams P)
     static_assert(NFW + NIWS + NILS <= NSLOT, "staging work must fit before the barrier");
 
     float a[R], b[R];
-    // operands of step i (0 <= i < NM) of a block, from LDS stage st, into ring slot i % R
-    auto lds_op = [&](int st, int i) {
+    // operands of step i (0 <= i < NM) of a block, from LDS stage st, into ring slot i % R;
+    // bp: the B base of the tile the block belongs to
+    auto lds_op = [&](int st, int i, const lds_float *bp) __attribute__((always_inline)) {
         const int g = i / KHW, t = i % KHW;
         const int u = t % HF, v = t / HF;   // window order: v outer, u inner; the filter is stored (u,v)
         // volatile: keeps these as single-dword LDS reads with 16-bit immediate
         // offsets (merged two-address reads have 8-bit offsets and would need a VALU
         // add each -- and VALU work comes out of the MFMA rate).
         a[i % R] = *(const volatile lds_float *)(ap0 + st * STAGE + 2 * g * KHW + u * WF + v);
-        b[i % R] = *(const volatile lds_float *)(bp0 + st * STAGE + 2 * g * SS + t);
+        b[i % R] = *(const volatile lds_float *)(bp + st * STAGE + 2 * g * SS + t);
     };
 
+    // NX1 / NX2: the block after this one / the one after that belongs to the next tile (a
+    // workgroup with several tiles keeps the pipeline running across the tile boundary);
+    // kb2: index, within its own tile, of the block whose global loads are issued here.
     const int nkb = P.Ci / CB;
-    auto block = [&](int kb, auto stc, auto has1c, auto has2c) {
+    auto block = [&](int kb2, auto stc, auto has1c, auto has2c, auto nx1c, auto nx2c) __attribute__((always_inline)) {
         constexpr int ST = decltype(stc)::value;
         constexpr bool HAS1 = decltype(has1c)::value, HAS2 = decltype(has2c)::value;
+        constexpr bool NX1 = decltype(nx1c)::value, NX2 = decltype(nx2c)::value;
 #pragma unroll
         for (int i = 0; i < NM; ++i) {
             if (HAS1 && i == NSLOT) __syncthreads();
             acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i % R], b[i % R], acc, 0, 0, 0);
             // ring slot i % R is free again: fetch the operands of step i + R (of this
             // block, or of the next one out of the other stage)
-            if (i + R < NM) lds_op(ST, i + R);
-            else if (HAS1) lds_op(ST ^ 1, i + R - NM);
+            if (i + R < NM) lds_op(ST, i + R, bp_c);
+            else if (HAS1) { if (NX1) lds_op(ST ^ 1, i + R - NM, bp_n); else lds_op(ST ^ 1, i + R - NM, bp_c); }
             if (i < NFW) {                       // filter chunk i/HPC: store a half, then reload it
                 if (HAS1) store_f(ST ^ 1, i / HPC, i % HPC);
-                if (HAS2 && (i % HPC == HPC - 1)) load_f(kb + 2, i / HPC);
-            } else if (i < NFW + NIWS) {   // strip words of block kb+1: two stores per slot
+                if (HAS2 && (i % HPC == HPC - 1)) { if (NX2) load_f(kb2, i / HPC, rf_n); else load_f(kb2, i / HPC, rf_c); }
+            } else if (i < NFW + NIWS) {   // strip words of the next block: two stores per slot
                 if (HAS1) {
                     const int w = 2 * (i - NFW);
-                    store_i(ST ^ 1, ST ^ 1, w / JX, w % JX);
-                    if (w + 1 < NIW) store_i(ST ^ 1, ST ^ 1, (w + 1) / JX, (w + 1) % JX);
+                    if (NX1) {
+                        store_i(ST ^ 1, ST ^ 1, w / JX, w % JX, loffI_n, zero_n);
+                        if (w + 1 < NIW) store_i(ST ^ 1, ST ^ 1, (w + 1) / JX, (w + 1) % JX, loffI_n, zero_n);
+                    } else {
+                        store_i(ST ^ 1, ST ^ 1, w / JX, w % JX, loffI_c, zero_c);
+                        if (w + 1 < NIW) store_i(ST ^ 1, ST ^ 1, (w + 1) / JX, (w + 1) % JX, loffI_c, zero_c);
+                    }
                 }
-            } else if (i < NFW + NIWS + NILS) {   // strip words of block kb+2: LPS loads per slot
+            } else if (i < NFW + NIWS + NILS) {   // strip words of the block after that: LPS loads per slot
                 if (HAS2) {
 #pragma unroll
                     for (int q = 0; q < LPS; ++q) {
                         const int w = (i - NFW - NIWS) * LPS + q;
-                        if (w < NIW) load_i(kb + 2, ST, w / JX, w % JX);
+                        if (w < NIW) {
+                            if (NX2) load_i(kb2, ST, w / JX, w % JX, rw_n, soffb_n);
+                            else load_i(kb2, ST, w / JX, w % JX, rw_c, soffb_c);
+                        }
                     }
                 }
             }
@@ -301,45 +331,65 @@ __global__ __launch_bounds__(256, OCC) void conv_mfma_fast_kernel(MfmaParams P)
     using T = std::true_type;
     using F = std::false_type;
 
-    // ---- prologue: block 0 into stage 0, block 1 into the registers ----
+    // ---- prologue: block 0 of the first tile into stage 0, its block 1 into the registers ----
 #pragma unroll
-    for (int j = 0; j < JF; ++j) load_f(0, j);
+    for (int j = 0; j < JF; ++j) load_f(0, j, rf_c);
 #pragma unroll
-    for (int w = 0; w < NIW; ++w) load_i(0, 0, w / JX, w % JX);
+    for (int w = 0; w < NIW; ++w) load_i(0, 0, w / JX, w % JX, rw_c, soffb_c);
 #pragma unroll
     for (int j = 0; j < JF; ++j)
 #pragma unroll
         for (int hh = 0; hh < HPC; ++hh) store_f(0, j, hh);
 #pragma unroll
-    for (int w = 0; w < NIW; ++w) store_i(0, 0, w / JX, w % JX);
+    for (int w = 0; w < NIW; ++w) store_i(0, 0, w / JX, w % JX, loffI_c, zero_c);
     if (nkb > 1) {
 #pragma unroll
-        for (int j = 0; j < JF; ++j) load_f(1, j);
+        for (int j = 0; j < JF; ++j) load_f(1, j, rf_c);
 #pragma unroll
-        for (int w = 0; w < NIW; ++w) load_i(1, 1, w / JX, w % JX);
+        for (int w = 0; w < NIW; ++w) load_i(1, 1, w / JX, w % JX, rw_c, soffb_c);
     }
     __syncthreads();
 #pragma unroll
-    for (int i = 0; i < R; ++i) lds_op(0, i);
+    for (int i = 0; i < R; ++i) lds_op(0, i, bp_c);
 
-    int kb = 0;
-    for (; kb + 3 < nkb; kb += 2) {   // unrolled by two so that the stage is a constant
-        block(kb, I0{}, T{}, T{});
-        block(kb + 1, I1{}, T{}, T{});
-    }
-    const int rem = nkb - kb;   // 1, 2 or 3 blocks left
-    if (rem == 3) {
-        block(kb, I0{}, T{}, T{});
-        block(kb + 1, I1{}, T{}, F{});
-        block(kb + 2, I0{}, F{}, F{});
-    } else if (rem == 2) {
-        block(kb, I0{}, T{}, F{});
-        block(kb + 1, I1{}, F{}, F{});
-    } else {
-        block(kb, I0{}, F{}, F{});
-    }
+    // ---- tiles of this workgroup ----
+    // The host gives a workgroup more than one tile only when nkb is even (every tile then
+    // starts in LDS stage 0) and Co is a multiple of the tile height.
+    for (uint32_t vb = blockIdx.x;;) {
+        const bool has_next = PER && vb + gridDim.x < ntiles;   // wave-uniform
+        if (has_next) tile_geometry(vb + gridDim.x, P0_n, Pend_n, m0_n, bp_n, soffb_n, loffI_n, zero_n, rf_n, rw_n);
 
-    store_tile(P, acc, P0, Pend, m0, wm, wn, h, l32);
+        int kb = 0;
+        for (; kb + 3 < nkb; kb += 2) {   // unrolled by two so that the stage is a constant
+            block(kb + 2, I0{}, T{}, T{}, F{}, F{});
+            block(kb + 3, I1{}, T{}, T{}, F{}, F{});
+        }
+        const int rem = nkb - kb;   // 1, 2 or 3 blocks left
+        if (has_next) {             // rem == 2: the next tile's blocks 0 and 1 are fetched meanwhile
+            block(0, I0{}, T{}, T{}, F{}, T{});
+            block(1, I1{}, T{}, T{}, T{}, T{});
+        } else if (rem == 3) {
+            block(kb + 2, I0{}, T{}, T{}, F{}, F{});
+            block(0, I1{}, T{}, F{}, F{}, F{});
+            block(0, I0{}, F{}, F{}, F{}, F{});
+        } else if (rem == 2) {
+            block(0, I0{}, T{}, F{}, F{}, F{});
+            block(0, I1{}, F{}, F{}, F{}, F{});
+        } else {
+            block(0, I0{}, F{}, F{}, F{}, F{});
+        }
+
+        store_tile(P, acc, P0_c, Pend_c, m0_c, wm, wn, h, l32);
+        if (!has_next) break;
+
+        // the next tile becomes the current one
+        vb += gridDim.x;
+        P0_c = P0_n; Pend_c = Pend_n; m0_c = m0_n; bp_c = bp_n; zero_c = zero_n; rf_c = rf_n; rw_c = rw_n;
+#pragma unroll
+        for (int j = 0; j < JX; ++j) { soffb_c[j] = soffb_n[j]; loffI_c[j] = loffI_n[j]; }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+    }
 }
 
 template <int HF, int WF, int CB, int JX, int CW, int OCC>
@@ -351,13 +401,31 @@ static hipError_t launch_fast_t(const MfmaParams &P, uint32_t blocks, hipStream_
     constexpr int KB = CB * HF * WF;
     constexpr int PF = KB | 1;
     constexpr size_t lds = 2u * 4u * (size_t)(((MB * PF + 3) & ~3) + CB * 256 * JX);
-    auto kern = &conv_mfma_fast_kernel<HF, WF, CB, JX, CW, OCC, IMP>;
+    // Several tiles per workgroup (the pipeline then runs across tile boundaries) when every tile
+    // starts in LDS stage 0 (an even number of K blocks), every filter row of every tile exists,
+    // and there are at least three tiles per resident workgroup.  It pays for short K loops --
+    // with 8 blocks per tile the per-tile start-up is an eighth of the work (+8 % measured) --
+    // and costs 1-3 % with 16 or more, where it is not used.  The count is a multiple of 8 so
+    // that a workgroup's tiles stay on its XCD under the block-id remapping.
+    MfmaParams Q = P;
+    Q.nblocks = blocks;
+    uint32_t grid = blocks;
+    if ((Q.Ci / CB) % 2 == 0 && Q.Ci / CB <= 12 && Q.Co % MB == 0) {
+        int dev = 0, ncu = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e == hipSuccess) e = hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e != hipSuccess) return e;
+        const uint32_t resident = ((uint32_t)ncu * OCC) & ~7u;
+        if (resident >= 8 && blocks >= 3 * resident) grid = resident;
+    }
+    auto kern = grid < blocks ? &conv_mfma_fast_kernel<HF, WF, CB, JX, CW, OCC, IMP, true>
+                              : &conv_mfma_fast_kernel<HF, WF, CB, JX, CW, OCC, IMP, false>;
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(kern, dim3(blocks), dim3(256), lds, st, P);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, st, Q);
     return hipGetLastError();
 }
 

@@ -92,6 +92,32 @@ def test_three_channel_3x3_layer_with_many_pixels(Co, pad):
     check_layer(I, F, 1, pad, basic=False, twice=False)
 
 
+# (N, Ci, Hi, Wi, Co, Hf, Wf, s, p): short K loops and at least 2304 tiles, so that the pipelined
+# kernel gives every workgroup several tiles and runs its pipeline across tile boundaries
+MANY_TILE_SHAPES = [
+    (48, 16, 56, 56, 64, 3, 3, 1, 1),    # two K blocks per tile
+    (46, 64, 57, 57, 64, 3, 3, 1, 1),    # eight K blocks; ragged last tile; rows of 57 pixels
+    (24, 32, 56, 56, 128, 3, 3, 1, 1),   # two M tiles per pixel tile
+    (42, 8, 64, 64, 64, 5, 5, 1, 0),     # 5x5 instance
+    (40, 4, 128, 128, 64, 7, 7, 2, 0),   # 7x7 stride-2 instance
+]
+
+
+@pytest.mark.parametrize("shape", MANY_TILE_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_many_tiles_per_workgroup(shape):
+    N, Ci, Hi, Wi, Co, Hf, Wf, s, p = shape
+    I, F = workloads.random_layer_inputs(7300 + sum(shape), N, Ci, Hi, Wi, Co, Hf, Wf)
+    print("many tiles", shape, flush=True)
+    check_layer(I, F, s, p, basic=False, twice=False)
+    # the workspace-free variant runs the same pipeline from the input: same bits
+    dW = run_transform(I, Hf, Wf, s, p)
+    dO = run_conv(dW, F, N, Ci, Hi, Wi, s, p)
+    dO2 = torch.full_like(dO, float("nan"))
+    im2win.conv2d_im2win_implicit_fwd(I.cuda(), F.cuda(), dO2, N, Ci, Hi, Wi, Co, Hf, Wf, s, p)
+    torch.cuda.synchronize()
+    assert torch.equal(dO.view(torch.int32), dO2.view(torch.int32))
+
+
 def test_im2win_tensor_larger_than_4_gib():
     """A 5 GB im2win tensor (byte offsets pass 2^32): images at both ends and in the
     middle are checked in full, plus sampled outputs anywhere."""
