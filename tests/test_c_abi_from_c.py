@@ -1,0 +1,53 @@
+"""The boundary is a C ABI: a plain C program that includes include/im2win.h, links
+libim2win.so and calls the host-side entry points must compile and run (no GPU needed)."""
+import os
+import shutil
+import subprocess
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+C_SOURCE = r"""
+#include <stdio.h>
+#include <string.h>
+#include "im2win.h"
+
+int main(void)
+{
+    int Ho = 0, Wo = 0;
+    size_t ws = 0, col = 0;
+    /* Table 2, Conv4: 224, 7x7, stride 2, no padding -> 109 */
+    if (im2win_out_shape(224, 224, 7, 7, 2, 0, &Ho, &Wo) != IM2WIN_OK || Ho != 109 || Wo != 109) return 1;
+    /* Fig. 1: 4x4 input, 2x2 filter... counts 36 (im2win) and 48 (im2col) elements for the 3-channel case */
+    if (im2win_workspace_bytes(1, 3, 3, 3, 2, 2, 1, 0, &ws) != IM2WIN_OK || ws != 4 * 36) return 2;
+    if (im2col_footprint_bytes(1, 3, 3, 3, 2, 2, 1, 0, &col) != IM2WIN_OK || col != 4 * 48) return 3;
+    if (im2win_out_shape(4, 4, 5, 5, 1, 0, &Ho, &Wo) != IM2WIN_ERR_SHAPE) return 4;
+    if (im2win_transform(NULL, NULL, 1, 1, 4, 4, 2, 2, 1, 0, NULL) != IM2WIN_ERR_NULL) return 5;
+    if (conv2d_im2win_fwd_variant((const float *)16, (const float *)16, (float *)16, 1, 1, 4, 4, 1, 2, 2, 1, 0,
+                                  IM2WIN_VARIANT_NARROW_LOADS + 1, NULL) != IM2WIN_ERR_UNSUPPORTED) return 6;
+    if (strlen(im2win_status_str(IM2WIN_ERR_OVERFLOW)) == 0) return 7;
+    printf("c abi ok\n");
+    return 0;
+}
+"""
+
+
+def test_c_program_links_and_runs(tmp_path):
+    import paper_2306_14316_amd as im2win
+    lib = im2win.lib_path()
+    if not os.path.exists(lib):
+        pytest.skip("library not built")
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    src = tmp_path / "use_abi.c"
+    src.write_text(C_SOURCE)
+    exe = tmp_path / "use_abi"
+    libdir = os.path.dirname(lib)
+    cmd = [gcc, "-std=c99", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe),
+           "-L", libdir, "-lim2win", "-Wl,-rpath," + libdir, "-Wl,-rpath,/opt/rocm/lib"]
+    subprocess.run(cmd, check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True, timeout=120)
+    assert "c abi ok" in out.stdout
