@@ -20,7 +20,7 @@ int main(void)
     size_t ws = 0, col = 0;
     /* Table 2, Conv4: 224, 7x7, stride 2, no padding -> 109 */
     if (im2win_out_shape(224, 224, 7, 7, 2, 0, &Ho, &Wo) != IM2WIN_OK || Ho != 109 || Wo != 109) return 1;
-    /* Fig. 1: 4x4 input, 2x2 filter... counts 36 (im2win) and 48 (im2col) elements for the 3-channel case */
+    /* Fig. 1: three 3x3 channels, 2x2 filter: 36 im2win elements, 48 im2col elements */
     if (im2win_workspace_bytes(1, 3, 3, 3, 2, 2, 1, 0, &ws) != IM2WIN_OK || ws != 4 * 36) return 2;
     if (im2col_footprint_bytes(1, 3, 3, 3, 2, 2, 1, 0, &col) != IM2WIN_OK || col != 4 * 48) return 3;
     if (im2win_out_shape(4, 4, 5, 5, 1, 0, &Ho, &Wo) != IM2WIN_ERR_SHAPE) return 4;
