@@ -112,8 +112,8 @@ im2win_status conv2d_im2win_fwd_basic(const float *window_dev, const float *filt
  *   IM2WIN_VARIANT_NO_MFMA           no matrix cores, no register tile: one thread
  *                                    per output (Algorithm 2);
  *   IM2WIN_VARIANT_NARROW_LOADS      the default kernel with the filter rows fetched in
- *                                    8-byte instead of 16-byte pieces (the "vectorised
- *                                    load" of Section 3.3 halved); only the pipelined 3x3
+ *                                    8-byte instead of 16-byte pieces (the vector loads
+ *                                    of Section 3.3 at half width); only the pipelined 3x3
  *                                    kernel has such an instance, other layers run the
  *                                    default kernel.
  */

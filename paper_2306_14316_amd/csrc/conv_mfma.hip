@@ -7,8 +7,8 @@
 // output tile; each wave owns a 32x32 sub-tile held in 16 accumulator
 // registers and advances it with v_mfma_f32_32x32x2_f32.
 //
-// What the im2win layout buys (Section 3.1 / 3.3 "as many windows from the same
-// row as possible"): the window of pixel (i,m,n) for channel r is the
+// What the im2win layout buys (Section 3.1; Section 3.3 loads runs of windows that
+// belong to one output row): the window of pixel (i,m,n) for channel r is the
 // contiguous run What[i][r][m][n*s*Hf .. +Hf*Wf), and neighbouring pixels'
 // windows overlap.  So for one channel the tile's 64 pixels need only a few
 // contiguous strips of What (about (64*s + rows*(Wf-s))*Hf floats, against
