@@ -361,6 +361,8 @@ def main():
         out["ablation"] = [time_variants(workloads.layer(i), max(5, min(a.steps, 30))) for i in (2, 3)]
     if a.baselines:
         out["baselines"] = [time_baselines(l, max(5, min(a.steps, 20))) for l in workloads.LAYERS[1:]]
+        if a.table2:   # the paper's comparison (Section 4.3) on its own twelve layers
+            out["baselines_table2"] = [time_baselines(l, max(3, min(a.steps, 10))) for l in workloads.TABLE2]
     if a.table2:
         out["table2"] = [layer_report(t2, time_layer(t2, max(5, min(a.steps, 20)), 3)) for t2 in workloads.TABLE2]
     if not a.no_cpu_baseline:
