@@ -36,6 +36,144 @@ constexpr int pick_ring(int nm)
     return 0;
 }
 
+// ---- leftover tiles: sixteen 16x16 pieces per tile ------------------------------------------
+// A workgroup alone on a compute unit already keeps all four matrix pipes busy, so when fewer
+// tiles than compute units are left after the last full round of the grid they take a whole
+// tile time while most of the chip idles.  Each of those tiles is cut into sixteen 16x16
+// output pieces, one workgroup each (v_mfma_f32_16x16x4_f32), and inside the workgroup the four
+// waves split the channels: wave w multiplies channels [w*Ci/4, (w+1)*Ci/4) and the four partial
+// sums are added in a fixed order through LDS.  The waves share no operand, so nothing is
+// staged in LDS and the K loop has no barrier: a lane's filter taps of one channel and its
+// pixel's window of one channel are both contiguous runs in memory (the window order of
+// Section 3.1), read straight into registers D channel groups ahead.  The pieces are small
+// because freed workgroup slots are refilled at once: the pieces land three to a compute unit
+// on the units that finish first, and three of them must still be short.
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+template <int HF, int WF, bool IMP>
+__device__ __forceinline__ void tail_piece(const MfmaParams &P, uint32_t lt, int piece, float *lds,
+                                           int lane, int wave)
+{
+    constexpr int KHW = HF * WF;
+    constexpr int D = 7;   // channel groups (four channels each) in flight per wave
+    const int kq = lane >> 4, l16 = lane & 15;   // the lane's channel within a group, its row / pixel
+    const int sm = piece & 3, sn = piece >> 2;
+    const uint32_t tile_n = fdiv(lt, P.d_tm);
+    const uint32_t tile_m = lt - tile_n * (uint32_t)P.tiles_m;
+    const uint32_t P0 = tile_n * NB;
+    const uint32_t Pend = min(P0 + NB - 1, P.npix - 1);
+    const int mq = (int)tile_m * MB + sm * 16;      // first output channel of the piece
+    const uint32_t Pq = P0 + (uint32_t)(sn * 16);   // its first pixel
+    if (mq >= P.Co || Pq > Pend) return;            // nothing of this piece exists (whole workgroup)
+
+    auto desc = [](const float *base, size_t elems) __attribute__((always_inline)) {
+        const size_t left = elems * 4u;
+        return __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(base), 0,
+                                                 left < 0xffffffffull ? left : 0xffffffffull, 0x00020000);
+    };
+    // filter: descriptor on the piece's rows; the lane reads row l16 (rows past Co repeat the
+    // last one, their sums are never stored), channel kq of each group
+    const __amdgpu_buffer_rsrc_t rf = desc(P.flt + (size_t)mq * P.K, ((size_t)P.Co - (size_t)mq) * (size_t)P.K);
+    const uint32_t voffA = (uint32_t)(min(l16, P.Co - 1 - mq) * P.K + kq * KHW) * 4u;
+
+    // pixels: descriptor on the first pixel's window (its image in the workspace-free variant);
+    // the lane's pixel (pixels past the tile's last one repeat it, never stored)
+    const uint32_t q0 = fdiv(Pq, P.d_wo), img0 = fdiv(q0, P.d_ho);
+    const uint32_t Pl = min(Pq + (uint32_t)l16, Pend);
+    const uint32_t ql = fdiv(Pl, P.d_wo), imgl = fdiv(ql, P.d_ho);
+    const int nl = (int)(Pl - ql * (uint32_t)P.Wo), ml = (int)(ql - imgl * (uint32_t)P.Ho);
+    const uint32_t plane_bytes = (IMP ? P.in_plane : P.chan_stride) * 4u;
+    size_t base_off;
+    uint32_t voffB[IMP ? KHW : 1];
+    uint32_t inside = 0;   // workspace-free variant: bit t set when window element t lies in the image
+    if (!IMP) {
+        const int n0 = (int)(Pq - q0 * (uint32_t)P.Wo), mm0 = (int)(q0 - img0 * (uint32_t)P.Ho);
+        base_off = ((size_t)img0 * P.Ci * P.Ho + (size_t)mm0) * (size_t)P.rowlen + (size_t)(n0 * P.s * HF);
+        const size_t offl = ((size_t)imgl * P.Ci * P.Ho + (size_t)ml) * (size_t)P.rowlen + (size_t)(nl * P.s * HF);
+        voffB[0] = (uint32_t)(offl - base_off) * 4u + (uint32_t)kq * plane_bytes;   // host: a tile's rows span < 4 GiB
+    } else {
+        base_off = (size_t)img0 * P.Ci * P.in_plane;
+        const uint32_t rel = (imgl - img0) * (uint32_t)P.Ci * P.in_plane;           // host: a tile's images span < 4 GiB
+#pragma unroll
+        for (int t = 0; t < KHW; ++t) {
+            const int u = t % HF, v = t / HF;
+            const int hh = ml * P.s + u - P.p, ww = nl * P.s + v - P.p;
+            const bool in = (hh >= 0) & (hh < P.Hi) & (ww >= 0) & (ww < P.Wi);
+            inside |= in ? (1u << t) : 0u;
+            voffB[t] = in ? (rel + (uint32_t)(hh * P.Wi + ww)) * 4u + (uint32_t)kq * plane_bytes : 0u;
+        }
+    }
+    const __amdgpu_buffer_rsrc_t rw = desc(P.win + base_off, P.win_elems - base_off);
+
+    const int ngroups = P.Ci >> 4;        // channel groups per wave (the host checked Ci % 16 == 0)
+    const int c0 = wave * (P.Ci >> 2);    // the wave's first channel
+
+    float fa[D][KHW], fb[D][KHW];
+    auto run = [](float (&dst)[KHW], const __amdgpu_buffer_rsrc_t &r, uint32_t voff, uint32_t soff)
+                   __attribute__((always_inline)) {   // KHW consecutive floats (4-byte aligned)
+#pragma unroll
+        for (int i = 0; i + 4 <= KHW; i += 4) {
+            const float4v w = __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(r, voff + 4u * i, soff, 0));
+            dst[i] = w.x; dst[i + 1] = w.y; dst[i + 2] = w.z; dst[i + 3] = w.w;
+        }
+#pragma unroll
+        for (int i = KHW & ~3; i < KHW; ++i)
+            dst[i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, voff + 4u * i, soff, 0));
+    };
+    auto fetch = [&](float (&da)[KHW], float (&db)[KHW], int g) __attribute__((always_inline)) {
+        const uint32_t c = (uint32_t)(c0 + 4 * g);
+        run(da, rf, voffA, c * (uint32_t)(KHW * 4));
+        if (!IMP) {
+            run(db, rw, voffB[0], c * plane_bytes);
+        } else {
+#pragma unroll
+            for (int t = 0; t < KHW; ++t)
+                db[t] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rw, voffB[IMP ? t : 0], c * plane_bytes, 0));
+        }
+    };
+
+    floatx4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+    for (int d = 0; d < D; ++d)
+        if (d < ngroups) fetch(fa[d], fb[d], d);
+    for (int g0 = 0; g0 < ngroups; g0 += D) {
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            if (g0 + d < ngroups) {
+#pragma unroll
+                for (int t = 0; t < KHW; ++t) {
+                    const int u = t % HF, v = t / HF;   // window order: v outer, u inner; the filter is stored (u,v)
+                    const float b = IMP ? (((inside >> t) & 1u) ? fb[d][t] : 0.0f) : fb[d][t];
+                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(fa[d][u * WF + v], b, acc, 0, 0, 0);
+                }
+                if (g0 + d + D < ngroups) fetch(fa[d], fb[d], g0 + d + D);
+            }
+        }
+    }
+
+    // ((wave 0 + wave 1) + wave 2) + wave 3, then wave 0 stores the piece: accumulator register
+    // v of lane (kq, l16) holds output channel 4*kq + v and pixel l16 of the piece
+    if (wave > 0) {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) lds[((wave - 1) * 4 + v) * 64 + lane] = acc[v];
+    }
+    __syncthreads();
+    if (wave == 0) {
+        const uint32_t Pm = Pq + (uint32_t)l16;
+        if (Pm <= Pend) {
+            const uint32_t img = fdiv(Pm, P.d_howo);
+            const uint32_t pin = Pm - img * P.howo;
+            float *o = P.out + (size_t)img * P.Co * P.howo + pin;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int j = mq + 4 * kq + v;
+                const float r = ((acc[v] + lds[v * 64 + lane]) + lds[(4 + v) * 64 + lane]) + lds[(8 + v) * 64 + lane];
+                if (j < P.Co) o[(size_t)j * P.howo] = r;
+            }
+        }
+    }
+}
+
 // CW: floats per filter staging chunk (4: 16-byte loads, 2: 8-byte loads).
 // OCC: workgroups per CU the register allocation should leave room for.
 // IMP: workspace-free variant.  P.win is the NCHW input; the tile's im2win strips
@@ -44,7 +182,8 @@ constexpr int pick_ring(int nm)
 // m*s + u - p, column k - p (zero outside the image).
 // PER: the grid may hold fewer workgroups than tiles; a workgroup then takes tiles blockIdx.x,
 // + gridDim.x, ... and keeps the pipeline running across tile boundaries.
-template <int HF, int WF, int CB, int JX, int CW, int OCC, bool IMP, bool PER>
+// TAIL: workgroups P.nmain and up take one sixteenth each of the tiles P.nmain .. P.nblocks-1.
+template <int HF, int WF, int CB, int JX, int CW, int OCC, bool IMP, bool PER, bool TAIL>
 __global__ __launch_bounds__(256, OCC) void conv_mfma_fast_kernel(MfmaParams P)
 {
     constexpr int KHW = HF * WF;
@@ -69,6 +208,24 @@ __global__ __launch_bounds__(256, OCC) void conv_mfma_fast_kernel(MfmaParams P)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave & 1, wn = wave >> 1;
     const int h = lane >> 5, l32 = lane & 31;
+
+    if constexpr (TAIL) if (blockIdx.x >= P.nmain) {
+        // Piece q of leftover tile t.  Workgroup b runs on XCD b % 8 and P.nmain is a multiple
+        // of 8: the sixteen pieces of a tile are dealt to the same XCD, whose L2 then serves
+        // their shared filter rows and windows (the last L % 8 tiles aside).
+        const uint32_t sub = blockIdx.x - P.nmain, L = P.nblocks - P.nmain, full = L & ~7u;
+        uint32_t t, q;
+        if (sub < 16u * full) {
+            t = (sub & 7u) + ((sub >> 7) << 3);
+            q = (sub >> 3) & 15u;
+        } else {
+            const uint32_t s2 = sub - 16u * full, Lr = L - full;
+            q = s2 / Lr;
+            t = full + (s2 - q * Lr);
+        }
+        tail_piece<HF, WF, IMP>(P, P.nmain + t, (int)q, lds, lane, __builtin_amdgcn_readfirstlane(wave));
+        return;
+    }
 
     const int sHf = P.s * HF;
     const uint32_t ntiles = P.nblocks;   // all tiles of the layer; this workgroup takes blockIdx.x, + gridDim.x, ...
@@ -100,7 +257,7 @@ __global__ __launch_bounds__(256, OCC) void conv_mfma_fast_kernel(MfmaParams P)
     auto tile_geometry = [&](uint32_t vb, uint32_t &P0, uint32_t &Pend, int &m0, const lds_float *&bp,
                              uint32_t (&soffb)[JX], int (&loffI)[JX], uint32_t &zero,
                              __amdgpu_buffer_rsrc_t &rf, __amdgpu_buffer_rsrc_t &rw) __attribute__((always_inline)) {
-        const uint32_t lb = xcd_swizzle(vb, ntiles);
+        const uint32_t lb = xcd_swizzle(vb, TAIL ? P.nmain : ntiles);
         const uint32_t tile_n = fdiv(lb, P.d_tm);
         const uint32_t tile_m = lb - tile_n * (uint32_t)P.tiles_m;
         m0 = (int)tile_m * MB;
@@ -409,20 +566,37 @@ static hipError_t launch_fast_t(const MfmaParams &P, uint32_t blocks, hipStream_
     // that a workgroup's tiles stay on its XCD under the block-id remapping.
     MfmaParams Q = P;
     Q.nblocks = blocks;
+    Q.nmain = blocks;
     uint32_t grid = blocks;
+    int dev = 0, ncu = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess) return e;
     if ((Q.Ci / CB) % 2 == 0 && Q.Ci / CB <= 12 && Q.Co % MB == 0) {
-        int dev = 0, ncu = 0;
-        hipError_t e = hipGetDevice(&dev);
-        if (e == hipSuccess) e = hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev);
-        if (e != hipSuccess) return e;
         const uint32_t resident = ((uint32_t)ncu * OCC) & ~7u;
         if (resident >= 8 && blocks >= 3 * resident) grid = resident;
     }
-    auto kern = grid < blocks ? &conv_mfma_fast_kernel<HF, WF, CB, JX, CW, OCC, IMP, true>
-                              : &conv_mfma_fast_kernel<HF, WF, CB, JX, CW, OCC, IMP, false>;
+    // Leftover tiles: the workgroups go out in rounds that end together, and a compute unit is
+    // as fast with one workgroup as with OCC of them, so a layer takes as long as its busiest
+    // compute unit: ceil(tiles / ncu) tile times.  When the last blocks % ncu tiles are few (at
+    // most a quarter of the compute units: the pieces read their operands without sharing them
+    // through LDS, four times the traffic of a whole tile) they are cut into sixteenths.
+    constexpr bool TAILABLE = HF == 3 && WF == 3 && CB == 8;
+    bool tail = false;
+    if (TAILABLE && Q.Ci % 16 == 0 && grid == blocks && ncu >= 8 && ncu % 8 == 0 && blocks > (uint32_t)ncu) {
+        const uint32_t left = blocks % (uint32_t)ncu;
+        if (left > 0 && 4 * left <= (uint32_t)ncu) {
+            Q.nmain = blocks - left;
+            grid = Q.nmain + 16 * left;
+            tail = true;
+        }
+    }
+    void (*kern)(MfmaParams) = &conv_mfma_fast_kernel<HF, WF, CB, JX, CW, OCC, IMP, false, false>;
+    if (grid < blocks) kern = &conv_mfma_fast_kernel<HF, WF, CB, JX, CW, OCC, IMP, true, false>;
+    if (tail) kern = &conv_mfma_fast_kernel<HF, WF, CB, JX, CW, OCC, IMP, false, TAILABLE>;
     if (lds > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
     hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, st, Q);
@@ -452,6 +626,8 @@ hipError_t launch_conv_mfma_fast(MfmaParams P, const Shape &sh, uint32_t blocks,
         implicit ? (unsigned long long)sh.Ci * sh.Hi * (unsigned long long)sh.Wi * 4ull
                  : (unsigned long long)sh.Ci * sh.Ho * (unsigned long long)sh.rowlen * 4ull;
     if (img_bytes * (unsigned long long)(P.rmax + 1) >= (1ull << 32)) return hipErrorNotSupported;
+    // filter words likewise: 32-bit byte offsets from the tile's first filter row
+    if ((unsigned long long)sh.K * 4ull * MB >= (1ull << 32)) return hipErrorNotSupported;
     if (narrow && !implicit && sh.Hf == 3 && sh.Wf == 3 && sh.Ci % 8 == 0 && al16) {   // ablation: 8-byte filter chunks
         if (P.S <= 256) return launch_fast_t<3, 3, 8, 1, 2, 3, false>(P, blocks, st);
         if (P.S <= 512) return launch_fast_t<3, 3, 8, 2, 2, 3, false>(P, blocks, st);

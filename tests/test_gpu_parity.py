@@ -118,6 +118,32 @@ def test_many_tiles_per_workgroup(shape):
     assert torch.equal(dO.view(torch.int32), dO2.view(torch.int32))
 
 
+# Layers whose tile count leaves a few tiles (at most a quarter of the compute units) after the
+# last full round of the grid: the pipelined 3x3 kernel computes those in sixteen 16x16 pieces,
+# the four waves of a workgroup splitting the channels (a multiple of 16).  Tile counts are for
+# 256 compute units.
+LEFTOVER_TILE_SHAPES = [
+    (1, 16, 130, 130, 64, 3, 3, 1, 1),   # 265 tiles: 9 left; one channel group per wave; last tile has 4 pixels
+    (1, 48, 96, 96, 88, 3, 3, 1, 0),     # 278 tiles: 22 left; 3 groups per wave; second M tile: 24 of 64 rows
+    (11, 128, 78, 78, 40, 3, 3, 2, 1),   # 262 tiles: 6 left; 8 groups per wave (one refill); stride 2; tiles cross rows and images
+    (6, 32, 56, 56, 64, 3, 3, 1, 1),     # 294 tiles: 38 left
+]
+
+
+@pytest.mark.parametrize("shape", LEFTOVER_TILE_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_leftover_tiles_in_pieces(shape):
+    N, Ci, Hi, Wi, Co, Hf, Wf, s, p = shape
+    I, F = workloads.random_layer_inputs(7900 + sum(shape), N, Ci, Hi, Wi, Co, Hf, Wf)
+    print("leftover tiles", shape, flush=True)
+    check_layer(I, F, s, p, basic=False, twice=False)
+    dW = run_transform(I, Hf, Wf, s, p)
+    dO = run_conv(dW, F, N, Ci, Hi, Wi, s, p)
+    dO2 = torch.full_like(dO, float("nan"))
+    im2win.conv2d_im2win_implicit_fwd(I.cuda(), F.cuda(), dO2, N, Ci, Hi, Wi, Co, Hf, Wf, s, p)
+    torch.cuda.synchronize()
+    assert torch.equal(dO.view(torch.int32), dO2.view(torch.int32))
+
+
 def test_im2win_tensor_larger_than_4_gib():
     """A 5 GB im2win tensor (byte offsets pass 2^32): images at both ends and in the
     middle are checked in full, plus sampled outputs anywhere."""
