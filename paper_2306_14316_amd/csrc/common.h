@@ -30,6 +30,27 @@ __device__ __forceinline__ uint32_t fdiv(uint32_t n, const FastDiv &f)
     return (__umulhi(n, f.mul) + n) >> f.shift;
 }
 
+// Workgroups are handed to the 8 XCDs round-robin (block b runs on XCD b % 8)
+// and each XCD has its own L2.  Remap so that each XCD works through one
+// contiguous range of logical blocks: neighbouring items (the M tiles that share an
+// im2win strip, neighbouring strips; the transform's neighbouring output rows, which read the
+// same input rows) then meet in the same L2.
+__device__ __forceinline__ uint32_t xcd_swizzle(uint32_t b, uint32_t nblocks)
+{
+    const uint32_t x = b & 7u, i = b >> 3;
+    const uint32_t q = nblocks >> 3, r = nblocks & 7u;
+    return x * q + min(x, r) + i;
+}
+
+// The same idea for streaming kernels, kept local: within each group of 64 consecutive blocks
+// XCD x takes blocks 8x .. 8x+7, so neighbours meet in one L2 while the eight XCDs still write
+// one compact front (remapping the whole grid, as above, slowed large transforms by 7-9 %).
+__device__ __forceinline__ uint32_t xcd_swizzle64(uint32_t b, uint32_t nblocks)
+{
+    if (b >= (nblocks & ~63u)) return b;   // last partial group: as dealt
+    return (b & ~63u) | ((b & 7u) << 3) | ((b >> 3) & 7u);
+}
+
 // Shapes derived once on the host from the ABI arguments.
 struct Shape {
     int N, Ci, Hi, Wi, Co, Hf, Wf, s, p;

@@ -35,17 +35,6 @@ struct MfmaParams {
 
 __host__ __device__ inline int round4(int x) { return (x + 3) & ~3; }
 
-// Workgroups are handed to the 8 XCDs round-robin (block b runs on XCD b % 8)
-// and each XCD has its own L2.  Remap so that each XCD works through one
-// contiguous range of logical tiles: the M tiles that share an im2win strip,
-// and neighbouring strips, then meet in the same L2.
-__device__ __forceinline__ uint32_t xcd_swizzle(uint32_t b, uint32_t nblocks)
-{
-    const uint32_t x = b & 7u, i = b >> 3;
-    const uint32_t q = nblocks >> 3, r = nblocks & 7u;
-    return x * q + min(x, r) + i;
-}
-
 // Epilogue: accumulator register v of lane (h, l32) holds output channel
 // 8*(v/4) + 4*h + v%4 of the wave's 32 and pixel l32 of the wave's 32.  Pixels
 // are contiguous in NCHW for a fixed (image, channel), so every store

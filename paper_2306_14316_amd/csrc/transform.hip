@@ -24,7 +24,8 @@ struct TransformParams {
 template <int VEC>
 __global__ __launch_bounds__(256) void transform_kernel(TransformParams P)
 {
-    uint32_t y0 = (blockIdx.x * 256u + threadIdx.x) * VEC;
+    // consecutive blocks read overlapping input rows: keep them on one XCD (one L2)
+    uint32_t y0 = (xcd_swizzle64(blockIdx.x, gridDim.x) * 256u + threadIdx.x) * VEC;
     if (y0 >= P.total) return;
 
     uint32_t row = fdiv(y0, P.d_rowlen);          // (i*Ci + r)*Ho + m
@@ -94,8 +95,9 @@ __global__ __launch_bounds__(256) void transform_lds_kernel(TransformLdsParams P
     extern __shared__ __align__(16) unsigned char smem_t[];
     uint32_t *strip = reinterpret_cast<uint32_t *>(smem_t);   // [nrows][LW]
 
-    const uint32_t plane = fdiv(blockIdx.x, P.d_rb);
-    const int m0 = (int)(blockIdx.x - plane * (uint32_t)P.RB) * P.MR;
+    const uint32_t lb = xcd_swizzle64(blockIdx.x, gridDim.x);   // neighbours in a plane share input rows: same XCD
+    const uint32_t plane = fdiv(lb, P.d_rb);
+    const int m0 = (int)(lb - plane * (uint32_t)P.RB) * P.MR;
     const int mr = min(P.MR, P.Ho - m0);
     const int nrows = (mr - 1) * P.s + P.Hf;
     const int h_lo = m0 * P.s - P.p;
