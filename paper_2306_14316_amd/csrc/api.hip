@@ -28,13 +28,13 @@ im2win_status derive(int N, int Ci, int Hi, int Wi, int Co, int Hf, int Wf, int 
         *r = a * b;
         return *r <= kMaxElems;
     };
-    long long t, in_e, win_e, out_e, flt_e, col_e;
+    // every tensor of the call: input, im2win tensor, output, filter
+    long long t, in_e, win_e, out_e, flt_e;
     if (!mul_ok(n_in, Hi, &t) || !mul_ok(t, Wi, &in_e)) return IM2WIN_ERR_OVERFLOW;
     if (rowlen > kMaxElems || !mul_ok(n_in, Ho, &t) || !mul_ok(t, rowlen, &win_e)) return IM2WIN_ERR_OVERFLOW;
-    if (!mul_ok((long long)N * Co > kMaxElems ? kMaxElems + 1 : (long long)N * Co, Ho, &t) ||
-        !mul_ok(t, Wo, &out_e)) return IM2WIN_ERR_OVERFLOW;
+    if ((long long)N * Co > kMaxElems || !mul_ok((long long)N * Co, Ho, &t) || !mul_ok(t, Wo, &out_e))
+        return IM2WIN_ERR_OVERFLOW;
     if (khw > kMaxElems || !mul_ok(khw, Ci, &t) || !mul_ok(t, Co, &flt_e)) return IM2WIN_ERR_OVERFLOW;
-    (void)col_e; (void)in_e; (void)win_e; (void)out_e; (void)flt_e;
     sh->N = N; sh->Ci = Ci; sh->Hi = Hi; sh->Wi = Wi; sh->Co = Co; sh->Hf = Hf; sh->Wf = Wf;
     sh->s = stride; sh->p = pad;
     sh->Ho = (int)Ho; sh->Wo = (int)Wo; sh->Hp = (int)Hp; sh->Wp = (int)Wp;
