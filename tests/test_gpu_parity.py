@@ -83,6 +83,40 @@ def test_table2_layers_small_batch(L):
     check_layer(I, F, Ls.stride, Ls.pad, basic=False, twice=False)
 
 
+@pytest.mark.parametrize("L", workloads.TABLE2, ids=lambda l: l.name)
+def test_table2_layers_full_batch(L):
+    """The twelve layers of Table 2 at the paper's batch of 128, in the launch configuration the
+    benchmark times: the first and the last image in full (im2win tensor bit for bit, every
+    output), 20000 sampled outputs anywhere, and the workspace-free call bit for bit."""
+    N, Ci, Hi, Wi, Co, Hf, Wf, s, p = L.dims
+    print("layer", L.name, flush=True)
+    I, F = workloads.make_inputs(L)
+    dW = run_transform(I, Hf, Wf, s, p)
+    dO = run_conv(dW, F, N, Ci, Hi, Wi, s, p)
+    for i in (0, N - 1):
+        Ii = I[i:i + 1].numpy()
+        assert_bitwise_equal(dW[i:i + 1], oracle.im2win(Ii, Hf, Wf, s, p))
+        O_ref, B_ref = oracle.conv2d_direct(Ii, F.numpy(), s, p)
+        assert_conv_close(dO[i:i + 1].cpu().numpy(), O_ref, B_ref)
+    print("layer", L.name, "samples", flush=True)
+    Ho, Wo = im2win.im2win_out_shape(Hi, Wi, Hf, Wf, s, p)
+    rng = np.random.default_rng(L.seed)
+    idx = np.stack([rng.integers(0, N, 20000), rng.integers(0, Co, 20000),
+                    rng.integers(0, Ho, 20000), rng.integers(0, Wo, 20000)], axis=1).astype(np.int32)
+    O_s, B_s = oracle.conv2d_direct_at(I.numpy(), F.numpy(), s, p, idx)
+    ti = torch.from_numpy(idx.astype(np.int64)).cuda()
+    got = dO[ti[:, 0], ti[:, 1], ti[:, 2], ti[:, 3]].cpu().numpy().astype(np.float64)
+    assert np.isfinite(got).all()
+    assert (np.abs(got - O_s) <= 1e-4 * B_s).all()
+    assert bool(torch.isfinite(dO).all())
+    del dW
+    print("layer", L.name, "workspace-free", flush=True)
+    dO2 = torch.full_like(dO, float("nan"))
+    im2win.conv2d_im2win_implicit_fwd(I.cuda(), F.cuda(), dO2, N, Ci, Hi, Wi, Co, Hf, Wf, s, p)
+    torch.cuda.synchronize()
+    assert torch.equal(dO.view(torch.int32), dO2.view(torch.int32))
+
+
 @pytest.mark.parametrize("Co,pad", [(64, 0), (20, 1), (96, 1)])
 def test_three_channel_3x3_layer_with_many_pixels(Co, pad):
     """Table 2's Conv7 shape at batch 16: enough pixels for the tiles of four 64-pixel groups
