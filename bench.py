@@ -231,6 +231,19 @@ def _event_ms(fn, k):
     return e0.elapsed_time(e1) / k
 
 
+def device_copy_gbs():
+    """Bandwidth of a plain 256 MiB device-to-device copy (bytes read + bytes written per second):
+    what a streaming kernel with one read and one write stream reaches on this machine, the second
+    yardstick for the transform beside the 8 TB/s of the data sheet."""
+    import torch
+    src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(src)
+    _ramp(lambda: dst.copy_(src), 0.03)
+    ms = min(_event_ms(lambda: dst.copy_(src), 10) for _ in range(3))
+    del src, dst
+    return 2.0 * 256 * 1024 * 1024 / (ms * 1e-3) / 1e9
+
+
 def time_baselines(L, steps):
     """The comparison baselines on one layer, beside the im2win path (HIP events, average of
     `steps` launches each): the direct convolution, and im2col followed by a GEMM."""
@@ -348,6 +361,9 @@ def main():
         "paper_context": "paper reports ratios only, on an RTX 3090 at fp32, batch 128: im2win 3.5x im2col+cuBLAS, "
                          "1.1x (up to 1.8x) the fastest cuDNN algorithm, 5-155x a naive direct kernel",
     }
+    copy_gbs = device_copy_gbs()
+    out["roofline_transform"]["measured_copy_gbs"] = copy_gbs
+    out["roofline_transform"]["frac_of_measured_copy"] = rep["transform_gbs_avg"] / copy_gbs
     if a.layers == "all":
         reps = []
         for other in workloads.LAYERS:
