@@ -209,6 +209,7 @@ static void fill_params(MfmaParams &P, const float *win, const float *flt, float
     P.howo = (uint32_t)(sh.Ho * sh.Wo);
     P.chan_stride = (uint32_t)((size_t)sh.Ho * sh.rowlen);
     P.win_elems = (size_t)sh.N * sh.Ci * sh.Ho * (size_t)sh.rowlen;
+    P.out_elems = (size_t)sh.npix * sh.Co;
     P.implicit = 0;
     P.Hi = sh.Hi; P.Wi = sh.Wi; P.p = sh.p;
     P.in_plane = (uint32_t)(sh.Hi * sh.Wi);

@@ -208,6 +208,8 @@ __global__ __launch_bounds__(256, OCC) void conv_mfma_fast_kernel(MfmaParams P)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave & 1, wn = wave >> 1;
     const int h = lane >> 5, l32 = lane & 31;
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);   // the same, known to be wave-uniform
+    const int wm_u = wave_u & 1, wn_u = wave_u >> 1;
 
     if constexpr (TAIL) if (blockIdx.x >= P.nmain) {
         // Piece q of leftover tile t.  Workgroup b runs on XCD b % 8 and P.nmain is a multiple
@@ -223,7 +225,7 @@ __global__ __launch_bounds__(256, OCC) void conv_mfma_fast_kernel(MfmaParams P)
             q = s2 / Lr;
             t = full + (s2 - q * Lr);
         }
-        tail_piece<HF, WF, IMP>(P, P.nmain + t, (int)q, lds, lane, __builtin_amdgcn_readfirstlane(wave));
+        tail_piece<HF, WF, IMP>(P, P.nmain + t, (int)q, lds, lane, wave_u);
         return;
     }
 
@@ -536,7 +538,7 @@ __global__ __launch_bounds__(256, OCC) void conv_mfma_fast_kernel(MfmaParams P)
             block(0, I0{}, F{}, F{}, F{}, F{});
         }
 
-        store_tile(P, acc, P0_c, Pend_c, m0_c, wm, wn, h, l32);
+        store_tile_desc(P, acc, P0_c, Pend_c, m0_c, wm_u, wn_u, h, l32);
         if (!has_next) break;
 
         // the next tile becomes the current one
@@ -628,6 +630,9 @@ hipError_t launch_conv_mfma_fast(MfmaParams P, const Shape &sh, uint32_t blocks,
     if (img_bytes * (unsigned long long)(P.rmax + 1) >= (1ull << 32)) return hipErrorNotSupported;
     // filter words likewise: 32-bit byte offsets from the tile's first filter row
     if ((unsigned long long)sh.K * 4ull * MB >= (1ull << 32)) return hipErrorNotSupported;
+    // output words: 32-bit byte offsets from (image of the tile's first pixel, first channel of the wave)
+    if (((unsigned long long)sh.Co * (unsigned long long)P.rmax + 64ull) * (unsigned long long)sh.Ho * sh.Wo * 4ull >= (1ull << 32))
+        return hipErrorNotSupported;
     if (narrow && !implicit && sh.Hf == 3 && sh.Wf == 3 && sh.Ci % 8 == 0 && al16) {   // ablation: 8-byte filter chunks
         if (P.S <= 256) return launch_fast_t<3, 3, 8, 1, 2, 3, false>(P, blocks, st);
         if (P.S <= 512) return launch_fast_t<3, 3, 8, 2, 2, 3, false>(P, blocks, st);

@@ -18,6 +18,7 @@ struct MfmaParams {
     int rowlen, khw, K;
     uint32_t npix, howo, chan_stride;
     size_t win_elems;   // floats in the whole im2win tensor
+    size_t out_elems;   // floats in the output
     // workspace-free variant only: `win` is then the NCHW input itself
     int implicit;       // 1: workspace-free variant
     int Hi, Wi, p;
@@ -51,6 +52,49 @@ __device__ __forceinline__ void store_tile(const MfmaParams &P, const floatx16 &
         for (int v = 0; v < 16; ++v) {
             const int j = m0 + wm * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
             if (j < P.Co) o[(size_t)j * P.howo] = acc[v];
+        }
+    }
+}
+
+// The same epilogue through a buffer descriptor, for the pipelined kernel: the base (image of
+// the tile's first pixel, first channel of the wave) is wave-uniform and sits in scalar
+// registers, the lane adds one 32-bit byte offset (its pixel, its first channel) and each store
+// a scalar channel offset, so the sixteen stores cost no vector-ALU address arithmetic (plain
+// pointer stores cost eight vector instructions each, which comes out of the MFMA rate).  The
+// host has checked that a tile's outputs lie within 4 GiB of that base.  wm, wn: wave-uniform.
+__device__ __forceinline__ void store_tile_desc(const MfmaParams &P, const floatx16 &acc, uint32_t P0,
+                                                uint32_t Pend, int m0, int wm, int wn, int h, int l32)
+{
+    const int jw = m0 + wm * 32;                  // first channel of the wave
+    if (jw >= P.Co) return;
+    const uint32_t img0 = fdiv(P0, P.d_howo);     // image of the tile's first pixel
+    const size_t obase = ((size_t)img0 * P.Co + (size_t)jw) * P.howo;
+    const size_t left = (P.out_elems - obase) * 4u;
+    const __amdgpu_buffer_rsrc_t ro = __builtin_amdgcn_make_buffer_rsrc(
+        P.out + obase, 0, left < 0xffffffffull ? left : 0xffffffffull, 0x00020000);
+    const uint32_t Pm = P0 + (uint32_t)(wn * 32 + l32);
+    if (Pm <= Pend) {
+        const uint32_t img = fdiv(Pm, P.d_howo);
+        const uint32_t pin = Pm - img * P.howo;
+        const uint32_t voff = ((img - img0) * (uint32_t)P.Co * P.howo + pin + (uint32_t)(4 * h) * P.howo) * 4u;
+        const uint32_t howo4 = P.howo * 4u;
+        const bool full = jw + 32 <= P.Co;        // wave-uniform: every channel of the wave exists
+        const int room = P.Co - jw - 4 * h;       // channels this lane may store, counted from its first
+        if (full) {   // scalar branch: sixteen unconditional stores
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const float val = acc[v];   // (a scalar copy: bit-casting the vector element directly stores element 0)
+                __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, val), ro, voff,
+                                                      (uint32_t)(8 * (v >> 2) + (v & 3)) * howo4, 0);
+            }
+        } else {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int dj = 8 * (v >> 2) + (v & 3);
+                const float val = acc[v];
+                if (dj < room)
+                    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, val), ro, voff, (uint32_t)dj * howo4, 0);
+            }
         }
     }
 }
