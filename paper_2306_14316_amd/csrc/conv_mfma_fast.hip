@@ -329,6 +329,27 @@ __global__ __launch_bounds__(256, OCC) void conv_mfma_fast_kernel(MfmaParams P)
     tile_geometry(blockIdx.x, P0_c, Pend_c, m0_c, bp_c, soffb_c, loffI_c, zero_c, rf_c, rw_c);
     const int m0 = m0_c;   // (filter staging below: with several tiles per workgroup every row of every tile is live)
 
+    // Prefetch registers for the strip words: two alternating sets (the words come from HBM
+    // and are given about one and a half K blocks to arrive).  Global loads go through the
+    // tiles' buffer descriptors: a wave-uniform base held in scalar registers, the thread's
+    // constant 32-bit byte offset, and a scalar offset that selects the K block and channel.
+    // The K loop spends no vector ALU work on addresses.
+    float ir[2][CB * JX];
+    const uint32_t plane_bytes = (IMP ? P.in_plane : P.chan_stride) * 4u;
+    auto load_i = [&](int kb, int set, int c, int j, const __amdgpu_buffer_rsrc_t &rw, const uint32_t (&soffb)[JX]) __attribute__((always_inline)) {
+        ir[set][c * JX + j] = __builtin_bit_cast(
+            float, __builtin_amdgcn_raw_buffer_load_b32(rw, soffb[j], (uint32_t)(kb * CB + c) * plane_bytes, 0));
+    };
+    // The strip words of the first tile's first two K blocks are requested here, before the
+    // filter staging coordinates are worked out: they have the longest way to come.
+    const int nkb = P.Ci / CB;
+#pragma unroll
+    for (int w = 0; w < CB * JX; ++w) load_i(0, 0, w / JX, w % JX, rw_c, soffb_c);
+    if (nkb > 1) {
+#pragma unroll
+        for (int w = 0; w < CB * JX; ++w) load_i(1, 1, w / JX, w % JX, rw_c, soffb_c);
+    }
+
     // ---- filter staging coordinates of this thread's chunks ----
     // The tile is MB rows x CPR chunks of CW floats.  Chunk columns are dealt out
     // so that each dword LDS write of a half-wave is conflict-free with the odd
@@ -370,15 +391,8 @@ __global__ __launch_bounds__(256, OCC) void conv_mfma_fast_kernel(MfmaParams P)
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
 
-    // Prefetch registers: one set for the filter chunks (they come from L2), two
-    // alternating sets for the strip words (they come from HBM and are given about
-    // one and a half K blocks to arrive).
+    // Prefetch registers of the filter chunks: one set (they come from L2).
     float fr[JF][CW];
-    float ir[2][CB * JX];
-    // Global loads go through the tiles' buffer descriptors: a wave-uniform base held in scalar
-    // registers, the thread's constant 32-bit byte offset, and a scalar offset that selects the
-    // K block and channel.  The K loop spends no vector ALU work on addresses.
-    const uint32_t plane_bytes = (IMP ? P.in_plane : P.chan_stride) * 4u;
 
     auto load_f = [&](int kb, int j, const __amdgpu_buffer_rsrc_t &rf) __attribute__((always_inline)) {
         if (CW == 4) {
@@ -388,10 +402,6 @@ __global__ __launch_bounds__(256, OCC) void conv_mfma_fast_kernel(MfmaParams P)
             const float2v w = __builtin_bit_cast(float2v, __builtin_amdgcn_raw_buffer_load_b64(rf, goffb[j], kb * (KB * 4), 0));
             fr[j][0] = w.x; fr[j][1] = w.y;
         }
-    };
-    auto load_i = [&](int kb, int set, int c, int j, const __amdgpu_buffer_rsrc_t &rw, const uint32_t (&soffb)[JX]) __attribute__((always_inline)) {
-        ir[set][c * JX + j] = __builtin_bit_cast(
-            float, __builtin_amdgcn_raw_buffer_load_b32(rw, soffb[j], (uint32_t)(kb * CB + c) * plane_bytes, 0));
     };
     auto store_f = [&](int st, int j, int half) __attribute__((always_inline)) {   // words 2*half, 2*half+1 of chunk j
         lds_float *d = (lds_float *)lds + st * STAGE + loff[j] + 2 * half;
@@ -443,7 +453,6 @@ __global__ __launch_bounds__(256, OCC) void conv_mfma_fast_kernel(MfmaParams P)
     // NX1 / NX2: the block after this one / the one after that belongs to the next tile (a
     // workgroup with several tiles keeps the pipeline running across the tile boundary);
     // kb2: index, within its own tile, of the block whose global loads are issued here.
-    const int nkb = P.Ci / CB;
     auto block = [&](int kb2, auto stc, auto has1c, auto has2c, auto nx1c, auto nx2c) __attribute__((always_inline)) {
         constexpr int ST = decltype(stc)::value;
         constexpr bool HAS1 = decltype(has1c)::value, HAS2 = decltype(has2c)::value;
@@ -494,8 +503,6 @@ __global__ __launch_bounds__(256, OCC) void conv_mfma_fast_kernel(MfmaParams P)
 #pragma unroll
     for (int j = 0; j < JF; ++j) load_f(0, j, rf_c);
 #pragma unroll
-    for (int w = 0; w < NIW; ++w) load_i(0, 0, w / JX, w % JX, rw_c, soffb_c);
-#pragma unroll
     for (int j = 0; j < JF; ++j)
 #pragma unroll
         for (int hh = 0; hh < HPC; ++hh) store_f(0, j, hh);
@@ -504,8 +511,6 @@ __global__ __launch_bounds__(256, OCC) void conv_mfma_fast_kernel(MfmaParams P)
     if (nkb > 1) {
 #pragma unroll
         for (int j = 0; j < JF; ++j) load_f(1, j, rf_c);
-#pragma unroll
-        for (int w = 0; w < NIW; ++w) load_i(1, 1, w / JX, w % JX, rw_c, soffb_c);
     }
     __syncthreads();
 #pragma unroll
