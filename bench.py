@@ -152,7 +152,9 @@ def kernel_names(L):
         conv = "conv_mfma_fast_kernel"
     else:
         conv = "conv_mfma_kernel"
-    return conv, ("transform_lds_kernel" if L.Hf >= 5 and L.Wp >= 64 else "transform_kernel")
+    moved = 4 * L.N * L.Ci * (L.Hi * L.Wi + L.Ho * L.Wp * L.Hf)
+    staged = (L.Hf >= 5 and L.Wp >= 64) or (L.Hf >= 3 and L.Wp >= 48 and moved >= 192 * 2 ** 20)
+    return conv, ("transform_lds_kernel" if staged else "transform_kernel")
 
 
 def layer_report(L, t):

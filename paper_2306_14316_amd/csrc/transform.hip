@@ -194,9 +194,16 @@ static int lds_rows_per_block(const Shape &sh, int LW, size_t budget_bytes)
 
 hipError_t launch_transform(const float *in, float *win, const Shape &sh, hipStream_t st)
 {
-    // Tall windows over wide rows (and an aligned tensor) take the LDS-staged kernel;
-    // on small planes or short windows the plain gather is as fast or faster.
-    if (sh.Hf >= 5 && sh.Wp >= 64 && (reinterpret_cast<uintptr_t>(win) & 15u) == 0) {
+    // Which kernel (measured on the layers of Table 2 and on sweeps of 3x3 shapes): tall windows
+    // over wide rows take the LDS-staged kernel; so do short windows (3x3) once the tensors are
+    // large -- past about the size of the 256 MB memory-side cache the plain gather drops from
+    // 5 to 4.2 TB/s while the staged kernel holds 5.2-5.9 TB/s on rows of 48 words and more.
+    // On small planes or small tensors the plain gather is as fast or faster.
+    const unsigned long long moved =
+        4ull * (unsigned long long)sh.N * sh.Ci * ((unsigned long long)sh.Hi * sh.Wi + (unsigned long long)sh.Ho * sh.rowlen);
+    const bool tall = sh.Hf >= 5 && sh.Wp >= 64;
+    const bool large = sh.Hf >= 3 && sh.Wp >= 48 && moved >= (192ull << 20);
+    if ((tall || large) && (reinterpret_cast<uintptr_t>(win) & 15u) == 0) {
         const int LW = lds_pitch(sh.Wp, sh.Hf);
         const int MR = lds_rows_per_block(sh, LW, 32 * 1024);
         const long long blocks = MR ? (long long)sh.N * sh.Ci * ((sh.Ho + MR - 1) / MR) : 0;

@@ -286,6 +286,33 @@ def test_transform_tall_windows(shape):
     assert torch.isnan(buf[:32]).all() and torch.isnan(buf[32 + n:]).all()   # nothing written outside
 
 
+# (N, Ci, Hi, Wi, Hf, s, p): short windows on tensors large enough (input + im2win tensor of
+# 192 MiB or more, rows of 48 words or more) for the LDS-staged transform to be chosen
+LARGE_SHORT_WINDOW_SHAPES = [
+    (64, 20, 150, 131, 3, 1, 1),   # odd row length (399 words): stretches start at every word offset mod 4
+    (96, 24, 150, 131, 3, 2, 2),   # stride 2, two rows and columns of padding
+    (40, 16, 161, 190, 4, 1, 0),   # a four-row window
+]
+
+
+@pytest.mark.parametrize("shape", LARGE_SHORT_WINDOW_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_transform_short_windows_large_tensors(shape):
+    N, Ci, Hi, Wi, Hf, s, p = shape
+    Ho, _ = im2win.im2win_out_shape(Hi, Wi, Hf, 1, s, p)
+    n = N * Ci * Ho * (Wi + 2 * p) * Hf
+    assert 4 * (N * Ci * Hi * Wi + n) >= 192 * 2 ** 20 and Wi + 2 * p >= 48
+    g = torch.Generator(device="cpu")
+    g.manual_seed(8100 + sum(shape))
+    I = torch.randn((N, Ci, Hi, Wi), generator=g, dtype=torch.float32)
+    print("transform shape", shape, flush=True)
+    buf = torch.full((n + 64,), float("nan"), dtype=torch.float32, device="cuda")
+    win = buf[32:32 + n]
+    im2win.im2win_transform(I.cuda(), win, N, Ci, Hi, Wi, Hf, 1, s, p)
+    torch.cuda.synchronize()
+    assert_bitwise_equal(win.reshape(N, Ci, Ho, -1), oracle.im2win(I.numpy(), Hf, 1, s, p))
+    assert torch.isnan(buf[:32]).all() and torch.isnan(buf[32 + n:]).all()   # nothing written outside
+
+
 def test_transform_unaligned_output_pointer():
     """A window buffer that is only 4-byte aligned takes the scalar-store path."""
     N, Ci, Hi, Wi, Hf, Wf, s, p = 2, 3, 9, 10, 3, 3, 1, 1
