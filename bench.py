@@ -98,8 +98,10 @@ def time_layer(L, steps, warmup):
     torch.cuda.synchronize()
 
     # Kernel-level HIP events are recorded on every EVERY-th step of the timed
-    # region (on all of them they would add several microseconds to each step).
-    EVERY = 5
+    # region: an evented step takes about 17 us longer (the markers keep the two
+    # kernels from being dispatched back to back), so on all steps they would
+    # distort the step time they are there to explain.
+    EVERY = 10
     ev = {k: [torch.cuda.Event(enable_timing=True) for _ in range(3)] for k in range(0, steps, EVERY)}
     torch.cuda.synchronize()
     t0 = time.perf_counter()
