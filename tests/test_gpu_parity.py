@@ -207,6 +207,41 @@ def test_im2win_tensor_larger_than_4_gib():
     assert not bool(torch.isnan(dO).any())
 
 
+def test_output_planes_beyond_32_bit_offsets():
+    """One 2900x2900 image, 64 output channels: an output tile's channels lie more than 4 GiB
+    apart, past the 32-bit offsets of the pipelined kernel's stores, so the layer must take a
+    kernel that addresses its output with full pointers.  Sampled outputs, plus the first and
+    the last output rows of every channel in full (the ends of the 2.1 GB output)."""
+    N, Ci, Hi, Wi, Co, Hf, Wf, s, p = 1, 8, 2900, 2900, 64, 3, 3, 1, 0
+    g = torch.Generator(device="cpu")
+    g.manual_seed(4343)
+    I = torch.rand((N, Ci, Hi, Wi), generator=g, dtype=torch.float32)
+    F = torch.randn((Co, Ci, Hf, Wf), generator=g, dtype=torch.float32) * 0.15
+    Ho, Wo = im2win.im2win_out_shape(Hi, Wi, Hf, Wf, s, p)
+    assert 4 * Co * Ho * Wo > 2 ** 31
+    print("huge image: transform + convolution", flush=True)
+    dW = run_transform(I, Hf, Wf, s, p)
+    dO = run_conv(dW, F, N, Ci, Hi, Wi, s, p)
+    assert bool(torch.isfinite(dO).all())
+    rng = np.random.default_rng(11)
+    idx = np.stack([np.zeros(20000, dtype=np.int64), rng.integers(0, Co, 20000),
+                    rng.integers(0, Ho, 20000), rng.integers(0, Wo, 20000)], axis=1)
+    rows = np.array([(0, j, m, n) for j in range(Co) for m in (0, Ho - 1) for n in range(0, Wo, 7)])
+    idx = np.concatenate([idx, rows]).astype(np.int32)
+    O_s, B_s = oracle.conv2d_direct_at(I.numpy(), F.numpy(), s, p, idx)
+    ti = torch.from_numpy(idx.astype(np.int64)).cuda()
+    got = dO[ti[:, 0], ti[:, 1], ti[:, 2], ti[:, 3]].cpu().numpy().astype(np.float64)
+    assert (np.abs(got - O_s) <= 1e-4 * B_s).all()
+    del dW
+    print("huge image: workspace-free", flush=True)
+    dO2 = torch.full_like(dO, float("nan"))
+    im2win.conv2d_im2win_implicit_fwd(I.cuda(), F.cuda(), dO2, N, Ci, Hi, Wi, Co, Hf, Wf, s, p)
+    torch.cuda.synchronize()
+    got2 = dO2[ti[:, 0], ti[:, 1], ti[:, 2], ti[:, 3]].cpu().numpy().astype(np.float64)
+    assert (np.abs(got2 - O_s) <= 1e-4 * B_s).all()
+    assert bool(torch.isfinite(dO2).all())
+
+
 @pytest.mark.parametrize("idx", [1, 2])
 def test_basic_kernel_on_benchmark_layers(idx):
     L = workloads.layer(idx)
