@@ -207,14 +207,16 @@ def test_im2win_tensor_larger_than_4_gib():
     assert not bool(torch.isnan(dO).any())
 
 
-def test_output_planes_beyond_32_bit_offsets():
+@pytest.mark.parametrize("Ci", [8, 3])
+def test_output_planes_beyond_32_bit_offsets(Ci):
     """One 2900x2900 image, 64 output channels: an output tile's channels lie more than 4 GiB
-    apart, past the 32-bit offsets of the pipelined kernel's stores, so the layer must take a
-    kernel that addresses its output with full pointers.  Sampled outputs, plus the first and
-    the last output rows of every channel in full (the ends of the 2.1 GB output)."""
-    N, Ci, Hi, Wi, Co, Hf, Wf, s, p = 1, 8, 2900, 2900, 64, 3, 3, 1, 0
+    apart, past the 32-bit offsets of the stores of the pipelined kernel (8 input channels)
+    and of the filter-stationary kernel (3 input channels), so the layer must take a kernel
+    that addresses its output with full pointers.  Sampled outputs, plus the first and the last
+    output rows of every channel (the ends of the 2.1 GB output)."""
+    N, Hi, Wi, Co, Hf, Wf, s, p = 1, 2900, 2900, 64, 3, 3, 1, 0
     g = torch.Generator(device="cpu")
-    g.manual_seed(4343)
+    g.manual_seed(4343 + Ci)
     I = torch.rand((N, Ci, Hi, Wi), generator=g, dtype=torch.float32)
     F = torch.randn((Co, Ci, Hf, Wf), generator=g, dtype=torch.float32) * 0.15
     Ho, Wo = im2win.im2win_out_shape(Hi, Wi, Hf, Wf, s, p)
