@@ -45,9 +45,10 @@ constexpr int pick_ring(int nm)
 // sums are added in a fixed order through LDS.  The waves share no operand, so nothing is
 // staged in LDS and the K loop has no barrier: a lane's filter taps of one channel and its
 // pixel's window of one channel are both contiguous runs in memory (the window order of
-// Section 3.1), read straight into registers D channel groups ahead.  The pieces are small
-// because freed workgroup slots are refilled at once: the pieces land three to a compute unit
-// on the units that finish first, and three of them must still be short.
+// Section 3.1), read straight into registers D channel groups ahead.  A piece lasts one cold
+// load latency plus its MFMA chain: sixteenths keep the chain short and, for 64 channels, have
+// every load in flight at once (32x32 quadrants with the same wave split exposed a second load
+// latency and gained nothing).
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 template <int HF, int WF, bool IMP>
@@ -183,7 +184,11 @@ __device__ __forceinline__ void tail_piece(const MfmaParams &P, uint32_t lt, int
 // PER: the grid may hold fewer workgroups than tiles; a workgroup then takes tiles blockIdx.x,
 // + gridDim.x, ... and keeps the pipeline running across tile boundaries.
 // TAIL: workgroups P.nmain and up take one sixteenth each of the tiles P.nmain .. P.nblocks-1.
-template <int HF, int WF, int CB, int JX, int CW, int OCC, bool IMP, bool PER, bool TAIL>
+// HALF: workgroups P.nmain and up take one half (32 pixels) each of the tiles P.nmain ..
+// P.nblocks-1, two waves per 32x32 block of outputs, each multiplying half of the channels of
+// every K block (the two partial sums meet in LDS before the store).  For leftovers too many
+// for the sixteenths: a half tile is staged through LDS like a whole one, at 3/4 of its traffic.
+template <int HF, int WF, int CB, int JX, int CW, int OCC, bool IMP, bool PER, bool TAIL, bool HALF = false>
 __global__ __launch_bounds__(256, OCC) void conv_mfma_fast_kernel(MfmaParams P)
 {
     constexpr int KHW = HF * WF;
@@ -210,6 +215,15 @@ __global__ __launch_bounds__(256, OCC) void conv_mfma_fast_kernel(MfmaParams P)
     const int h = lane >> 5, l32 = lane & 31;
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);   // the same, known to be wave-uniform
     const int wm_u = wave_u & 1, wn_u = wave_u >> 1;
+    static_assert(!HALF || (!PER && !TAIL && (CB / 2) % 2 == 0 && ((CB / 4) * HF * WF) % pick_ring((CB / 2) * HF * WF) == 0),
+                  "half tiles: the channel pairs of a K block split evenly between two waves");
+    // half-tile workgroups: which tile, which half; waves 0/1 take the first half of the channel
+    // pairs of every K block, waves 2/3 the second (hk = 1)
+    const bool hmode = HALF && blockIdx.x >= P.nmain;                       // workgroup-uniform
+    const uint32_t vb_first = hmode ? P.nmain + ((blockIdx.x - P.nmain) >> 1) : blockIdx.x;
+    const int hpix = hmode ? (int)((blockIdx.x - P.nmain) & 1u) * 32 : 0;   // first pixel of the half, within the tile
+    const int wn_g = hmode ? 0 : wn;             // pixel block of the wave within the (half) tile
+    const int hk = hmode ? (wave >> 1) : 0, hk_u = hmode ? (wave_u >> 1) : 0;
 
     if constexpr (TAIL) if (blockIdx.x >= P.nmain) {
         // Piece q of leftover tile t.  Workgroup b runs on XCD b % 8 and P.nmain is a multiple
@@ -259,12 +273,16 @@ __global__ __launch_bounds__(256, OCC) void conv_mfma_fast_kernel(MfmaParams P)
     auto tile_geometry = [&](uint32_t vb, uint32_t &P0, uint32_t &Pend, int &m0, const lds_float *&bp,
                              uint32_t (&soffb)[JX], int (&loffI)[JX], uint32_t &zero,
                              __amdgpu_buffer_rsrc_t &rf, __amdgpu_buffer_rsrc_t &rw) __attribute__((always_inline)) {
-        const uint32_t lb = xcd_swizzle(vb, TAIL ? P.nmain : ntiles);
+        const uint32_t lb = (TAIL || HALF) ? (vb < P.nmain ? xcd_swizzle(vb, P.nmain) : vb) : xcd_swizzle(vb, ntiles);
         const uint32_t tile_n = fdiv(lb, P.d_tm);
         const uint32_t tile_m = lb - tile_n * (uint32_t)P.tiles_m;
         m0 = (int)tile_m * MB;
         P0 = tile_n * NB;
         Pend = min(P0 + NB - 1, P.npix - 1);
+        if (HALF && hmode) {   // the half's own 32 pixels (the caller has checked that it has any)
+            P0 += (uint32_t)hpix;
+            Pend = min(P0 + 31u, Pend);
+        }
 
         // strip geometry (rows q0..q1 of output pixels, q = i*Ho + m)
         const uint32_t q0 = fdiv(P0, P.d_wo), q1 = fdiv(Pend, P.d_wo);
@@ -319,14 +337,18 @@ __global__ __launch_bounds__(256, OCC) void conv_mfma_fast_kernel(MfmaParams P)
             }
         }
         // per-lane B operand base: the lane's window start in the LDS strip
-        const uint32_t Pl = min(P0 + (uint32_t)(wn * 32 + l32), Pend);
+        const uint32_t Pl = min(P0 + (uint32_t)(wn_g * 32 + l32), Pend);
         const uint32_t ql = fdiv(Pl, P.d_wo);
         const int nl = (int)(Pl - ql * (uint32_t)P.Wo);
         const int rhol = (int)(ql - q0);
         const int b_base = rhol == 0 ? (nl - nlo0) * sHf : len0 + (rhol - 1) * P.fullseg + nl * sHf;
-        bp = (const lds_float *)lds + SF_FLOATS + b_base + h * SS;
+        bp = (const lds_float *)lds + SF_FLOATS + b_base + h * SS + hk * ((CB / 2) * SS);
     };
-    tile_geometry(blockIdx.x, P0_c, Pend_c, m0_c, bp_c, soffb_c, loffI_c, zero_c, rf_c, rw_c);
+    if (HALF && hmode) {   // a ragged last tile may have no pixel in its second half (whole workgroup)
+        const uint32_t tn = fdiv(vb_first, P.d_tm);
+        if (tn * NB + (uint32_t)hpix >= P.npix) return;
+    }
+    tile_geometry(vb_first, P0_c, Pend_c, m0_c, bp_c, soffb_c, loffI_c, zero_c, rf_c, rw_c);
     const int m0 = m0_c;   // (filter staging below: with several tiles per workgroup every row of every tile is live)
 
     // Prefetch registers for the strip words: two alternating sets (the words come from HBM
@@ -384,7 +406,7 @@ __global__ __launch_bounds__(256, OCC) void conv_mfma_fast_kernel(MfmaParams P)
     // the same place), which keeps the staging code free of branches.
     if (tid + 256 * (JF - 1) >= NFC) { goffb[JF - 1] = goffb[0]; loff[JF - 1] = loff[0]; }
 
-    const lds_float *ap0 = (const lds_float *)lds + (wm * 32 + l32) * PF + h * KHW;
+    const lds_float *ap0 = (const lds_float *)lds + (wm * 32 + l32) * PF + h * KHW + hk * ((CB / 2) * KHW);
     float *wI0 = lds + SF_FLOATS + tid;
 
     floatx16 acc;
@@ -516,6 +538,75 @@ __global__ __launch_bounds__(256, OCC) void conv_mfma_fast_kernel(MfmaParams P)
 #pragma unroll
     for (int i = 0; i < R; ++i) lds_op(0, i, bp_c);
 
+    // ---- half tile: the same pipeline with half of the MFMA steps per K block ----
+    if constexpr (HALF) if (hmode) {
+        constexpr int NMH = NM / 2;          // this wave's MFMAs per block: its half of the channel pairs
+        constexpr int NSLOTH = NMH - R;      // MFMAs before the barrier
+        constexpr int NITEM = NFW + NIWS + NIW;              // staging items: filter half-stores, strip stores (two each), strip loads
+        constexpr int IPS = (NITEM + NSLOTH - 1) / NSLOTH;   // items per slot
+        static_assert(NSLOTH > 0, "K block too short for the pipeline");
+        auto block_half = [&](int kb2, auto stc, auto has1c, auto has2c) __attribute__((always_inline)) {
+            constexpr int ST = decltype(stc)::value;
+            constexpr bool HAS1 = decltype(has1c)::value, HAS2 = decltype(has2c)::value;
+#pragma unroll
+            for (int i = 0; i < NMH; ++i) {
+                if (HAS1 && i == NSLOTH) __syncthreads();
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i % R], b[i % R], acc, 0, 0, 0);
+                if (i + R < NMH) lds_op(ST, i + R, bp_c);
+                else if (HAS1) lds_op(ST ^ 1, i + R - NMH, bp_c);
+                if (i < NSLOTH) {
+#pragma unroll
+                    for (int it = i * IPS; it < (i + 1) * IPS && it < NITEM; ++it) {
+                        if (it < NFW) {                       // filter chunk it/HPC: store a half, then reload it
+                            if (HAS1) store_f(ST ^ 1, it / HPC, it % HPC);
+                            if (HAS2 && (it % HPC == HPC - 1)) load_f(kb2, it / HPC, rf_c);
+                        } else if (it < NFW + NIWS) {         // strip words of the next block: two stores
+                            if (HAS1) {
+                                const int w = 2 * (it - NFW);
+                                store_i(ST ^ 1, ST ^ 1, w / JX, w % JX, loffI_c, zero_c);
+                                if (w + 1 < NIW) store_i(ST ^ 1, ST ^ 1, (w + 1) / JX, (w + 1) % JX, loffI_c, zero_c);
+                            }
+                        } else {                              // strip words of the block after that
+                            const int w = it - NFW - NIWS;
+                            if (HAS2) load_i(kb2, ST, w / JX, w % JX, rw_c, soffb_c);
+                        }
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        };
+        int kb = 0;
+        for (; kb + 3 < nkb; kb += 2) {
+            block_half(kb + 2, I0{}, T{}, T{});
+            block_half(kb + 3, I1{}, T{}, T{});
+        }
+        const int rem = nkb - kb;   // 1, 2 or 3 blocks left
+        if (rem == 3) {
+            block_half(kb + 2, I0{}, T{}, T{});
+            block_half(0, I1{}, T{}, F{});
+            block_half(0, I0{}, F{}, F{});
+        } else if (rem == 2) {
+            block_half(0, I0{}, T{}, F{});
+            block_half(0, I1{}, F{}, F{});
+        } else {
+            block_half(0, I0{}, F{}, F{});
+        }
+        // the two partial sums of a block of outputs: waves 2/3 hand theirs to waves 0/1 through
+        // LDS (every wave has taken its last operands before the stages are overwritten)
+        __syncthreads();
+        if (hk_u) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) lds[((wm_u * 16 + v) * 64) + lane] = acc[v];
+        }
+        __syncthreads();
+        if (!hk_u) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[v] += lds[((wm_u * 16 + v) * 64) + lane];
+            store_tile_desc(P, acc, P0_c, Pend_c, m0_c, wm_u, 0, h, l32);
+        }
+        return;
+    }
+
     // ---- tiles of this workgroup ----
     // The host gives a workgroup more than one tile only when nkb is even (every tile then
     // starts in LDS stage 0) and Co is a multiple of the tile height.
@@ -586,21 +677,37 @@ static hipError_t launch_fast_t(const MfmaParams &P, uint32_t blocks, hipStream_
     // Leftover tiles: the workgroups go out in rounds that end together, and a compute unit is
     // as fast with one workgroup as with OCC of them, so a layer takes as long as its busiest
     // compute unit: ceil(tiles / ncu) tile times.  When the last blocks % ncu tiles are few (at
-    // most a quarter of the compute units: the pieces read their operands without sharing them
-    // through LDS, four times the traffic of a whole tile) they are cut into sixteenths.
+    // most an eighth of the compute units: the pieces read their operands without sharing them
+    // through LDS, four times the traffic of a whole tile; measured against the halves below on
+    // 64- and 256-channel layers, they win up to about 32-44 leftover tiles of 256) they are cut
+    // into sixteenths.
     constexpr bool TAILABLE = HF == 3 && WF == 3 && CB == 8;
     bool tail = false;
     if (TAILABLE && Q.Ci % 16 == 0 && grid == blocks && ncu >= 8 && ncu % 8 == 0 && blocks > (uint32_t)ncu) {
         const uint32_t left = blocks % (uint32_t)ncu;
-        if (left > 0 && 4 * left <= (uint32_t)ncu) {
+        if (left > 0 && 8 * left <= (uint32_t)ncu) {
             Q.nmain = blocks - left;
             grid = Q.nmain + 16 * left;
             tail = true;
         }
     }
+    // More leftover tiles than that, up to half of the compute units: each is cut into two halves
+    // of 32 pixels, staged through LDS like a whole tile; a compute unit then ends with one whole
+    // tile and one half instead of two whole tiles.
+    constexpr bool HALFABLE = HF == 3 && WF == 3 && CB == 8;
+    bool half = false;
+    if (HALFABLE && !tail && grid == blocks && ncu >= 8 && ncu % 8 == 0 && blocks > (uint32_t)ncu) {
+        const uint32_t left = blocks % (uint32_t)ncu;
+        if (left > 0 && 2 * left <= (uint32_t)ncu) {
+            Q.nmain = blocks - left;
+            grid = Q.nmain + 2 * left;
+            half = true;
+        }
+    }
     void (*kern)(MfmaParams) = &conv_mfma_fast_kernel<HF, WF, CB, JX, CW, OCC, IMP, false, false>;
     if (grid < blocks) kern = &conv_mfma_fast_kernel<HF, WF, CB, JX, CW, OCC, IMP, true, false>;
     if (tail) kern = &conv_mfma_fast_kernel<HF, WF, CB, JX, CW, OCC, IMP, false, TAILABLE>;
+    if (half) kern = &conv_mfma_fast_kernel<HF, WF, CB, JX, CW, OCC, IMP, false, false, HALFABLE>;
     if (lds > 48 * 1024) {
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);

@@ -152,7 +152,7 @@ def test_many_tiles_per_workgroup(shape):
     assert torch.equal(dO.view(torch.int32), dO2.view(torch.int32))
 
 
-# Layers whose tile count leaves a few tiles (at most a quarter of the compute units) after the
+# Layers whose tile count leaves a few tiles (at most an eighth of the compute units) after the
 # last full round of the grid: the pipelined 3x3 kernel computes those in sixteen 16x16 pieces,
 # the four waves of a workgroup splitting the channels (a multiple of 16).  Tile counts are for
 # 256 compute units.
@@ -160,7 +160,7 @@ LEFTOVER_TILE_SHAPES = [
     (1, 16, 130, 130, 64, 3, 3, 1, 1),   # 265 tiles: 9 left; one channel group per wave; last tile has 4 pixels
     (1, 48, 96, 96, 88, 3, 3, 1, 0),     # 278 tiles: 22 left; 3 groups per wave; second M tile: 24 of 64 rows
     (11, 128, 78, 78, 40, 3, 3, 2, 1),   # 262 tiles: 6 left; 8 groups per wave (one refill); stride 2; tiles cross rows and images
-    (6, 32, 56, 56, 64, 3, 3, 1, 1),     # 294 tiles: 38 left
+    (7, 32, 50, 50, 64, 3, 3, 1, 1),     # 274 tiles: 18 left
 ]
 
 
@@ -170,6 +170,32 @@ def test_leftover_tiles_in_pieces(shape):
     I, F = workloads.random_layer_inputs(7900 + sum(shape), N, Ci, Hi, Wi, Co, Hf, Wf)
     print("leftover tiles", shape, flush=True)
     check_layer(I, F, s, p, basic=False, twice=False)
+    dW = run_transform(I, Hf, Wf, s, p)
+    dO = run_conv(dW, F, N, Ci, Hi, Wi, s, p)
+    dO2 = torch.full_like(dO, float("nan"))
+    im2win.conv2d_im2win_implicit_fwd(I.cuda(), F.cuda(), dO2, N, Ci, Hi, Wi, Co, Hf, Wf, s, p)
+    torch.cuda.synchronize()
+    assert torch.equal(dO.view(torch.int32), dO2.view(torch.int32))
+
+
+# Leftovers of up to half of the compute units that do not qualify for the sixteenths (more than
+# an eighth of the compute units, or channels not a multiple of 16): two half tiles of 32 pixels
+# each, two waves per block of outputs splitting the channel pairs of every K block.
+HALF_TILE_SHAPES = [
+    (1, 8, 130, 130, 64, 3, 3, 1, 1),    # 265 tiles: 9 left; one K block; the last tile's second half is empty
+    (1, 24, 96, 96, 88, 3, 3, 1, 0),     # 278 tiles: 22 left; three K blocks; second M tile: 24 of 64 rows
+    (11, 40, 78, 78, 40, 3, 3, 2, 1),    # 262 tiles: 6 left; five K blocks; stride 2; tiles cross rows and images
+    (7, 64, 56, 56, 64, 3, 3, 1, 1),     # 343 tiles: 87 left; eight K blocks
+    (9, 32, 50, 50, 128, 3, 3, 1, 0),    # 648 tiles (two M tiles each): 136 left -> no split (more than half the CUs)
+]
+
+
+@pytest.mark.parametrize("shape", HALF_TILE_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_leftover_tiles_in_halves(shape):
+    N, Ci, Hi, Wi, Co, Hf, Wf, s, p = shape
+    I, F = workloads.random_layer_inputs(7950 + sum(shape), N, Ci, Hi, Wi, Co, Hf, Wf)
+    print("half tiles", shape, flush=True)
+    check_layer(I, F, s, p, basic=False, twice=True)
     dW = run_transform(I, Hf, Wf, s, p)
     dO = run_conv(dW, F, N, Ci, Hi, Wi, s, p)
     dO2 = torch.full_like(dO, float("nan"))
