@@ -183,11 +183,13 @@ __device__ __forceinline__ void tail_piece(const MfmaParams &P, uint32_t lt, int
 // m*s + u - p, column k - p (zero outside the image).
 // PER: the grid may hold fewer workgroups than tiles; a workgroup then takes tiles blockIdx.x,
 // + gridDim.x, ... and keeps the pipeline running across tile boundaries.
-// TAIL: workgroups P.nmain and up take one sixteenth each of the tiles P.nmain .. P.nblocks-1.
-// HALF: workgroups P.nmain and up take one half (32 pixels) each of the tiles P.nmain ..
-// P.nblocks-1, two waves per 32x32 block of outputs, each multiplying half of the channels of
-// every K block (the two partial sums meet in LDS before the store).  For leftovers too many
-// for the sixteenths: a half tile is staged through LDS like a whole one, at 3/4 of its traffic.
+// Leftover tiles.  Workgroups 0 .. P.nmain-1 compute the tiles 0 .. P.nmain-1 whole; then come
+// two workgroups for each of the next P.nhalf tiles (HALF), then sixteen for each of the rest (TAIL).
+// HALF: a workgroup takes one half (32 pixels) of its tile, two waves per 32x32 block of
+// outputs, each multiplying half of the channels of every K block (the two partial sums meet in
+// LDS before the store).  For leftovers too many for the sixteenths: a half tile is staged
+// through LDS like a whole one, at 3/4 of its traffic.
+// TAIL: a workgroup takes one sixteenth of its tile (tail_piece above).
 template <int HF, int WF, int CB, int JX, int CW, int OCC, bool IMP, bool PER, bool TAIL, bool HALF = false>
 __global__ __launch_bounds__(256, OCC) void conv_mfma_fast_kernel(MfmaParams P)
 {
@@ -215,21 +217,22 @@ __global__ __launch_bounds__(256, OCC) void conv_mfma_fast_kernel(MfmaParams P)
     const int h = lane >> 5, l32 = lane & 31;
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);   // the same, known to be wave-uniform
     const int wm_u = wave_u & 1, wn_u = wave_u >> 1;
-    static_assert(!HALF || (!PER && !TAIL && (CB / 2) % 2 == 0 && ((CB / 4) * HF * WF) % pick_ring((CB / 2) * HF * WF) == 0),
+    static_assert(!HALF || (!PER && (CB / 2) % 2 == 0 && ((CB / 4) * HF * WF) % pick_ring((CB / 2) * HF * WF) == 0),
                   "half tiles: the channel pairs of a K block split evenly between two waves");
     // half-tile workgroups: which tile, which half; waves 0/1 take the first half of the channel
     // pairs of every K block, waves 2/3 the second (hk = 1)
-    const bool hmode = HALF && blockIdx.x >= P.nmain;                       // workgroup-uniform
+    const bool hmode = HALF && blockIdx.x >= P.nmain && blockIdx.x < P.nmain + 2u * P.nhalf;   // workgroup-uniform
     const uint32_t vb_first = hmode ? P.nmain + ((blockIdx.x - P.nmain) >> 1) : blockIdx.x;
     const int hpix = hmode ? (int)((blockIdx.x - P.nmain) & 1u) * 32 : 0;   // first pixel of the half, within the tile
     const int wn_g = hmode ? 0 : wn;             // pixel block of the wave within the (half) tile
     const int hk = hmode ? (wave >> 1) : 0, hk_u = hmode ? (wave_u >> 1) : 0;
 
-    if constexpr (TAIL) if (blockIdx.x >= P.nmain) {
-        // Piece q of leftover tile t.  Workgroup b runs on XCD b % 8 and P.nmain is a multiple
-        // of 8: the sixteen pieces of a tile are dealt to the same XCD, whose L2 then serves
-        // their shared filter rows and windows (the last L % 8 tiles aside).
-        const uint32_t sub = blockIdx.x - P.nmain, L = P.nblocks - P.nmain, full = L & ~7u;
+    if constexpr (TAIL) if (blockIdx.x >= P.nmain + 2u * P.nhalf) {
+        // Piece q of leftover tile t.  Workgroup b runs on XCD b % 8 and the pieces start at a
+        // multiple of 8: the sixteen pieces of a tile are dealt to the same XCD, whose L2 then
+        // serves their shared filter rows and windows (the last L % 8 tiles aside).
+        const uint32_t first = P.nmain + P.nhalf;   // first tile computed in pieces
+        const uint32_t sub = blockIdx.x - (P.nmain + 2u * P.nhalf), L = P.nblocks - first, full = L & ~7u;
         uint32_t t, q;
         if (sub < 16u * full) {
             t = (sub & 7u) + ((sub >> 7) << 3);
@@ -239,7 +242,7 @@ __global__ __launch_bounds__(256, OCC) void conv_mfma_fast_kernel(MfmaParams P)
             q = s2 / Lr;
             t = full + (s2 - q * Lr);
         }
-        tail_piece<HF, WF, IMP>(P, P.nmain + t, (int)q, lds, lane, wave_u);
+        tail_piece<HF, WF, IMP>(P, first + t, (int)q, lds, lane, wave_u);
         return;
     }
 
@@ -676,38 +679,33 @@ static hipError_t launch_fast_t(const MfmaParams &P, uint32_t blocks, hipStream_
     }
     // Leftover tiles: the workgroups go out in rounds that end together, and a compute unit is
     // as fast with one workgroup as with OCC of them, so a layer takes as long as its busiest
-    // compute unit: ceil(tiles / ncu) tile times.  When the last blocks % ncu tiles are few (at
-    // most an eighth of the compute units: the pieces read their operands without sharing them
-    // through LDS, four times the traffic of a whole tile; measured against the halves below on
-    // 64- and 256-channel layers, they win up to about 32-44 leftover tiles of 256) they are cut
-    // into sixteenths.
-    constexpr bool TAILABLE = HF == 3 && WF == 3 && CB == 8;
-    bool tail = false;
-    if (TAILABLE && Q.Ci % 16 == 0 && grid == blocks && ncu >= 8 && ncu % 8 == 0 && blocks > (uint32_t)ncu) {
-        const uint32_t left = blocks % (uint32_t)ncu;
-        if (left > 0 && 8 * left <= (uint32_t)ncu) {
-            Q.nmain = blocks - left;
-            grid = Q.nmain + 16 * left;
-            tail = true;
-        }
+    // compute unit: ceil(tiles / ncu) tile times.  Workgroups dispatched late are spread evenly
+    // over the compute units, so the last blocks % ncu tiles are cut up to give every unit a
+    // share (3x3 instances):
+    //   - up to ncu/2 of them into two halves of 32 pixels each, staged through LDS like a
+    //     whole tile -- a compute unit then ends with one whole tile and one half instead of
+    //     two whole tiles;
+    //   - up to ncu/8 of them (the rest, when it is that small and Ci is a multiple of 16)
+    //     into sixteenths, which read their operands without sharing them through LDS: four
+    //     times the traffic of a whole tile, but one cold load latency long (measured against
+    //     the halves on 64- and 256-channel layers, they win up to 32-44 leftover tiles of 256).
+    constexpr bool SPLITTABLE = HF == 3 && WF == 3 && CB == 8;
+    uint32_t nhalf = 0, npiece = 0;
+    if (SPLITTABLE && grid == blocks && ncu >= 8 && ncu % 8 == 0 && blocks > (uint32_t)ncu) {
+        const uint32_t left = blocks % (uint32_t)ncu, eighth = (uint32_t)ncu / 8, halfcu = (uint32_t)ncu / 2;
+        const bool pieces_ok = Q.Ci % 16 == 0;
+        if (pieces_ok && left <= eighth) npiece = left;
+        else if (left <= halfcu) nhalf = left;
+        else if (pieces_ok && left - halfcu <= eighth) { nhalf = halfcu; npiece = left - halfcu; }
+        Q.nmain = blocks - nhalf - npiece;
+        grid = Q.nmain + 2 * nhalf + 16 * npiece;
     }
-    // More leftover tiles than that, up to half of the compute units: each is cut into two halves
-    // of 32 pixels, staged through LDS like a whole tile; a compute unit then ends with one whole
-    // tile and one half instead of two whole tiles.
-    constexpr bool HALFABLE = HF == 3 && WF == 3 && CB == 8;
-    bool half = false;
-    if (HALFABLE && !tail && grid == blocks && ncu >= 8 && ncu % 8 == 0 && blocks > (uint32_t)ncu) {
-        const uint32_t left = blocks % (uint32_t)ncu;
-        if (left > 0 && 2 * left <= (uint32_t)ncu) {
-            Q.nmain = blocks - left;
-            grid = Q.nmain + 2 * left;
-            half = true;
-        }
-    }
+    Q.nhalf = nhalf;
     void (*kern)(MfmaParams) = &conv_mfma_fast_kernel<HF, WF, CB, JX, CW, OCC, IMP, false, false>;
     if (grid < blocks) kern = &conv_mfma_fast_kernel<HF, WF, CB, JX, CW, OCC, IMP, true, false>;
-    if (tail) kern = &conv_mfma_fast_kernel<HF, WF, CB, JX, CW, OCC, IMP, false, TAILABLE>;
-    if (half) kern = &conv_mfma_fast_kernel<HF, WF, CB, JX, CW, OCC, IMP, false, false, HALFABLE>;
+    if (npiece && !nhalf) kern = &conv_mfma_fast_kernel<HF, WF, CB, JX, CW, OCC, IMP, false, SPLITTABLE>;
+    if (nhalf && !npiece) kern = &conv_mfma_fast_kernel<HF, WF, CB, JX, CW, OCC, IMP, false, false, SPLITTABLE>;
+    if (nhalf && npiece) kern = &conv_mfma_fast_kernel<HF, WF, CB, JX, CW, OCC, IMP, false, SPLITTABLE, SPLITTABLE>;
     if (lds > 48 * 1024) {
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);

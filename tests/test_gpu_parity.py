@@ -186,7 +186,10 @@ HALF_TILE_SHAPES = [
     (1, 24, 96, 96, 88, 3, 3, 1, 0),     # 278 tiles: 22 left; three K blocks; second M tile: 24 of 64 rows
     (11, 40, 78, 78, 40, 3, 3, 2, 1),    # 262 tiles: 6 left; five K blocks; stride 2; tiles cross rows and images
     (7, 64, 56, 56, 64, 3, 3, 1, 1),     # 343 tiles: 87 left; eight K blocks
-    (9, 32, 50, 50, 128, 3, 3, 1, 0),    # 648 tiles (two M tiles each): 136 left -> no split (more than half the CUs)
+    (9, 32, 50, 50, 128, 3, 3, 1, 0),    # 648 tiles (two M tiles each): 136 left -> 128 in halves, 8 in sixteenths
+    (8, 32, 42, 42, 128, 3, 3, 1, 0),    # 400 tiles: 144 left -> 128 in halves, 16 in sixteenths
+    (8, 24, 42, 42, 128, 3, 3, 1, 0),    # the same with 24 channels: no sixteenths, the 144 stay whole
+    (9, 32, 53, 53, 128, 3, 3, 1, 0),    # 732 tiles: 220 left: too many, all whole
 ]
 
 
