@@ -691,7 +691,7 @@ static hipError_t launch_fast_t(const MfmaParams &P, uint32_t blocks, hipStream_
     //     the halves on 64- and 256-channel layers, they win up to 32-44 leftover tiles of 256).
     constexpr bool SPLITTABLE = HF == 3 && WF == 3 && CB == 8;
     uint32_t nhalf = 0, npiece = 0;
-    if (SPLITTABLE && grid == blocks && ncu >= 8 && ncu % 8 == 0 && blocks > (uint32_t)ncu) {
+    if (SPLITTABLE && grid == blocks && ncu >= 8 && ncu % 8 == 0) {   // (a layer with fewer tiles than compute units is all leftover)
         const uint32_t left = blocks % (uint32_t)ncu, eighth = (uint32_t)ncu / 8, halfcu = (uint32_t)ncu / 2;
         const bool pieces_ok = Q.Ci % 16 == 0;
         if (pieces_ok && left <= eighth) npiece = left;
