@@ -35,11 +35,11 @@ PEAK_HBM_GBS = 8000.0             # MI355X HBM3E
 # profiles/conv_mfma_fast_and_transform_cfg2_3x3_c64_56.md (headline layer) and
 # profiles/all_layers_default_bench.md.  Layers that were not measured report null.
 MEASURED_CONV_TRAFFIC_BYTES = {
-    "cfg1_tiny_3x3": 205824, "cfg2_3x3_c64_56": 107734584, "cfg3_3x3_c256_14": 215324643,
-    "cfg4_7x7_s2_c3_224": 688852854, "cfg5_11x11_s4_c3_227": 412391247}
+    "cfg1_tiny_3x3": 205824, "cfg2_3x3_c64_56": 107761653, "cfg3_3x3_c256_14": 206840729,
+    "cfg4_7x7_s2_c3_224": 688850223, "cfg5_11x11_s4_c3_227": 412440742}
 MEASURED_TRANSFORM_TRAFFIC_BYTES = {
-    "cfg1_tiny_3x3": 85500, "cfg2_3x3_c64_56": 106936511, "cfg3_3x3_c256_14": 114459367,
-    "cfg4_7x7_s2_c3_224": 369846399, "cfg5_11x11_s4_c3_227": 309400488}
+    "cfg1_tiny_3x3": 85500, "cfg2_3x3_c64_56": 106936518, "cfg3_3x3_c256_14": 114459371,
+    "cfg4_7x7_s2_c3_224": 369831431, "cfg5_11x11_s4_c3_227": 309585768}
 
 
 def parse_args():
