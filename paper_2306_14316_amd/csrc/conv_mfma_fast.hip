@@ -35,6 +35,14 @@ constexpr int pick_ring(int nm)
         if (nm % r == 0) return r;
     return 0;
 }
+// ... and, where half tiles run half of a block's MFMAs per wave, half of that count too.
+constexpr int pick_ring_half(int nm)
+{
+    const int cand[] = {9, 10, 8, 7, 11, 12, 6, 5};
+    for (int r : cand)
+        if (nm % 2 == 0 && nm % r == 0 && (nm / 2) % r == 0) return r;
+    return 0;
+}
 
 // ---- leftover tiles: sixteen 16x16 pieces per tile ------------------------------------------
 // A workgroup alone on a compute unit already keeps all four matrix pipes busy, so when fewer
@@ -202,7 +210,7 @@ __global__ __launch_bounds__(256, OCC) void conv_mfma_fast_kernel(MfmaParams P)
     constexpr int SS = 256 * JX;            // LDS floats per channel strip (compile-time stride)
     constexpr int SF_FLOATS = (MB * PF + 3) & ~3;
     constexpr int STAGE = SF_FLOATS + CB * SS;   // floats per LDS stage
-    constexpr int R = pick_ring((CB / 2) * KHW);
+    constexpr int R = HALF ? pick_ring_half((CB / 2) * KHW) : pick_ring((CB / 2) * KHW);
     static_assert(R > 0, "no ring length divides the MFMAs per block");
     static_assert(CW == 4 || CW == 2, "chunks are 16 or 8 bytes");
     static_assert(KB % CW == 0, "K block must be a whole number of chunks");
@@ -217,7 +225,7 @@ __global__ __launch_bounds__(256, OCC) void conv_mfma_fast_kernel(MfmaParams P)
     const int h = lane >> 5, l32 = lane & 31;
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);   // the same, known to be wave-uniform
     const int wm_u = wave_u & 1, wn_u = wave_u >> 1;
-    static_assert(!HALF || (!PER && (CB / 2) % 2 == 0 && ((CB / 4) * HF * WF) % pick_ring((CB / 2) * HF * WF) == 0),
+    static_assert(!HALF || (!PER && (CB / 2) % 2 == 0),
                   "half tiles: the channel pairs of a K block split evenly between two waves");
     // half-tile workgroups: which tile, which half; waves 0/1 take the first half of the channel
     // pairs of every K block, waves 2/3 the second (hk = 1)
@@ -681,7 +689,7 @@ static hipError_t launch_fast_t(const MfmaParams &P, uint32_t blocks, hipStream_
     // as fast with one workgroup as with OCC of them, so a layer takes as long as its busiest
     // compute unit: ceil(tiles / ncu) tile times.  Workgroups dispatched late are spread evenly
     // over the compute units, so the last blocks % ncu tiles are cut up to give every unit a
-    // share (3x3 instances):
+    // share (3x3 instances; the 5x5 instance knows the halves only):
     //   - up to ncu/2 of them into two halves of 32 pixels each, staged through LDS like a
     //     whole tile -- a compute unit then ends with one whole tile and one half instead of
     //     two whole tiles;
@@ -689,11 +697,12 @@ static hipError_t launch_fast_t(const MfmaParams &P, uint32_t blocks, hipStream_
     //     into sixteenths, which read their operands without sharing them through LDS: four
     //     times the traffic of a whole tile, but one cold load latency long (measured against
     //     the halves on 64- and 256-channel layers, they win up to 32-44 leftover tiles of 256).
-    constexpr bool SPLITTABLE = HF == 3 && WF == 3 && CB == 8;
+    constexpr bool PIECEABLE = HF == 3 && WF == 3 && CB == 8;
+    constexpr bool HALFABLE = PIECEABLE || (HF == 5 && WF == 5 && CB == 4);   // (the 5x5 instance: halves only)
     uint32_t nhalf = 0, npiece = 0;
-    if (SPLITTABLE && grid == blocks && ncu >= 8 && ncu % 8 == 0) {   // (a layer with fewer tiles than compute units is all leftover)
+    if (HALFABLE && grid == blocks && ncu >= 8 && ncu % 8 == 0) {   // (a layer with fewer tiles than compute units is all leftover)
         const uint32_t left = blocks % (uint32_t)ncu, eighth = (uint32_t)ncu / 8, halfcu = (uint32_t)ncu / 2;
-        const bool pieces_ok = Q.Ci % 16 == 0;
+        const bool pieces_ok = PIECEABLE && Q.Ci % 16 == 0;
         if (pieces_ok && left <= eighth) npiece = left;
         else if (left <= halfcu) nhalf = left;
         else if (pieces_ok && left - halfcu <= eighth) { nhalf = halfcu; npiece = left - halfcu; }
@@ -703,9 +712,9 @@ static hipError_t launch_fast_t(const MfmaParams &P, uint32_t blocks, hipStream_
     Q.nhalf = nhalf;
     void (*kern)(MfmaParams) = &conv_mfma_fast_kernel<HF, WF, CB, JX, CW, OCC, IMP, false, false>;
     if (grid < blocks) kern = &conv_mfma_fast_kernel<HF, WF, CB, JX, CW, OCC, IMP, true, false>;
-    if (npiece && !nhalf) kern = &conv_mfma_fast_kernel<HF, WF, CB, JX, CW, OCC, IMP, false, SPLITTABLE>;
-    if (nhalf && !npiece) kern = &conv_mfma_fast_kernel<HF, WF, CB, JX, CW, OCC, IMP, false, false, SPLITTABLE>;
-    if (nhalf && npiece) kern = &conv_mfma_fast_kernel<HF, WF, CB, JX, CW, OCC, IMP, false, SPLITTABLE, SPLITTABLE>;
+    if (npiece && !nhalf) kern = &conv_mfma_fast_kernel<HF, WF, CB, JX, CW, OCC, IMP, false, PIECEABLE>;
+    if (nhalf && !npiece) kern = &conv_mfma_fast_kernel<HF, WF, CB, JX, CW, OCC, IMP, false, false, HALFABLE>;
+    if (nhalf && npiece) kern = &conv_mfma_fast_kernel<HF, WF, CB, JX, CW, OCC, IMP, false, PIECEABLE, HALFABLE>;
     if (lds > 48 * 1024) {
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);

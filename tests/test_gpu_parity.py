@@ -190,6 +190,8 @@ HALF_TILE_SHAPES = [
     (8, 32, 42, 42, 128, 3, 3, 1, 0),    # 400 tiles: 144 left -> 128 in halves, 16 in sixteenths
     (8, 24, 42, 42, 128, 3, 3, 1, 0),    # the same with 24 channels: no sixteenths, the 144 stay whole
     (9, 32, 53, 53, 128, 3, 3, 1, 0),    # 732 tiles: 220 left: too many, all whole
+    (5, 8, 68, 68, 64, 5, 5, 1, 0),      # the 5x5 instance: 320 tiles, 64 left, two K blocks
+    (3, 12, 60, 60, 70, 5, 5, 1, 2),     # 5x5: 338 tiles, 82 left, three K blocks, second M tile: 6 of 64 rows
 ]
 
 
