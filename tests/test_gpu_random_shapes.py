@@ -84,3 +84,45 @@ def test_random_shape_all_routes(shape):
     torch.cuda.synchronize()
     assert_conv_close(dO3.cpu().numpy(), O_ref, B_ref)
     assert_conv_close(dO4.cpu().numpy(), O_ref, B_ref)
+
+
+def _leftover_shapes(seed, count):
+    """3x3 and 5x5 multi-channel layers with 150 to 700 tiles: every way the pipelined kernel
+    cuts the tiles left after the last full round of 256 (sixteenths, halves, both, none)."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        Hf = Wf = int(rng.choice([3, 3, 3, 5]))
+        Ci = int(rng.choice([8, 16, 24, 32, 48, 64])) if Hf == 3 else int(rng.choice([4, 8, 12, 16]))
+        s = int(rng.choice([1, 1, 2]))
+        p = int(rng.integers(0, 3))
+        Hi, Wi = int(rng.integers(20, 90)), int(rng.integers(20, 90))
+        Co = int(rng.choice([24, 64, 64, 100, 128]))
+        Ho, Wo = (Hi + 2 * p - Hf) // s + 1, (Wi + 2 * p - Wf) // s + 1
+        if Ho < 1 or Wo < 1:
+            continue
+        want = int(rng.integers(150, 700))                      # tiles
+        N = max(1, round(want * 64 / ((Co + 63) // 64) / (Ho * Wo)))
+        tiles = ((N * Ho * Wo + 63) // 64) * ((Co + 63) // 64)
+        if not 150 <= tiles <= 700 or N * Co * Ho * Wo * Ci * Hf * Wf > 8e8:
+            continue
+        out.append((N, Ci, Hi, Wi, Co, Hf, Wf, s, p))
+    return out
+
+
+LEFTOVER_SHAPES = _leftover_shapes(20230615, 20)
+
+
+@pytest.mark.parametrize("shape", LEFTOVER_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_random_shape_leftover_tiles(shape):
+    N, Ci, Hi, Wi, Co, Hf, Wf, s, p = shape
+    I, F = workloads.random_layer_inputs(4100 + sum(shape), N, Ci, Hi, Wi, Co, Hf, Wf)
+    print("random leftover shape", shape, flush=True)
+    O_ref, B_ref = oracle.conv2d_direct(I.numpy(), F.numpy(), s, p)
+    dW = run_transform(I, Hf, Wf, s, p)
+    dO = run_conv(dW, F, N, Ci, Hi, Wi, s, p)
+    assert_conv_close(dO.cpu().numpy(), O_ref, B_ref)
+    dO2 = torch.full_like(dO, POISON)
+    im2win.conv2d_im2win_implicit_fwd(I.cuda(), F.cuda(), dO2, N, Ci, Hi, Wi, Co, Hf, Wf, s, p)
+    torch.cuda.synchronize()
+    assert torch.equal(dO.view(torch.int32), dO2.view(torch.int32))
