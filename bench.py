@@ -140,6 +140,7 @@ def time_layer(L, steps, warmup):
     return dict(implicit_ms_per_step=imp_ms, ms_per_step=(t1 - t0) * 1e3 / steps,
                 transform_ms_avg=sum(tr) / len(tr), transform_ms_best=min(tr),
                 conv_ms_avg=sum(cv) / len(cv), conv_ms_best=min(cv),
+                conv_ms_median=sorted(cv)[len(cv) // 2], transform_ms_median=sorted(tr)[len(tr) // 2],
                 workspace_bytes=ws, im2col_bytes=col,
                 transform_alg_bytes=4 * N * Ci * Hi * Wi + ws,
                 conv_alg_bytes=ws + 4 * Co * Ci * Hf * Wf + 4 * N * Co * L.Ho * L.Wo)
@@ -172,7 +173,9 @@ def layer_report(L, t):
         "transform_gbs_avg": t["transform_alg_bytes"] / (t["transform_ms_avg"] * 1e-3) / 1e9,
         "transform_frac_of_hbm_peak": t["transform_alg_bytes"] / (t["transform_ms_avg"] * 1e-3) / 1e9 / PEAK_HBM_GBS,
         "ms_per_step": t["ms_per_step"], "conv_ms_avg": t["conv_ms_avg"], "conv_ms_best": t["conv_ms_best"],
+        "conv_ms_median": t["conv_ms_median"],
         "transform_ms_avg": t["transform_ms_avg"], "transform_ms_best": t["transform_ms_best"],
+        "transform_ms_median": t["transform_ms_median"],
         "workspace_bytes": t["workspace_bytes"], "im2col_bytes": t["im2col_bytes"],
         "workspace_free_ms_per_step": t["implicit_ms_per_step"],
         "workspace_free_step_tflops": (fl / (t["implicit_ms_per_step"] * 1e-3) / 1e12) if t["implicit_ms_per_step"] else None,
