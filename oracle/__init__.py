@@ -167,7 +167,7 @@ def conv2d_im2col_gemm(I, F, s: int, p: int) -> np.ndarray:
 
 
 def conv2d_over_im2win(What, F, Hi: int, Wi: int, s: int, p: int) -> np.ndarray:
-    """Three-loop (M,N,K) convolution reading the im2win tensor (Algorithms 1-2)."""
+    """Convolution as dot products over the contiguous windows of the im2win tensor (Section 3.1-3.2)."""
     What, F = _f32(What), _f32(F)
     Co, Ci, Hf, Wf = F.shape
     N = What.shape[0]

@@ -234,11 +234,16 @@ int oracle_conv2d_im2col_gemm(const float *I, const float *F,
 }
 
 /*
- * Convolution over the im2win tensor in the three-loop (M, N, K) form of
- * Algorithms 1 and 2: M = Co, N = Ni*Ho*Wo, K = Ci*Hf*Wf, indices decoded on
- * the fly, the input operand read from What.  Algorithm 2 writes the operand
- * with four input coordinates although What has shape (Ni, Ci, Ho, Wp*Hf);
- * the reading taken here is What(i_n, i_c, o_h, i_w*Hf + f_h), i_w = o_w*s+f_w.
+ * Convolution read off the im2win tensor (Section 3.1-3.2).  The property the
+ * method rests on: for output pixel (i, m, n) and channel r, the Hf x Wf patch
+ * of the padded input is ONE contiguous run of What, Hf*Wf floats long, that
+ * starts at column n*s*Hf of row What[i][r][m][.] and holds the patch column
+ * after column (element v*Hf + u is patch row u, patch column v).  Each output
+ * is therefore the sum, over the channels, of the dot product of that run with
+ * the channel's filter taps taken in the same column-major order.  Plain nested
+ * loops over the output and over (r, v, u); no flattened-index decoding.  A
+ * differently structured third route to Eq. 1's numbers: it pins the element
+ * order inside a row of What and the way the convolution must index it.
  */
 int oracle_conv2d_over_im2win(const float *What, const float *F,
                               int N, int Ci, int Hi, int Wi, int Co, int Hf, int Wf,
@@ -247,26 +252,21 @@ int oracle_conv2d_over_im2win(const float *What, const float *F,
     int Ho = oracle_out_dim(Hi, Hf, s, p);
     int Wo = oracle_out_dim(Wi, Wf, s, p);
     if (Ho < 0 || Wo < 0 || N <= 0 || Ci <= 0 || Co <= 0) return -1;
-    int Wp = Wi + 2 * p;
-    int64_t Md = Co, Nd = (int64_t)N * Ho * Wo, Kd = (int64_t)Ci * Hf * Wf;
-    for (int64_t mm = 0; mm < Md; ++mm) {
-        int o_c = (int)mm;
-        for (int64_t nn = 0; nn < Nd; ++nn) {
-            int o_n = (int)(nn / ((int64_t)Ho * Wo));
-            int o_h = (int)((nn % ((int64_t)Ho * Wo)) / Wo);
-            int o_w = (int)((nn % ((int64_t)Ho * Wo)) % Wo);
-            double acc = 0.0;
-            for (int64_t k = 0; k < Kd; ++k) {
-                int f_c = (int)(k / (Hf * Wf));
-                int kres = (int)(k % (Hf * Wf));
-                int f_h = kres / Wf, f_w = kres % Wf;
-                int i_w = o_w * s + f_w;
-                double x = (double)What[((((size_t)o_n * Ci + f_c) * Ho + o_h) * Wp + i_w) * Hf + f_h];
-                double w = (double)F[(((size_t)o_c * Ci + f_c) * Hf + f_h) * Wf + f_w];
-                acc += x * w;
-            }
-            O[(((size_t)o_n * Co + o_c) * Ho + o_h) * Wo + o_w] = acc;
-        }
-    }
+    size_t rowlen = (size_t)(Wi + 2 * p) * Hf;   /* floats in one row of What */
+    for (int i = 0; i < N; ++i)
+        for (int j = 0; j < Co; ++j)
+            for (int m = 0; m < Ho; ++m)
+                for (int n = 0; n < Wo; ++n) {
+                    double acc = 0.0;
+                    for (int r = 0; r < Ci; ++r) {
+                        const float *row = What + (((size_t)i * Ci + r) * Ho + m) * rowlen;
+                        const float *window = row + (size_t)n * s * Hf;   /* contiguous Hf*Wf floats */
+                        const float *taps = F + ((size_t)j * Ci + r) * Hf * Wf;
+                        for (int v = 0; v < Wf; ++v)
+                            for (int u = 0; u < Hf; ++u)
+                                acc += (double)window[v * Hf + u] * (double)taps[u * Wf + v];
+                    }
+                    O[(((size_t)i * Co + j) * Ho + m) * Wo + n] = acc;
+                }
     return 0;
 }

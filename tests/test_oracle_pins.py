@@ -200,9 +200,9 @@ def test_im2col_matrix_rows_are_flattened_windows(shape):
 
 @pytest.mark.parametrize("shape", TINY_SHAPES)
 def test_convolution_over_im2win_agrees(shape):
-    """The three-loop form over the im2win tensor reaches the definition's
-    result: fixes the element order inside a row of the tensor and the reading
-    of Algorithm 2's operand index together."""
+    """Dot products over the contiguous windows of the im2win tensor reach the
+    definition's result: fixes the element order inside a row of the tensor
+    (column after column) and the window start n*s*Hf together."""
     N, Ci, Hi, Wi, Co, Hf, Wf, s, p = shape
     I, F = rand_pair(N, Ci, Hi, Wi, Co, Hf, Wf)
     O, _ = oracle.conv2d_direct(I, F, s, p)
