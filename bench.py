@@ -64,8 +64,26 @@ def parse_args():
     return ap.parse_args()
 
 
+def layer_flops(L):
+    """The metric's flop count of a layer, 2*N*Co*Ho*Wo*Ci*Hf*Wf, with the output size the library derives."""
+    import paper_2306_14316_amd as im2win
+    Ho, Wo = im2win.im2win_out_shape(L.Hi, L.Wi, L.Hf, L.Wf, L.stride, L.pad)
+    return 2 * L.N * L.Co * Ho * Wo * L.Ci * L.Hf * L.Wf
+
+
+KERNEL_SAMPLES = 20   # launches per kernel timing batch, at least (whatever --steps says)
+
+
 def time_layer(L, steps, warmup):
-    """Run warmup + steps passes of transform+conv; returns timing dict (ms)."""
+    """Run warmup + steps passes of transform+conv; returns timing dict (ms).
+
+    Two separate measurements.  The step time is the wall clock around `steps` passes of the whole
+    path, synchronised on both sides, with no events in between.  The per-kernel durations come
+    right after, on the same stream and the same buffers: for each kernel, three batches of
+    max(steps, KERNEL_SAMPLES) back-to-back launches between one pair of HIP events (an event
+    pair around a single launch of a 20 us kernel reads several microseconds too long, and
+    markers between the two kernels of a step keep them from being dispatched back to back);
+    reported are the mean over all batches, the best and the median batch."""
     import torch
     import paper_2306_14316_amd as im2win
     from paper_2306_14316_amd import workloads
@@ -73,12 +91,18 @@ def time_layer(L, steps, warmup):
     N, Ci, Hi, Wi, Co, Hf, Wf, s, p = L.dims
     I, F = workloads.make_inputs(L)
     dI, dF = I.cuda(), F.cuda()
-    dW = torch.full((N, Ci, L.Ho, L.Wp * Hf), float("nan"), dtype=torch.float32, device="cuda")
-    dO = torch.full((N, Co, L.Ho, L.Wo), float("nan"), dtype=torch.float32, device="cuda")
+    ws = im2win.im2win_workspace_bytes(N, Ci, Hi, Wi, Hf, Wf, s, p)
+    col = im2win.im2col_footprint_bytes(N, Ci, Hi, Wi, Hf, Wf, s, p)
+    Ho, Wo = im2win.im2win_out_shape(Hi, Wi, Hf, Wf, s, p)
+    dW = torch.full((ws // 4,), float("nan"), dtype=torch.float32, device="cuda")
+    dO = torch.full((N, Co, Ho, Wo), float("nan"), dtype=torch.float32, device="cuda")
+
+    tr = lambda: im2win.im2win_transform(dI, dW, N, Ci, Hi, Wi, Hf, Wf, s, p)
+    cv = lambda: im2win.conv2d_im2win_fwd(dW, dF, dO, N, Ci, Hi, Wi, Co, Hf, Wf, s, p)
 
     def step():
-        im2win.im2win_transform(dI, dW, N, Ci, Hi, Wi, Hf, Wf, s, p)
-        im2win.conv2d_im2win_fwd(dW, dF, dO, N, Ci, Hi, Wi, Co, Hf, Wf, s, p)
+        tr()
+        cv()
 
     # Set-up, not part of the W warm-up steps: the first pass checks that every
     # output word is written, and a short burst brings the GPU clocks up (a cold
@@ -96,32 +120,17 @@ def time_layer(L, steps, warmup):
     for _ in range(warmup):
         step()
     torch.cuda.synchronize()
-
-    # Kernel-level HIP events are recorded on every EVERY-th step of the timed
-    # region: an evented step takes about 17 us longer (the markers keep the two
-    # kernels from being dispatched back to back), so on all steps they would
-    # distort the step time they are there to explain.
-    EVERY = 10
-    ev = {k: [torch.cuda.Event(enable_timing=True) for _ in range(3)] for k in range(0, steps, EVERY)}
-    torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for k in range(steps):
-        if k in ev:
-            ev[k][0].record()
-            im2win.im2win_transform(dI, dW, N, Ci, Hi, Wi, Hf, Wf, s, p)
-            ev[k][1].record()
-            im2win.conv2d_im2win_fwd(dW, dF, dO, N, Ci, Hi, Wi, Co, Hf, Wf, s, p)
-            ev[k][2].record()
-        else:
-            step()
+    for _ in range(steps):
+        step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    tr = [e[0].elapsed_time(e[1]) for e in ev.values()]
-    cv = [e[1].elapsed_time(e[2]) for e in ev.values()]
-    ws = im2win.im2win_workspace_bytes(N, Ci, Hi, Wi, Hf, Wf, s, p)
-    col = im2win.im2col_footprint_bytes(N, Ci, Hi, Wi, Hf, Wf, s, p)
-    # The workspace-free variant (strips built in LDS from the input), where the layer has one:
-    # one call replaces the whole step.  Timed the same way, after the main measurement.
+
+    nk = max(steps, KERNEL_SAMPLES)
+    tr_b = [_event_ms(tr, nk) for _ in range(3)]
+    cv_b = [_event_ms(cv, nk) for _ in range(3)]
+    # The workspace-free variant (strips built in LDS from the input): one call replaces the whole
+    # step.  Timed the same way as the step, after the main measurement.
     imp_ms = None
     try:
         imp = lambda: im2win.conv2d_im2win_implicit_fwd(dI, dF, dO, N, Ci, Hi, Wi, Co, Hf, Wf, s, p)
@@ -138,45 +147,44 @@ def time_layer(L, steps, warmup):
     except im2win.Im2winError:
         pass
     return dict(implicit_ms_per_step=imp_ms, ms_per_step=(t1 - t0) * 1e3 / steps,
-                transform_ms_avg=sum(tr) / len(tr), transform_ms_best=min(tr),
-                conv_ms_avg=sum(cv) / len(cv), conv_ms_best=min(cv),
-                conv_ms_median=sorted(cv)[len(cv) // 2], transform_ms_median=sorted(tr)[len(tr) // 2],
+                kernel_samples=3 * nk,
+                transform_ms_avg=sum(tr_b) / 3, transform_ms_best=min(tr_b), transform_ms_median=sorted(tr_b)[1],
+                conv_ms_avg=sum(cv_b) / 3, conv_ms_best=min(cv_b), conv_ms_median=sorted(cv_b)[1],
                 workspace_bytes=ws, im2col_bytes=col,
                 transform_alg_bytes=4 * N * Ci * Hi * Wi + ws,
-                conv_alg_bytes=ws + 4 * Co * Ci * Hf * Wf + 4 * N * Co * L.Ho * L.Wo)
+                conv_alg_bytes=ws + 4 * Co * Ci * Hf * Wf + 4 * N * Co * Ho * Wo,
+                flops=2 * N * Co * Ho * Wo * Ci * Hf * Wf, Ho=Ho, Wo=Wo)
 
 
 def kernel_names(L):
-    """(convolution kernel, transform kernel) the library picks for a layer with aligned buffers."""
-    if L.Ci == 3 and (L.Hf, L.Wf) in ((3, 3), (7, 7), (11, 11)) and L.Wp * L.Hf >= 256:
-        conv = "conv_mfma_shallow_kernel"
-    elif (L.Hf, L.Wf) == (3, 3) and L.Ci % 8 == 0 or (L.Hf, L.Wf) == (5, 5) and L.Ci % 4 == 0 \
-            or (L.Hf, L.Wf) == (7, 7) and L.Ci % 2 == 0:
-        conv = "conv_mfma_fast_kernel"
-    else:
-        conv = "conv_mfma_kernel"
-    moved = 4 * L.N * L.Ci * (L.Hi * L.Wi + L.Ho * L.Wp * L.Hf)
-    staged = (L.Hf >= 5 and L.Wp >= 64) or (L.Hf >= 3 and L.Wp >= 48 and moved >= 192 * 2 ** 20)
-    return conv, ("transform_lds_kernel" if staged else "transform_kernel")
+    """(convolution kernel, transform kernel) of a layer, as the library's own dispatch names them."""
+    import paper_2306_14316_amd as im2win
+    N, Ci, Hi, Wi, Co, Hf, Wf, s, p = L.dims
+    return (im2win.conv2d_im2win_fwd_launch_info(N, Ci, Hi, Wi, Co, Hf, Wf, s, p),
+            im2win.im2win_transform_launch_info(N, Ci, Hi, Wi, Hf, Wf, s, p))
 
 
 def layer_report(L, t):
-    fl = L.flops
+    fl = t["flops"]
+    conv_k, tr_k = kernel_names(L)
     return {
         "workload": L.name,
         "shape": {"N": L.N, "Ci": L.Ci, "Hi": L.Hi, "Wi": L.Wi, "Co": L.Co, "Hf": L.Hf, "Wf": L.Wf,
                   "stride": L.stride, "pad": L.pad},
+        "conv_kernel": conv_k["kernel"], "transform_kernel": tr_k["kernel"],
         "step_tflops": fl / (t["ms_per_step"] * 1e-3) / 1e12,
         "conv_tflops_avg": fl / (t["conv_ms_avg"] * 1e-3) / 1e12,
         "conv_tflops_best": fl / (t["conv_ms_best"] * 1e-3) / 1e12,
         "conv_frac_of_fp32_matrix_peak": fl / (t["conv_ms_avg"] * 1e-3) / 1e12 / PEAK_FP32_MATRIX_TFLOPS,
         "transform_gbs_avg": t["transform_alg_bytes"] / (t["transform_ms_avg"] * 1e-3) / 1e9,
         "transform_frac_of_hbm_peak": t["transform_alg_bytes"] / (t["transform_ms_avg"] * 1e-3) / 1e9 / PEAK_HBM_GBS,
-        "ms_per_step": t["ms_per_step"], "conv_ms_avg": t["conv_ms_avg"], "conv_ms_best": t["conv_ms_best"],
-        "conv_ms_median": t["conv_ms_median"],
+        "ms_per_step": t["ms_per_step"], "kernel_samples": t["kernel_samples"],
+        "conv_ms_avg": t["conv_ms_avg"], "conv_ms_best": t["conv_ms_best"], "conv_ms_median": t["conv_ms_median"],
         "transform_ms_avg": t["transform_ms_avg"], "transform_ms_best": t["transform_ms_best"],
         "transform_ms_median": t["transform_ms_median"],
         "workspace_bytes": t["workspace_bytes"], "im2col_bytes": t["im2col_bytes"],
+        "conv_traffic_bytes": MEASURED_CONV_TRAFFIC_BYTES.get(L.name),
+        "transform_traffic_bytes": MEASURED_TRANSFORM_TRAFFIC_BYTES.get(L.name),
         "workspace_free_ms_per_step": t["implicit_ms_per_step"],
         "workspace_free_step_tflops": (fl / (t["implicit_ms_per_step"] * 1e-3) / 1e12) if t["implicit_ms_per_step"] else None,
     }
@@ -190,8 +198,9 @@ def time_variants(L, steps):
     N, Ci, Hi, Wi, Co, Hf, Wf, s, p = L.dims
     I, F = workloads.make_inputs(L)
     dI, dF = I.cuda(), F.cuda()
-    dW = torch.empty((N, Ci, L.Ho, L.Wp * Hf), dtype=torch.float32, device="cuda")
-    dO = torch.empty((N, Co, L.Ho, L.Wo), dtype=torch.float32, device="cuda")
+    sz = im2win.layer_sizes(*L.dims)
+    dW = torch.empty(sz["window_elems"], dtype=torch.float32, device="cuda")
+    dO = torch.empty(sz["output_elems"], dtype=torch.float32, device="cuda")
     im2win.im2win_transform(dI, dW, N, Ci, Hi, Wi, Hf, Wf, s, p)
     names = {0: "default", 3: "narrow_loads (8-byte instead of 16-byte filter fetches)",
              1: "no_pipeline (one LDS stage, no prefetch)", 2: "no_mfma (one thread per output)"}
@@ -213,7 +222,7 @@ def time_variants(L, steps):
         e1.record()
         torch.cuda.synchronize()
         ms = e0.elapsed_time(e1) / k
-        out[name] = {"conv_ms": ms, "conv_tflops": L.flops / (ms * 1e-3) / 1e12}
+        out[name] = {"conv_ms": ms, "conv_tflops": layer_flops(L) / (ms * 1e-3) / 1e12}
     return {"workload": L.name, "variants": out}
 
 
@@ -239,9 +248,7 @@ def _event_ms(fn, k):
 
 
 def device_copy_gbs():
-    """Bandwidth of a plain 256 MiB device-to-device copy (bytes read + bytes written per second):
-    what a streaming kernel with one read and one write stream reaches on this machine, the second
-    yardstick for the transform beside the 8 TB/s of the data sheet."""
+    """Bandwidth of a plain 256 MiB device-to-device copy of the runtime (bytes read + bytes written per second)."""
     import torch
     src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")
     dst = torch.empty_like(src)
@@ -249,6 +256,46 @@ def device_copy_gbs():
     ms = min(_event_ms(lambda: dst.copy_(src), 10) for _ in range(3))
     del src, dst
     return 2.0 * 256 * 1024 * 1024 / (ms * 1e-3) / 1e9
+
+
+def measured_stream_gbs(nbytes=256 * 1024 * 1024):
+    """What this device's HBM delivers to the library's own streaming probe kernels (16-byte accesses,
+    eight in flight per thread) over `nbytes`: read only, write only and copy, with ordinary and with
+    non-temporal accesses.  GB/s of bytes moved (a copy moves 2 x nbytes); best of three batches of ten."""
+    import torch
+    import paper_2306_14316_amd as im2win
+    src = torch.ones(nbytes // 4, dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(src)
+    out = {}
+    for name, mode, moved in (("read", im2win.PROBE_READ, nbytes), ("write", im2win.PROBE_WRITE, nbytes),
+                              ("copy", im2win.PROBE_COPY, 2 * nbytes)):
+        for nt in (0, im2win.PROBE_NONTEMPORAL):
+            fn = lambda: im2win.im2win_probe_stream(mode | nt, src, dst, nbytes)
+            _ramp(fn, 0.02)
+            ms = min(_event_ms(fn, 10) for _ in range(3))
+            out[name + ("_nontemporal" if nt else "")] = moved / (ms * 1e-3) / 1e9
+    del src, dst
+    return out
+
+
+def measured_mfma_peak_tflops():
+    """fp32 matrix rate of a register-resident v_mfma_f32_32x32x2_f32 loop on this device (the
+    library's probe kernel: no operand traffic at all), best of three launches of about 2 ms."""
+    import torch
+    import paper_2306_14316_amd as im2win
+    sink = torch.zeros(64, dtype=torch.float32, device="cuda")
+    per_wave = 40000
+    _ramp(lambda: im2win.im2win_probe_mfma_f32(sink, per_wave), 0.05)
+    best = 0.0
+    for _ in range(3):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        fl = im2win.im2win_probe_mfma_f32(sink, per_wave)
+        e1.record()
+        torch.cuda.synchronize()
+        best = max(best, fl / (e0.elapsed_time(e1) * 1e-3) / 1e12)
+    return best
 
 
 def time_baselines(L, steps):
@@ -260,13 +307,14 @@ def time_baselines(L, steps):
     N, Ci, Hi, Wi, Co, Hf, Wf, s, p = L.dims
     I, F = workloads.make_inputs(L)
     dI, dF = I.cuda(), F.cuda()
-    dO = torch.empty((N, Co, L.Ho, L.Wo), dtype=torch.float32, device="cuda")
-    dW = torch.empty((N, Ci, L.Ho, L.Wp * Hf), dtype=torch.float32, device="cuda")
+    sz = im2win.layer_sizes(*L.dims)
+    dO = torch.empty(sz["output_elems"], dtype=torch.float32, device="cuda")
+    dW = torch.empty(sz["window_elems"], dtype=torch.float32, device="cuda")
     colb = im2win.im2col_footprint_bytes(N, Ci, Hi, Wi, Hf, Wf, s, p)
     res = {"workload": L.name, "im2win_workspace_bytes": dW.numel() * 4, "im2col_workspace_bytes": colb}
 
     def tf(ms):
-        return L.flops / (ms * 1e-3) / 1e12
+        return layer_flops(L) / (ms * 1e-3) / 1e12
 
     f_t = lambda: im2win.im2win_transform(dI, dW, N, Ci, Hi, Wi, Hf, Wf, s, p)
     f_c = lambda: im2win.conv2d_im2win_fwd(dW, dF, dO, N, Ci, Hi, Wi, Co, Hf, Wf, s, p)
@@ -303,7 +351,7 @@ def cpu_baseline(L):
     oracle.im2win(In, L.Hf, L.Wf, L.stride, L.pad)
     oracle.conv2d_direct(In, Fn, L.stride, L.pad, with_bound=False)
     dt = time.perf_counter() - t0
-    return {"value": L.flops / dt / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+    return {"value": layer_flops(L) / dt / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
             "seconds": dt,
             "sample": "the whole %s workload (all %d images), one pass: im2win gather + seven-loop fp64 "
                       "direct convolution, OpenMP over (image, output channel)" % (L.name, L.N)}
@@ -346,8 +394,8 @@ def main():
         "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": L.name, **rep["shape"], "Ho": L.Ho, "Wo": L.Wo,
-                   "gemm": {"M": L.Co, "N": L.N * L.Ho * L.Wo, "K": L.Ci * L.Hf * L.Wf}},
+        "config": {"workload": L.name, **rep["shape"], "Ho": t["Ho"], "Wo": t["Wo"],
+                   "gemm": {"M": L.Co, "N": L.N * t["Ho"] * t["Wo"], "K": L.Ci * L.Hf * L.Wf}},
         "workspace_bytes": t["workspace_bytes"], "im2col_bytes": t["im2col_bytes"],
         "conv_only_tflops": conv_tflops, "conv_only_tflops_best_of_steps": rep["conv_tflops_best"],
         "transform_gbs": rep["transform_gbs_avg"],
@@ -356,21 +404,32 @@ def main():
                                    "note": "conv2d_im2win_implicit_fwd: one call, im2win strips built in LDS from the "
                                            "NCHW input, no workspace; not the headline (the step above is the paper's "
                                            "transform + convolution)"},
-        "roofline": {"kernel": kernel_names(L)[0], "bound": "mfma", "achieved": conv_tflops,
+        "roofline": {"kernel": rep["conv_kernel"], "launch": kernel_names(L)[0], "bound": "mfma",
+                     "achieved": conv_tflops,
                      "peak": PEAK_FP32_MATRIX_TFLOPS, "unit": "TFLOP/s",
                      "frac": conv_tflops / PEAK_FP32_MATRIX_TFLOPS, "traffic": traffic,
-                     "flops_per_launch": L.flops, "avg_launch_ms": t["conv_ms_avg"]},
-        "roofline_transform": {"kernel": kernel_names(L)[1], "bound": "hbm", "achieved": rep["transform_gbs_avg"],
+                     "flops_per_launch": t["flops"], "avg_launch_ms": t["conv_ms_avg"],
+                     "launches_timed": t["kernel_samples"], "algorithmic_bytes": t["conv_alg_bytes"]},
+        "roofline_transform": {"kernel": rep["transform_kernel"], "launch": kernel_names(L)[1], "bound": "hbm",
+                               "achieved": rep["transform_gbs_avg"],
                                "peak": PEAK_HBM_GBS, "unit": "GB/s",
                                "frac": rep["transform_gbs_avg"] / PEAK_HBM_GBS,
                                "traffic": MEASURED_TRANSFORM_TRAFFIC_BYTES.get(L.name),
-                               "bytes_per_launch": t["transform_alg_bytes"], "avg_launch_ms": t["transform_ms_avg"]},
+                               "bytes_per_launch": t["transform_alg_bytes"], "avg_launch_ms": t["transform_ms_avg"],
+                               "launches_timed": t["kernel_samples"]},
         "paper_context": "paper reports ratios only, on an RTX 3090 at fp32, batch 128: im2win 3.5x im2col+cuBLAS, "
                          "1.1x (up to 1.8x) the fastest cuDNN algorithm, 5-155x a naive direct kernel",
     }
+    # the two measured ceilings, from this device in this process
+    peak = measured_mfma_peak_tflops()
+    out["roofline"]["measured_mfma_peak_tflops"] = peak
+    out["roofline"]["frac_of_measured_peak"] = conv_tflops / peak
     copy_gbs = device_copy_gbs()
+    streams = measured_stream_gbs()
+    best_stream = max(max(streams["copy"], streams["copy_nontemporal"]), copy_gbs)
     out["roofline_transform"]["measured_copy_gbs"] = copy_gbs
-    out["roofline_transform"]["frac_of_measured_copy"] = rep["transform_gbs_avg"] / copy_gbs
+    out["roofline_transform"]["measured_stream_gbs"] = streams
+    out["roofline_transform"]["frac_of_measured_copy"] = rep["transform_gbs_avg"] / best_stream
     if a.layers == "all":
         reps = []
         for other in workloads.LAYERS:
@@ -379,6 +438,9 @@ def main():
             else:
                 k = max(10, min(a.steps, 30))
                 reps.append(layer_report(other, time_layer(other, k, min(a.warmup, 5))))
+        for r in reps:
+            r["conv_frac_of_measured_mfma_peak"] = r["conv_tflops_avg"] / peak
+            r["transform_frac_of_measured_copy"] = r["transform_gbs_avg"] / best_stream
         out["layers"] = reps
     if a.ablation:
         out["ablation"] = [time_variants(workloads.layer(i), max(5, min(a.steps, 30))) for i in (2, 3)]
@@ -390,6 +452,10 @@ def main():
         out["table2"] = [layer_report(t2, time_layer(t2, max(5, min(a.steps, 20)), 3)) for t2 in workloads.TABLE2]
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(L)
+        if a.layers == "all":   # the oracle on every layer, whole workloads (a second or less each)
+            for r, other in zip(out["layers"], workloads.LAYERS):
+                cb = out["cpu_baseline"] if other.name == L.name else cpu_baseline(other)
+                r["cpu_seconds"], r["cpu_tflops"], r["cpu_cores"] = cb["seconds"], cb["value"], cb["cores"]
     print(json.dumps(out))
 
 

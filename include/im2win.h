@@ -121,7 +121,8 @@ enum {
     IM2WIN_VARIANT_DEFAULT = 0,
     IM2WIN_VARIANT_NO_PIPELINE = 1,
     IM2WIN_VARIANT_NO_MFMA = 2,
-    IM2WIN_VARIANT_NARROW_LOADS = 3
+    IM2WIN_VARIANT_NARROW_LOADS = 3,
+    IM2WIN_VARIANT_LAST = IM2WIN_VARIANT_NARROW_LOADS
 };
 im2win_status conv2d_im2win_fwd_variant(const float *window_dev, const float *filter_dev,
                                         float *output_dev,
@@ -176,8 +177,34 @@ im2win_status conv2d_im2col_fwd(const float *col_dev, const float *filter_dev, f
                                 int N, int Ci, int Hi, int Wi, int Co, int Hf, int Wf,
                                 int stride, int pad, void *stream);
 
+/*
+ * Which kernel a call would launch, and how: host-side queries that run the
+ * library's own dispatch for the given layer and launch nothing (for reports and
+ * for matching profiler output; they are not needed to use the path).  Buffers
+ * are taken to be 16-byte aligned, as device allocations are.  The choice of
+ * grid depends on the current device's number of compute units; with no device
+ * present an MI355X's 256 are assumed.
+ *   kernel     the kernel as a profiler prints it: function name and template
+ *              arguments, without namespace and parameter list
+ *   grid_x/y   workgroups, block: threads per workgroup, lds_bytes: dynamic LDS
+ * im2win_transform_launch_info describes im2win_transform;
+ * conv2d_im2win_fwd_launch_info describes conv2d_im2win_fwd_variant(variant), or,
+ * with workspace_free != 0 (variant must then be IM2WIN_VARIANT_DEFAULT),
+ * conv2d_im2win_implicit_fwd.  Errors as for the calls they describe.
+ */
+typedef struct {
+    char kernel[160];
+    unsigned grid_x, grid_y, block;
+    size_t lds_bytes;
+} im2win_launch_info;
+im2win_status im2win_transform_launch_info(int N, int Ci, int Hi, int Wi, int Hf, int Wf,
+                                           int stride, int pad, im2win_launch_info *info);
+im2win_status conv2d_im2win_fwd_launch_info(int N, int Ci, int Hi, int Wi, int Co, int Hf, int Wf,
+                                            int stride, int pad, int variant, int workspace_free,
+                                            im2win_launch_info *info);
+
 /* Static description of a status code (never NULL). */
-const char *im2win_status_str(int status);
+const char *im2win_status_str(im2win_status status);
 
 #ifdef __cplusplus
 }

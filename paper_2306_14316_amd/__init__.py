@@ -17,11 +17,20 @@ from .binding import (  # noqa: F401
     VARIANT_NO_PIPELINE,
     VARIANT_NO_MFMA,
     VARIANT_NARROW_LOADS,
+    PROBE_COPY,
+    PROBE_NONTEMPORAL,
+    PROBE_READ,
+    PROBE_WRITE,
+    conv2d_im2win_fwd_launch_info,
+    im2win_probe_mfma_f32,
+    im2win_probe_stream,
+    im2win_transform_launch_info,
     im2col_footprint_bytes,
     im2col_transform,
     im2win_out_shape,
     im2win_transform,
     im2win_workspace_bytes,
+    layer_sizes,
     lib_path,
     load_library,
     status_str,

@@ -25,7 +25,21 @@ EXPORTS = (
     "im2col_transform",
     "conv2d_im2col_fwd",
     "im2win_status_str",
+    "im2win_transform_launch_info",
+    "conv2d_im2win_fwd_launch_info",
 )
+# measurement probes, declared in include/im2win_probe.h
+PROBE_EXPORTS = ("im2win_probe_mfma_f32", "im2win_probe_stream")
+
+
+class LaunchInfo(ctypes.Structure):
+    """im2win_launch_info of the header."""
+    _fields_ = [("kernel", ctypes.c_char * 160), ("grid_x", ctypes.c_uint), ("grid_y", ctypes.c_uint),
+                ("block", ctypes.c_uint), ("lds_bytes", ctypes.c_size_t)]
+
+    def as_dict(self):
+        return {"kernel": self.kernel.decode(), "grid": [self.grid_x, self.grid_y], "block": self.block,
+                "lds_bytes": self.lds_bytes}
 
 
 class Im2winError(RuntimeError):
@@ -65,6 +79,14 @@ def load_library():
         lib.conv2d_im2win_fwd_variant.argtypes = [vp, vp, vp] + [i] * 10 + [vp]
         lib.im2win_status_str.restype = ctypes.c_char_p
         lib.im2win_status_str.argtypes = [i]
+        lib.im2win_transform_launch_info.restype = i
+        lib.im2win_transform_launch_info.argtypes = [i] * 8 + [ctypes.POINTER(LaunchInfo)]
+        lib.conv2d_im2win_fwd_launch_info.restype = i
+        lib.conv2d_im2win_fwd_launch_info.argtypes = [i] * 11 + [ctypes.POINTER(LaunchInfo)]
+        lib.im2win_probe_mfma_f32.restype = i
+        lib.im2win_probe_mfma_f32.argtypes = [vp, i, ctypes.POINTER(ctypes.c_double), vp]
+        lib.im2win_probe_stream.restype = i
+        lib.im2win_probe_stream.argtypes = [i, vp, vp, ctypes.c_size_t, vp]
         _lib = lib
     return _lib
 
@@ -99,6 +121,22 @@ def im2col_footprint_bytes(N, Ci, Hi, Wi, Hf, Wf, stride, pad) -> int:
     return b.value
 
 
+def _window_elems(N, Ci, Hi, Wi, Hf, Wf, stride, pad) -> int:
+    return im2win_workspace_bytes(N, Ci, Hi, Wi, Hf, Wf, stride, pad) // 4
+
+
+def _out_elems(N, Co, Hi, Wi, Hf, Wf, stride, pad) -> int:
+    Ho, Wo = im2win_out_shape(Hi, Wi, Hf, Wf, stride, pad)
+    return N * Co * Ho * Wo
+
+
+def layer_sizes(N, Ci, Hi, Wi, Co, Hf, Wf, stride, pad) -> dict:
+    """Ho, Wo and the element counts of the im2win tensor and the output, as the library derives them."""
+    Ho, Wo = im2win_out_shape(Hi, Wi, Hf, Wf, stride, pad)
+    return {"Ho": Ho, "Wo": Wo, "window_elems": _window_elems(N, Ci, Hi, Wi, Hf, Wf, stride, pad),
+            "output_elems": N * Co * Ho * Wo}
+
+
 def _dev_ptr(t, name: str, numel: int):
     import torch
     if not isinstance(t, torch.Tensor) or not t.is_cuda:
@@ -118,18 +156,16 @@ def _stream(stream):
 
 def im2win_transform(input, window, N, Ci, Hi, Wi, Hf, Wf, stride, pad, stream=None):
     """window <- im2win(input); both are device tensors owned by the caller."""
-    Ho, _ = im2win_out_shape(Hi, Wi, Hf, Wf, stride, pad)
     a = _dev_ptr(input, "input", N * Ci * Hi * Wi)
-    w = _dev_ptr(window, "window", N * Ci * Ho * (Wi + 2 * pad) * Hf)
+    w = _dev_ptr(window, "window", _window_elems(N, Ci, Hi, Wi, Hf, Wf, stride, pad))
     _check(load_library().im2win_transform(a, w, N, Ci, Hi, Wi, Hf, Wf, stride, pad, _stream(stream)),
            "im2win_transform")
 
 
 def _conv(fn_name, window, filter, output, N, Ci, Hi, Wi, Co, Hf, Wf, stride, pad, stream):
-    Ho, Wo = im2win_out_shape(Hi, Wi, Hf, Wf, stride, pad)
-    w = _dev_ptr(window, "window", N * Ci * Ho * (Wi + 2 * pad) * Hf)
+    w = _dev_ptr(window, "window", _window_elems(N, Ci, Hi, Wi, Hf, Wf, stride, pad))
     f = _dev_ptr(filter, "filter", Co * Ci * Hf * Wf)
-    o = _dev_ptr(output, "output", N * Co * Ho * Wo)
+    o = _dev_ptr(output, "output", _out_elems(N, Co, Hi, Wi, Hf, Wf, stride, pad))
     fn = getattr(load_library(), fn_name)
     _check(fn(w, f, o, N, Ci, Hi, Wi, Co, Hf, Wf, stride, pad, _stream(stream)), fn_name)
 
@@ -150,10 +186,9 @@ VARIANT_DEFAULT, VARIANT_NO_PIPELINE, VARIANT_NO_MFMA, VARIANT_NARROW_LOADS = 0,
 def conv2d_im2win_fwd_variant(window, filter, output, N, Ci, Hi, Wi, Co, Hf, Wf, stride, pad, variant,
                               stream=None):
     """output <- the convolution computed by one of the ablation variants (VARIANT_*)."""
-    Ho, Wo = im2win_out_shape(Hi, Wi, Hf, Wf, stride, pad)
-    w = _dev_ptr(window, "window", N * Ci * Ho * (Wi + 2 * pad) * Hf)
+    w = _dev_ptr(window, "window", _window_elems(N, Ci, Hi, Wi, Hf, Wf, stride, pad))
     f = _dev_ptr(filter, "filter", Co * Ci * Hf * Wf)
-    o = _dev_ptr(output, "output", N * Co * Ho * Wo)
+    o = _dev_ptr(output, "output", _out_elems(N, Co, Hi, Wi, Hf, Wf, stride, pad))
     _check(load_library().conv2d_im2win_fwd_variant(w, f, o, N, Ci, Hi, Wi, Co, Hf, Wf, stride, pad,
                                                      int(variant), _stream(stream)),
            "conv2d_im2win_fwd_variant")
@@ -161,10 +196,9 @@ def conv2d_im2win_fwd_variant(window, filter, output, N, Ci, Hi, Wi, Co, Hf, Wf,
 
 def conv2d_im2win_implicit_fwd(input, filter, output, N, Ci, Hi, Wi, Co, Hf, Wf, stride, pad, stream=None):
     """output <- the im2win convolution straight from the NCHW input (no workspace)."""
-    Ho, Wo = im2win_out_shape(Hi, Wi, Hf, Wf, stride, pad)
     a = _dev_ptr(input, "input", N * Ci * Hi * Wi)
     f = _dev_ptr(filter, "filter", Co * Ci * Hf * Wf)
-    o = _dev_ptr(output, "output", N * Co * Ho * Wo)
+    o = _dev_ptr(output, "output", _out_elems(N, Co, Hi, Wi, Hf, Wf, stride, pad))
     _check(load_library().conv2d_im2win_implicit_fwd(a, f, o, N, Ci, Hi, Wi, Co, Hf, Wf, stride, pad,
                                                       _stream(stream)),
            "conv2d_im2win_implicit_fwd")
@@ -172,28 +206,71 @@ def conv2d_im2win_implicit_fwd(input, filter, output, N, Ci, Hi, Wi, Co, Hf, Wf,
 
 def conv2d_direct_fwd(input, filter, output, N, Ci, Hi, Wi, Co, Hf, Wf, stride, pad, stream=None):
     """output <- the direct convolution (baseline): one thread per output, no workspace."""
-    Ho, Wo = im2win_out_shape(Hi, Wi, Hf, Wf, stride, pad)
     a = _dev_ptr(input, "input", N * Ci * Hi * Wi)
     f = _dev_ptr(filter, "filter", Co * Ci * Hf * Wf)
-    o = _dev_ptr(output, "output", N * Co * Ho * Wo)
+    o = _dev_ptr(output, "output", _out_elems(N, Co, Hi, Wi, Hf, Wf, stride, pad))
     _check(load_library().conv2d_direct_fwd(a, f, o, N, Ci, Hi, Wi, Co, Hf, Wf, stride, pad, _stream(stream)),
            "conv2d_direct_fwd")
 
 
 def im2col_transform(input, col, N, Ci, Hi, Wi, Hf, Wf, stride, pad, stream=None):
     """col <- the stacked im2col matrices (baseline), N*Ho*Wo rows of Ci*Hf*Wf floats."""
-    Ho, Wo = im2win_out_shape(Hi, Wi, Hf, Wf, stride, pad)
     a = _dev_ptr(input, "input", N * Ci * Hi * Wi)
-    c = _dev_ptr(col, "col", N * Ho * Wo * Ci * Hf * Wf)
+    c = _dev_ptr(col, "col", im2col_footprint_bytes(N, Ci, Hi, Wi, Hf, Wf, stride, pad) // 4)
     _check(load_library().im2col_transform(a, c, N, Ci, Hi, Wi, Hf, Wf, stride, pad, _stream(stream)),
            "im2col_transform")
 
 
 def conv2d_im2col_fwd(col, filter, output, N, Ci, Hi, Wi, Co, Hf, Wf, stride, pad, stream=None):
     """output <- GEMM of the im2col matrix with the filter matrix (baseline)."""
-    Ho, Wo = im2win_out_shape(Hi, Wi, Hf, Wf, stride, pad)
-    c = _dev_ptr(col, "col", N * Ho * Wo * Ci * Hf * Wf)
+    c = _dev_ptr(col, "col", im2col_footprint_bytes(N, Ci, Hi, Wi, Hf, Wf, stride, pad) // 4)
     f = _dev_ptr(filter, "filter", Co * Ci * Hf * Wf)
-    o = _dev_ptr(output, "output", N * Co * Ho * Wo)
+    o = _dev_ptr(output, "output", _out_elems(N, Co, Hi, Wi, Hf, Wf, stride, pad))
     _check(load_library().conv2d_im2col_fwd(c, f, o, N, Ci, Hi, Wi, Co, Hf, Wf, stride, pad, _stream(stream)),
            "conv2d_im2col_fwd")
+
+
+def im2win_transform_launch_info(N, Ci, Hi, Wi, Hf, Wf, stride, pad) -> dict:
+    """The kernel im2win_transform would launch for this layer (nothing is launched)."""
+    info = LaunchInfo()
+    _check(load_library().im2win_transform_launch_info(N, Ci, Hi, Wi, Hf, Wf, stride, pad, ctypes.byref(info)),
+           "im2win_transform_launch_info")
+    return info.as_dict()
+
+
+def conv2d_im2win_fwd_launch_info(N, Ci, Hi, Wi, Co, Hf, Wf, stride, pad, variant=VARIANT_DEFAULT,
+                                  workspace_free=False) -> dict:
+    """The kernel conv2d_im2win_fwd_variant (or conv2d_im2win_implicit_fwd) would launch (nothing is launched)."""
+    info = LaunchInfo()
+    _check(load_library().conv2d_im2win_fwd_launch_info(N, Ci, Hi, Wi, Co, Hf, Wf, stride, pad, int(variant),
+                                                         1 if workspace_free else 0, ctypes.byref(info)),
+           "conv2d_im2win_fwd_launch_info")
+    return info.as_dict()
+
+
+PROBE_COPY, PROBE_READ, PROBE_WRITE, PROBE_NONTEMPORAL = 0, 1, 2, 4
+
+
+def _raw_ptr(t, name: str):
+    import torch
+    if not isinstance(t, torch.Tensor) or not t.is_cuda or not t.is_contiguous():
+        raise TypeError("%s must be a contiguous torch tensor in GPU memory" % name)
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def im2win_probe_mfma_f32(sink, mfma_per_wave: int, stream=None) -> float:
+    """Enqueue the register-resident fp32 MFMA loop; returns the flops of the launch."""
+    fl = ctypes.c_double()
+    _check(load_library().im2win_probe_mfma_f32(_dev_ptr(sink, "sink", sink.numel()), int(mfma_per_wave),
+                                                 ctypes.byref(fl), _stream(stream)), "im2win_probe_mfma_f32")
+    return fl.value
+
+
+def im2win_probe_stream(mode: int, src, dst, nbytes: int, stream=None):
+    """Enqueue a streaming kernel (PROBE_COPY / PROBE_READ / PROBE_WRITE, | PROBE_NONTEMPORAL) over nbytes."""
+    for t, name in ((src, "src"), (dst, "dst")):
+        if t is not None and t.numel() * t.element_size() < (nbytes if not (name == "dst" and (mode & 3) == PROBE_READ) else 16):
+            raise ValueError("%s is smaller than %d bytes" % (name, nbytes))
+    _check(load_library().im2win_probe_stream(int(mode), _raw_ptr(src, "src") if src is not None else None,
+                                               _raw_ptr(dst, "dst"), int(nbytes), _stream(stream)),
+           "im2win_probe_stream")

@@ -4,6 +4,9 @@
 #include "common.h"
 
 #include <limits.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
 
 using im2win::Shape;
 
@@ -43,7 +46,30 @@ im2win_status derive(int N, int Ci, int Hi, int Wi, int Co, int Hf, int Wf, int 
     return IM2WIN_OK;
 }
 
+im2win_status copy_plan(const im2win::LaunchPlan &plan, im2win_launch_info *info)
+{
+    static_assert(sizeof(info->kernel) == sizeof(plan.kernel), "same name capacity on both sides of the ABI");
+    memcpy(info->kernel, plan.kernel, sizeof(info->kernel));
+    info->grid_x = plan.grid_x; info->grid_y = plan.grid_y; info->block = plan.block;
+    info->lds_bytes = plan.lds_bytes;
+    return IM2WIN_OK;
+}
+
+// Stand-ins for the buffers of a planned call: never dereferenced, 16-byte aligned like the
+// buffers the planning calls are documented to assume.
+const float *const kAlignedIn = reinterpret_cast<const float *>(uintptr_t(256));
+float *const kAlignedOut = reinterpret_cast<float *>(uintptr_t(512));
+
 }  // namespace
+
+void im2win::plan_record(LaunchPlan *plan, dim3 grid, unsigned block, size_t lds, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(plan->kernel, sizeof(plan->kernel), fmt, ap);
+    va_end(ap);
+    plan->grid_x = grid.x; plan->grid_y = grid.y; plan->block = block; plan->lds_bytes = lds;
+}
 
 extern "C" {
 
@@ -109,7 +135,7 @@ im2win_status conv2d_im2win_fwd_variant(const float *window_dev, const float *fi
                                         int pad, int variant, void *stream)
 {
     if (!window_dev || !filter_dev || !output_dev) return IM2WIN_ERR_NULL;
-    if (variant < IM2WIN_VARIANT_DEFAULT || variant > IM2WIN_VARIANT_NARROW_LOADS) return IM2WIN_ERR_UNSUPPORTED;
+    if (variant < IM2WIN_VARIANT_DEFAULT || variant > IM2WIN_VARIANT_LAST) return IM2WIN_ERR_UNSUPPORTED;
     Shape sh;
     im2win_status st = derive(N, Ci, Hi, Wi, Co, Hf, Wf, stride, pad, &sh);
     if (st != IM2WIN_OK) return st;
@@ -181,7 +207,36 @@ im2win_status conv2d_im2col_fwd(const float *col_dev, const float *filter_dev, f
     return e == hipSuccess ? IM2WIN_OK : IM2WIN_ERR_HIP;
 }
 
-const char *im2win_status_str(int status)
+im2win_status im2win_transform_launch_info(int N, int Ci, int Hi, int Wi, int Hf, int Wf, int stride, int pad,
+                                           im2win_launch_info *info)
+{
+    if (!info) return IM2WIN_ERR_NULL;
+    Shape sh;
+    im2win_status st = derive(N, Ci, Hi, Wi, 1, Hf, Wf, stride, pad, &sh);
+    if (st != IM2WIN_OK) return st;
+    im2win::LaunchPlan plan;
+    hipError_t e = im2win::launch_transform(kAlignedIn, kAlignedOut, sh, nullptr, &plan);
+    return e == hipSuccess ? copy_plan(plan, info) : IM2WIN_ERR_HIP;
+}
+
+im2win_status conv2d_im2win_fwd_launch_info(int N, int Ci, int Hi, int Wi, int Co, int Hf, int Wf, int stride,
+                                            int pad, int variant, int workspace_free, im2win_launch_info *info)
+{
+    if (!info) return IM2WIN_ERR_NULL;
+    if (variant < IM2WIN_VARIANT_DEFAULT || variant > IM2WIN_VARIANT_LAST) return IM2WIN_ERR_UNSUPPORTED;
+    if (workspace_free && variant != IM2WIN_VARIANT_DEFAULT) return IM2WIN_ERR_UNSUPPORTED;
+    Shape sh;
+    im2win_status st = derive(N, Ci, Hi, Wi, Co, Hf, Wf, stride, pad, &sh);
+    if (st != IM2WIN_OK) return st;
+    im2win::LaunchPlan plan;
+    hipError_t e = workspace_free
+        ? im2win::launch_conv_implicit(kAlignedIn, kAlignedIn, kAlignedOut, sh, nullptr, &plan)
+        : im2win::launch_conv_mfma(kAlignedIn, kAlignedIn, kAlignedOut, sh, nullptr, variant, &plan);
+    if (e == hipErrorInvalidConfiguration || e == hipErrorNotSupported) return IM2WIN_ERR_UNSUPPORTED;
+    return e == hipSuccess ? copy_plan(plan, info) : IM2WIN_ERR_HIP;
+}
+
+const char *im2win_status_str(im2win_status status)
 {
     switch (status) {
         case IM2WIN_OK: return "ok";

@@ -49,7 +49,7 @@ __global__ __launch_bounds__(256) void conv_direct_kernel(DirectParams P)
 }
 
 hipError_t launch_conv_direct(const float *in, const float *flt, float *out, const Shape &sh,
-                              hipStream_t st)
+                              hipStream_t st, LaunchPlan *plan)
 {
     DirectParams P;
     P.in = in; P.flt = flt; P.out = out;
@@ -59,6 +59,7 @@ hipError_t launch_conv_direct(const float *in, const float *flt, float *out, con
     P.d_wo = make_fastdiv((uint32_t)sh.Wo);
     P.d_ho = make_fastdiv((uint32_t)sh.Ho);
     P.d_co = make_fastdiv((uint32_t)sh.Co);
+    if (plan) { plan_record(plan, dim3((P.total + 255u) / 256u), 256, 0, "conv_direct_kernel"); return hipSuccess; }
     hipLaunchKernelGGL(conv_direct_kernel, dim3((P.total + 255u) / 256u), dim3(256), 0, st, P);
     return hipGetLastError();
 }

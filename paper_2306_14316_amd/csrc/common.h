@@ -61,26 +61,39 @@ struct Shape {
     int npix;     // N*Ho*Wo : GEMM N dimension
 };
 
+// A launcher that is handed a LaunchPlan decides exactly as it would for a launch -- kernel
+// instance, grid, LDS -- writes the decision down and launches nothing.  The kernel is named as
+// a profiler prints it: function name and template arguments, without namespace or parameters.
+struct LaunchPlan {
+    char kernel[160];
+    unsigned grid_x, grid_y, block;
+    size_t lds_bytes;
+};
+void plan_record(LaunchPlan *plan, dim3 grid, unsigned block, size_t lds, const char *fmt, ...)
+    __attribute__((format(printf, 5, 6)));
+inline const char *tf(bool b) { return b ? "true" : "false"; }
+
 // ---- launchers (defined in the .hip files) -------------------------------
-hipError_t launch_transform(const float *in, float *win, const Shape &sh, hipStream_t st);
+hipError_t launch_transform(const float *in, float *win, const Shape &sh, hipStream_t st,
+                            LaunchPlan *plan = nullptr);
 hipError_t launch_conv_basic(const float *win, const float *flt, float *out, const Shape &sh,
-                             hipStream_t st);
+                             hipStream_t st, LaunchPlan *plan = nullptr);
 // Comparison baselines: direct convolution on the NCHW input; im2col matrix and GEMM over it.
 // The im2col launchers return hipErrorInvalidValue when the matrix has 2^31 or more 16-byte groups.
 hipError_t launch_conv_direct(const float *in, const float *flt, float *out, const Shape &sh,
-                              hipStream_t st);
+                              hipStream_t st, LaunchPlan *plan = nullptr);
 hipError_t launch_im2col(const float *in, float *col, const Shape &sh, hipStream_t st);
 hipError_t launch_gemm_im2col(const float *col, const float *flt, float *out, const Shape &sh,
                               hipStream_t st);
 // Workspace-free convolution from the NCHW input; hipErrorNotSupported when the layer is not one the
 // pipelined kernel takes.
 hipError_t launch_conv_implicit(const float *in, const float *flt, float *out, const Shape &sh,
-                                hipStream_t st);
+                                hipStream_t st, LaunchPlan *plan = nullptr);
 // Kernel selection for the MFMA convolution (the values of the public
 // IM2WIN_VARIANT_* constants).
 enum ConvVariant { kVariantDefault = 0, kVariantNoPipeline = 1, kVariantNoMfma = 2, kVariantNarrowLoads = 3 };
 // Returns hipErrorInvalidConfiguration when no tile configuration fits in LDS.
 hipError_t launch_conv_mfma(const float *win, const float *flt, float *out, const Shape &sh,
-                            hipStream_t st, int variant = kVariantDefault);
+                            hipStream_t st, int variant = kVariantDefault, LaunchPlan *plan = nullptr);
 
 }  // namespace im2win

@@ -44,7 +44,7 @@ __global__ __launch_bounds__(256) void conv_basic_kernel(BasicParams P)
 }
 
 hipError_t launch_conv_basic(const float *win, const float *flt, float *out, const Shape &sh,
-                             hipStream_t st)
+                             hipStream_t st, LaunchPlan *plan)
 {
     BasicParams P;
     P.win = win; P.flt = flt; P.out = out;
@@ -56,6 +56,7 @@ hipError_t launch_conv_basic(const float *win, const float *flt, float *out, con
     P.d_ho = make_fastdiv((uint32_t)sh.Ho);
     P.d_co = make_fastdiv((uint32_t)sh.Co);
     uint32_t blocks = (P.total + 255u) / 256u;
+    if (plan) { plan_record(plan, dim3(blocks), 256, 0, "conv_basic_kernel"); return hipSuccess; }
     hipLaunchKernelGGL(conv_basic_kernel, dim3(blocks), dim3(256), 0, st, P);
     return hipGetLastError();
 }

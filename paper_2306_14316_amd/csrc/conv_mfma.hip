@@ -24,6 +24,9 @@
 // The filter tile is staged to LDS in window order (v outer, u inner) and
 // transposed to [k][m], so the A operand is also base + constant per step.
 #include "conv_mfma_tile.h"
+#include "runtime_cache.h"
+
+#include <limits.h>
 
 namespace im2win {
 
@@ -188,11 +191,14 @@ static size_t lds_bytes(int cb, int S, int khw)
 }
 
 template <int KHW_T>
-static hipError_t launch_t(const MfmaParams &P, size_t lds, uint32_t blocks, hipStream_t st)
+static hipError_t launch_t(const MfmaParams &P, size_t lds, uint32_t blocks, hipStream_t st, LaunchPlan *plan)
 {
+    if (plan) { plan_record(plan, dim3(blocks), 256, lds, "conv_mfma_kernel<%d>", KHW_T); return hipSuccess; }
     if (lds > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_mfma_kernel<KHW_T>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        static KernelCache kc;
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e == hipSuccess) e = allow_dynamic_lds(kc, reinterpret_cast<const void *>(&conv_mfma_kernel<KHW_T>), lds, dev);
         if (e != hipSuccess) return e;
     }
     hipLaunchKernelGGL(conv_mfma_kernel<KHW_T>, dim3(blocks), dim3(256), lds, st, P);
@@ -200,7 +206,10 @@ static hipError_t launch_t(const MfmaParams &P, size_t lds, uint32_t blocks, hip
 }
 
 // Tile-independent kernel parameters of a layer (everything but the generic kernel's K block).
-static void fill_params(MfmaParams &P, const float *win, const float *flt, float *out, const Shape &sh)
+// Returns false when the layer is outside what the tiled kernels index with 32-bit integers or
+// stage in LDS (a tile's strips of one channel would not fit): the caller then takes the
+// one-thread-per-output kernel, which handles any legal shape.
+static bool fill_params(MfmaParams &P, const float *win, const float *flt, float *out, const Shape &sh)
 {
     P.win = win; P.flt = flt; P.out = out;
     P.Ci = sh.Ci; P.Ho = sh.Ho; P.Wo = sh.Wo; P.Co = sh.Co; P.Hf = sh.Hf; P.Wf = sh.Wf; P.s = sh.s;
@@ -213,14 +222,21 @@ static void fill_params(MfmaParams &P, const float *win, const float *flt, float
     P.implicit = 0;
     P.Hi = sh.Hi; P.Wi = sh.Wi; P.p = sh.p;
     P.in_plane = (uint32_t)(sh.Hi * sh.Wi);
-    P.fullseg = ((sh.Wo - 1) * sh.s + sh.Wf) * sh.Hf;
     P.tiles_m = (sh.Co + MB - 1) / MB;
 
-    // Strip floats per channel: NB pixels over at most rmax output rows.
+    // Strip floats per channel: NB pixels over R output rows take ((NB - R)*s + R*Wf)*Hf floats.
+    // With overlapping windows (s < Wf) that grows with R, at most rmax rows; otherwise it is
+    // largest for the fewest rows NB pixels can lie in.  In 64 bits: the stride has no upper bound.
     int rmax = (NB + sh.Wo - 2) / sh.Wo + 1;
     if (rmax > NB) rmax = NB;
-    const int over = sh.Wf > sh.s ? sh.Wf - sh.s : 0;
-    P.S = (NB * sh.s + rmax * over) * sh.Hf + 1;
+    const int rmin = (NB + sh.Wo - 1) / sh.Wo;
+    const long long R = sh.s < sh.Wf ? rmax : rmin;
+    const long long S = ((NB - R) * (long long)sh.s + R * sh.Wf) * sh.Hf + 1;
+    const long long fullseg = ((long long)(sh.Wo - 1) * sh.s + sh.Wf) * sh.Hf;
+    const long long step = (long long)sh.s * sh.Hf;   // floats between neighbouring windows
+    if (S > 160 * 1024 / 4 || fullseg > INT_MAX || step * sh.Wo > INT_MAX) return false;
+    P.fullseg = (int)fullseg;
+    P.S = (int)S;
     P.rmax = rmax;
     P.cb = 0;
     P.vec4 = 0;
@@ -231,10 +247,11 @@ static void fill_params(MfmaParams &P, const float *win, const float *flt, float
     P.d_wf = make_fastdiv((uint32_t)sh.Wf);
     P.d_cpr = make_fastdiv(1);
     P.d_tm = make_fastdiv((uint32_t)P.tiles_m);
+    return true;
 }
 
 // The generic kernel: picks the channels per K block that fit in LDS and launches.
-static hipError_t launch_generic(MfmaParams &P, const Shape &sh, uint32_t blocks, hipStream_t st)
+static hipError_t launch_generic(MfmaParams &P, const Shape &sh, uint32_t blocks, hipStream_t st, LaunchPlan *plan)
 {
     const size_t lds_max = 160 * 1024;
     int cb = sh.Ci < 8 ? sh.Ci : 8;
@@ -246,46 +263,52 @@ static hipError_t launch_generic(MfmaParams &P, const Shape &sh, uint32_t blocks
              ((reinterpret_cast<uintptr_t>(P.flt) & 15u) == 0);
     P.d_cpr = make_fastdiv((uint32_t)((cb * sh.khw) / 4 > 0 ? (cb * sh.khw) / 4 : 1));
     switch (sh.khw) {
-        case 9:   return launch_t<9>(P, lds, blocks, st);
-        case 49:  return launch_t<49>(P, lds, blocks, st);
-        case 121: return launch_t<121>(P, lds, blocks, st);
-        default:  return launch_t<0>(P, lds, blocks, st);
+        case 9:   return launch_t<9>(P, lds, blocks, st, plan);
+        case 49:  return launch_t<49>(P, lds, blocks, st, plan);
+        case 121: return launch_t<121>(P, lds, blocks, st, plan);
+        default:  return launch_t<0>(P, lds, blocks, st, plan);
     }
 }
 
 // Workspace-free convolution straight from the NCHW input: the pipelined kernel where the
-// layer fits it, the generic kernel otherwise.
+// layer fits it, the generic kernel otherwise; a layer neither can tile (see fill_params; a
+// window too large for the LDS filter tile) is computed by the direct one-thread-per-output kernel.
 hipError_t launch_conv_implicit(const float *in, const float *flt, float *out, const Shape &sh,
-                                hipStream_t st)
+                                hipStream_t st, LaunchPlan *plan)
 {
     MfmaParams P;
-    fill_params(P, in, flt, out, sh);
+    if (!fill_params(P, in, flt, out, sh)) return launch_conv_direct(in, flt, out, sh, st, plan);
     P.implicit = 1;
     P.win_elems = (size_t)sh.N * sh.Ci * sh.Hi * (size_t)sh.Wi;   // the tensor P.win points at is the input
     const uint32_t blocks = ((P.npix + NB - 1) / NB) * (uint32_t)P.tiles_m;
-    hipError_t fe = launch_conv_mfma_shallow(in, flt, out, sh, st, true);
+    hipError_t fe = launch_conv_mfma_shallow(in, flt, out, sh, st, true, plan);
     if (fe != hipErrorNotSupported) return fe;
-    fe = launch_conv_mfma_fast(P, sh, blocks, st, true);
+    fe = launch_conv_mfma_fast(P, sh, blocks, st, true, false, plan);
     if (fe != hipErrorNotSupported) return fe;
-    return launch_generic(P, sh, blocks, st);
+    fe = launch_generic(P, sh, blocks, st, plan);
+    if (fe == hipErrorInvalidConfiguration) return launch_conv_direct(in, flt, out, sh, st, plan);
+    return fe;
 }
 
 hipError_t launch_conv_mfma(const float *win, const float *flt, float *out, const Shape &sh,
-                            hipStream_t st, int variant)
+                            hipStream_t st, int variant, LaunchPlan *plan)
 {
-    if (variant == kVariantNoMfma) return launch_conv_basic(win, flt, out, sh, st);
+    if (variant == kVariantNoMfma) return launch_conv_basic(win, flt, out, sh, st, plan);
     MfmaParams P;
-    fill_params(P, win, flt, out, sh);
+    if (!fill_params(P, win, flt, out, sh)) return launch_conv_basic(win, flt, out, sh, st, plan);
 
     const uint32_t tiles_n = (P.npix + NB - 1) / NB;
     const uint32_t blocks = tiles_n * (uint32_t)P.tiles_m;
     if (variant == kVariantDefault || variant == kVariantNarrowLoads) {
-        hipError_t fe = launch_conv_mfma_shallow(win, flt, out, sh, st);
+        hipError_t fe = launch_conv_mfma_shallow(win, flt, out, sh, st, false, plan);
         if (fe != hipErrorNotSupported) return fe;
-        fe = launch_conv_mfma_fast(P, sh, blocks, st, false, variant == kVariantNarrowLoads);
+        fe = launch_conv_mfma_fast(P, sh, blocks, st, false, variant == kVariantNarrowLoads, plan);
         if (fe != hipErrorNotSupported) return fe;
     }
-    return launch_generic(P, sh, blocks, st);
+    // (a window too large for the generic kernel's LDS filter tile: the basic kernel computes it)
+    const hipError_t ge = launch_generic(P, sh, blocks, st, plan);
+    if (ge == hipErrorInvalidConfiguration) return launch_conv_basic(win, flt, out, sh, st, plan);
+    return ge;
 }
 
 }  // namespace im2win

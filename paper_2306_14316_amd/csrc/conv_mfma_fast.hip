@@ -16,6 +16,7 @@
 //   - every non-MFMA instruction of the K loop is placed, in program order,
 //     between two MFMAs of the wave's dependent chain, where it issues for free.
 #include "conv_mfma_tile.h"
+#include "runtime_cache.h"
 
 #include <type_traits>
 
@@ -659,10 +660,10 @@ __global__ __launch_bounds__(256, OCC) void conv_mfma_fast_kernel(MfmaParams P)
 }
 
 template <int HF, int WF, int CB, int JX, int CW, int OCC>
-static hipError_t launch_fast_i(const MfmaParams &P, uint32_t blocks, hipStream_t st, bool implicit);
+static hipError_t launch_fast_i(const MfmaParams &P, uint32_t blocks, hipStream_t st, bool implicit, LaunchPlan *plan);
 
 template <int HF, int WF, int CB, int JX, int CW, int OCC, bool IMP = false>
-static hipError_t launch_fast_t(const MfmaParams &P, uint32_t blocks, hipStream_t st)
+static hipError_t launch_fast_t(const MfmaParams &P, uint32_t blocks, hipStream_t st, LaunchPlan *plan)
 {
     constexpr int KB = CB * HF * WF;
     constexpr int PF = KB | 1;
@@ -678,8 +679,8 @@ static hipError_t launch_fast_t(const MfmaParams &P, uint32_t blocks, hipStream_
     Q.nmain = blocks;
     uint32_t grid = blocks;
     int dev = 0, ncu = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e == hipSuccess) e = hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev);
+    hipError_t e = device_cus(&dev, &ncu);
+    if (e != hipSuccess && plan) { e = hipSuccess; ncu = 256; }   // planning without a device: an MI355X's 256 compute units
     if (e != hipSuccess) return e;
     if ((Q.Ci / CB) % 2 == 0 && Q.Ci / CB <= 12 && Q.Co % MB == 0) {
         const uint32_t resident = ((uint32_t)ncu * OCC) & ~7u;
@@ -711,31 +712,35 @@ static hipError_t launch_fast_t(const MfmaParams &P, uint32_t blocks, hipStream_
     }
     Q.nhalf = nhalf;
     void (*kern)(MfmaParams) = &conv_mfma_fast_kernel<HF, WF, CB, JX, CW, OCC, IMP, false, false>;
-    if (grid < blocks) kern = &conv_mfma_fast_kernel<HF, WF, CB, JX, CW, OCC, IMP, true, false>;
-    if (npiece && !nhalf) kern = &conv_mfma_fast_kernel<HF, WF, CB, JX, CW, OCC, IMP, false, PIECEABLE>;
-    if (nhalf && !npiece) kern = &conv_mfma_fast_kernel<HF, WF, CB, JX, CW, OCC, IMP, false, false, HALFABLE>;
-    if (nhalf && npiece) kern = &conv_mfma_fast_kernel<HF, WF, CB, JX, CW, OCC, IMP, false, PIECEABLE, HALFABLE>;
-    if (lds > 48 * 1024) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
+    int which = 0;   // which of this launcher's five kernel instances
+    if (grid < blocks) { kern = &conv_mfma_fast_kernel<HF, WF, CB, JX, CW, OCC, IMP, true, false>; which = 1; }
+    if (npiece && !nhalf) { kern = &conv_mfma_fast_kernel<HF, WF, CB, JX, CW, OCC, IMP, false, PIECEABLE>; which = 2; }
+    if (nhalf && !npiece) { kern = &conv_mfma_fast_kernel<HF, WF, CB, JX, CW, OCC, IMP, false, false, HALFABLE>; which = 3; }
+    if (nhalf && npiece) { kern = &conv_mfma_fast_kernel<HF, WF, CB, JX, CW, OCC, IMP, false, PIECEABLE, HALFABLE>; which = 4; }
+    if (plan) {
+        const bool per = which == 1, tail = (which == 2 || which == 4) && PIECEABLE, half = (which == 3 || which == 4) && HALFABLE;
+        plan_record(plan, dim3(grid), 256, lds, "conv_mfma_fast_kernel<%d, %d, %d, %d, %d, %d, %s, %s, %s, %s>",
+                    HF, WF, CB, JX, CW, OCC, tf(IMP), tf(per), tf(tail), tf(half));
+        return hipSuccess;
     }
+    static KernelCache kc[5];
+    if ((e = allow_dynamic_lds(kc[which], reinterpret_cast<const void *>(kern), lds, dev)) != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, st, Q);
     return hipGetLastError();
 }
 
 template <int HF, int WF, int CB, int JX, int CW, int OCC>
-static hipError_t launch_fast_i(const MfmaParams &P, uint32_t blocks, hipStream_t st, bool implicit)
+static hipError_t launch_fast_i(const MfmaParams &P, uint32_t blocks, hipStream_t st, bool implicit, LaunchPlan *plan)
 {
-    return implicit ? launch_fast_t<HF, WF, CB, JX, CW, OCC, true>(P, blocks, st)
-                    : launch_fast_t<HF, WF, CB, JX, CW, OCC, false>(P, blocks, st);
+    return implicit ? launch_fast_t<HF, WF, CB, JX, CW, OCC, true>(P, blocks, st, plan)
+                    : launch_fast_t<HF, WF, CB, JX, CW, OCC, false>(P, blocks, st, plan);
 }
 
 // Returns hipErrorNotSupported when the layer does not meet the fast path's conditions.
 // implicit: P.win is the NCHW input (P.Hi, P.Wi, P.p, P.in_plane set; P.win_elems = its size).
 // narrow: the ablation instance that fetches the filter in 8-byte pieces, where there is one.
 hipError_t launch_conv_mfma_fast(MfmaParams P, const Shape &sh, uint32_t blocks, hipStream_t st, bool implicit,
-                                 bool narrow)
+                                 bool narrow, LaunchPlan *plan)
 {
     const uintptr_t fa = reinterpret_cast<uintptr_t>(P.flt);
     const bool al16 = (fa & 15u) == 0 && (sh.K % 4 == 0);   // filter rows readable as aligned float4
@@ -753,20 +758,20 @@ hipError_t launch_conv_mfma_fast(MfmaParams P, const Shape &sh, uint32_t blocks,
     if (((unsigned long long)sh.Co * (unsigned long long)P.rmax + 64ull) * (unsigned long long)sh.Ho * sh.Wo * 4ull >= (1ull << 32))
         return hipErrorNotSupported;
     if (narrow && !implicit && sh.Hf == 3 && sh.Wf == 3 && sh.Ci % 8 == 0 && al16) {   // ablation: 8-byte filter chunks
-        if (P.S <= 256) return launch_fast_t<3, 3, 8, 1, 2, 3, false>(P, blocks, st);
-        if (P.S <= 512) return launch_fast_t<3, 3, 8, 2, 2, 3, false>(P, blocks, st);
+        if (P.S <= 256) return launch_fast_t<3, 3, 8, 1, 2, 3, false>(P, blocks, st, plan);
+        if (P.S <= 512) return launch_fast_t<3, 3, 8, 2, 2, 3, false>(P, blocks, st, plan);
     }
     if (sh.Hf == 3 && sh.Wf == 3 && sh.Ci % 8 == 0 && al16) {
-        if (P.S <= 256) return launch_fast_i<3, 3, 8, 1, 4, 3>(P, blocks, st, implicit);
-        if (P.S <= 512) return launch_fast_i<3, 3, 8, 2, 4, 3>(P, blocks, st, implicit);
+        if (P.S <= 256) return launch_fast_i<3, 3, 8, 1, 4, 3>(P, blocks, st, implicit, plan);
+        if (P.S <= 512) return launch_fast_i<3, 3, 8, 2, 4, 3>(P, blocks, st, implicit, plan);
     }
     if (sh.Hf == 5 && sh.Wf == 5 && sh.Ci % 4 == 0 && al16) {
-        if (P.S <= 256) return launch_fast_i<5, 5, 4, 1, 4, 2>(P, blocks, st, implicit);
-        if (P.S <= 512) return launch_fast_i<5, 5, 4, 2, 4, 2>(P, blocks, st, implicit);
+        if (P.S <= 256) return launch_fast_i<5, 5, 4, 1, 4, 2>(P, blocks, st, implicit, plan);
+        if (P.S <= 512) return launch_fast_i<5, 5, 4, 2, 4, 2>(P, blocks, st, implicit, plan);
     }
     if (sh.Hf == 7 && sh.Wf == 7 && sh.Ci % 2 == 0 && al8) {
-        if (P.S <= 512) return launch_fast_i<7, 7, 2, 2, 2, 2>(P, blocks, st, implicit);
-        if (P.S <= 1024) return launch_fast_i<7, 7, 2, 4, 2, 2>(P, blocks, st, implicit);
+        if (P.S <= 512) return launch_fast_i<7, 7, 2, 2, 2, 2>(P, blocks, st, implicit, plan);
+        if (P.S <= 1024) return launch_fast_i<7, 7, 2, 4, 2, 2>(P, blocks, st, implicit, plan);
     }
     return hipErrorNotSupported;
 }

@@ -17,7 +17,9 @@
 //     share a 32x32 output block, each taking half of the K steps, and exchange
 //     half of their accumulators through LDS before the store (KS = 2).
 #include "conv_mfma_tile.h"
+#include "runtime_cache.h"
 
+#include <algorithm>
 #include <type_traits>
 #include <utility>
 
@@ -475,7 +477,7 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
 }
 
 template <int HF, int WF, int CI, int WM, int KS, int JX, bool IMP, int G>
-static hipError_t launch_shallow_k(ShallowParams P, int mgroups, hipStream_t st)
+static hipError_t launch_shallow_k(ShallowParams P, int mgroups, hipStream_t st, LaunchPlan *plan)
 {
     P.ntiles = (P.npix + NB * G - 1) / (NB * G);
     constexpr int NT = 64 * WM * 2 * KS;
@@ -483,52 +485,56 @@ static hipError_t launch_shallow_k(ShallowParams P, int mgroups, hipStream_t st)
     constexpr int STAGE = CI * SS + 4;
     constexpr size_t lds = 4u * (size_t)(2 * STAGE + (KS == 2 ? 2 * WM * 2 * 2 * 8 * 64 : 0));
     auto kern = &conv_mfma_shallow_kernel<HF, WF, CI, WM, KS, JX, IMP, G>;
-    if (lds > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-    }
+    static KernelCache kc;
+    int dev = 0, ncu = 0;
+    hipError_t e = device_cus(&dev, &ncu);
+    const bool blind = e != hipSuccess && plan;   // planning without a device: an MI355X's 256 compute units
+    if (blind) { e = hipSuccess; ncu = 256; }
+    if (e != hipSuccess) return e;
+    if (!plan && (e = allow_dynamic_lds(kc, reinterpret_cast<const void *>(kern), lds, dev)) != hipSuccess) return e;
     // Persistent grid: enough workgroups to give every CU its share of resident waves.
     int per_cu = 0;
-    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, NT, lds);
-    if (e != hipSuccess) return e;
+    if (blind) per_cu = (int)std::min<size_t>(3, (160 * 1024) / lds);   // (LDS is what limits these kernels)
+    else if ((e = resident_per_cu(kc, reinterpret_cast<const void *>(kern), NT, lds, dev, &per_cu)) != hipSuccess) return e;
     if (per_cu < 1) return hipErrorInvalidConfiguration;
     if (per_cu > 3) per_cu = 3;
-    int dev = 0, ncu = 0;
-    if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
-    if ((e = hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
     uint32_t gx = (uint32_t)(ncu * per_cu) / (uint32_t)mgroups;
     if (gx < 1) gx = 1;
     if (gx > P.ntiles) gx = P.ntiles;
+    if (plan) {
+        plan_record(plan, dim3(gx, mgroups), NT, lds, "conv_mfma_shallow_kernel<%d, %d, %d, %d, %d, %d, %s, %d>",
+                    HF, WF, CI, WM, KS, JX, tf(IMP), G);
+        return hipSuccess;
+    }
     hipLaunchKernelGGL(kern, dim3(gx, mgroups), dim3(NT), lds, st, P);
     return hipGetLastError();
 }
 
 template <int HF, int WF, int CI, int WM, int KS, int JX, int G = 1>
-static hipError_t launch_shallow_t(const ShallowParams &P, int mgroups, hipStream_t st, bool implicit)
+static hipError_t launch_shallow_t(const ShallowParams &P, int mgroups, hipStream_t st, bool implicit, LaunchPlan *plan)
 {
-    return implicit ? launch_shallow_k<HF, WF, CI, WM, KS, JX, true, G>(P, mgroups, st)
-                    : launch_shallow_k<HF, WF, CI, WM, KS, JX, false, G>(P, mgroups, st);
+    return implicit ? launch_shallow_k<HF, WF, CI, WM, KS, JX, true, G>(P, mgroups, st, plan)
+                    : launch_shallow_k<HF, WF, CI, WM, KS, JX, false, G>(P, mgroups, st, plan);
 }
 
 // Returns hipErrorNotSupported when the layer does not meet this kernel's conditions.
 // implicit: `win` is the NCHW input (workspace-free variant).
 hipError_t launch_conv_mfma_shallow(const float *win, const float *flt, float *out, const Shape &sh,
-                                    hipStream_t st, bool implicit)
+                                    hipStream_t st, bool implicit, LaunchPlan *plan)
 {
     // rows a tile of 64*g pixels may touch, and its strip floats per channel (0: too many rows)
     auto rows_of = [&](int g) {
         int r = (NB * g + sh.Wo - 2) / sh.Wo + 1;
         return r > NB * g ? NB * g : r;
     };
-    auto strip_of = [&](int g) {
+    auto strip_of = [&](int g) -> long long {   // (64 bits: the stride has no upper bound)
         const int r = rows_of(g);
         if (r > SH_RMAX) return 0;
         const int over = sh.Wf > sh.s ? sh.Wf - sh.s : 0;
-        return (NB * g * sh.s + r * over) * sh.Hf + 1;
+        return ((long long)NB * g * sh.s + (long long)r * over) * sh.Hf + 1;
     };
-    const int S = strip_of(1);
-    if (S == 0) return hipErrorNotSupported;
+    const long long S = strip_of(1);
+    if (S == 0 || S > 4096) return hipErrorNotSupported;   // (the largest instance below holds 3072 floats per strip)
     // 32-bit strip offsets: the rows of one tile must lie within 2 GiB of each other
     const long long span = (implicit ? (long long)sh.Ci * sh.Hi * sh.Wi : (long long)sh.Ci * sh.Ho * sh.rowlen) * 4LL * (SH_RMAX + 1);
     if (span >= (1LL << 31)) return hipErrorNotSupported;
@@ -558,26 +564,26 @@ hipError_t launch_conv_mfma_shallow(const float *win, const float *flt, float *o
     const int wm = sh.Co <= 32 ? 1 : (sh.Co <= 64 ? 2 : 3);
     const int mgroups = (sh.Co + wm * 32 - 1) / (wm * 32);
     if (sh.Hf == 7 && sh.Wf == 7) {
-        if (wm == 1 && S <= 4 * 128) return launch_shallow_t<7, 7, 3, 1, 1, 4>(P, mgroups, st, implicit);
-        if (wm == 1 && S <= 8 * 128) return launch_shallow_t<7, 7, 3, 1, 1, 8>(P, mgroups, st, implicit);
-        if (wm == 2 && S <= 4 * 256) return launch_shallow_t<7, 7, 3, 2, 1, 4>(P, mgroups, st, implicit);
-        if (wm == 3 && S <= 3 * 384) return launch_shallow_t<7, 7, 3, 3, 1, 3>(P, mgroups, st, implicit);
+        if (wm == 1 && S <= 4 * 128) return launch_shallow_t<7, 7, 3, 1, 1, 4>(P, mgroups, st, implicit, plan);
+        if (wm == 1 && S <= 8 * 128) return launch_shallow_t<7, 7, 3, 1, 1, 8>(P, mgroups, st, implicit, plan);
+        if (wm == 2 && S <= 4 * 256) return launch_shallow_t<7, 7, 3, 2, 1, 4>(P, mgroups, st, implicit, plan);
+        if (wm == 3 && S <= 3 * 384) return launch_shallow_t<7, 7, 3, 3, 1, 3>(P, mgroups, st, implicit, plan);
     } else if (sh.Hf == 11 && sh.Wf == 11) {
-        if (wm == 1 && S <= 12 * 256) return launch_shallow_t<11, 11, 3, 1, 2, 12>(P, mgroups, st, implicit);
-        if (wm == 2 && S <= 6 * 512) return launch_shallow_t<11, 11, 3, 2, 2, 6>(P, mgroups, st, implicit);
-        if (wm == 3 && S <= 4 * 768) return launch_shallow_t<11, 11, 3, 3, 2, 4>(P, mgroups, st, implicit);
+        if (wm == 1 && S <= 12 * 256) return launch_shallow_t<11, 11, 3, 1, 2, 12>(P, mgroups, st, implicit, plan);
+        if (wm == 2 && S <= 6 * 512) return launch_shallow_t<11, 11, 3, 2, 2, 6>(P, mgroups, st, implicit, plan);
+        if (wm == 3 && S <= 4 * 768) return launch_shallow_t<11, 11, 3, 3, 2, 4>(P, mgroups, st, implicit, plan);
     } else if (sh.Hf == 3 && sh.Wf == 3) {
         // K = 27 is 14 MFMA steps: tiles of four pixel groups where the layer has enough of them
-        const int S4 = strip_of(4);
+        const long long S4 = strip_of(4);
         const bool many = P.npix >= 4u * NB * 4u * 768u;
         if (many && S4 > 0) {
-            if (wm == 1 && S4 <= 7 * 128) return launch_shallow_t<3, 3, 3, 1, 1, 7, 4>(P, mgroups, st, implicit);
-            if (wm == 2 && S4 <= 4 * 256) return launch_shallow_t<3, 3, 3, 2, 1, 4, 4>(P, mgroups, st, implicit);
-            if (wm == 3 && S4 <= 3 * 384) return launch_shallow_t<3, 3, 3, 3, 1, 3, 4>(P, mgroups, st, implicit);
+            if (wm == 1 && S4 <= 7 * 128) return launch_shallow_t<3, 3, 3, 1, 1, 7, 4>(P, mgroups, st, implicit, plan);
+            if (wm == 2 && S4 <= 4 * 256) return launch_shallow_t<3, 3, 3, 2, 1, 4, 4>(P, mgroups, st, implicit, plan);
+            if (wm == 3 && S4 <= 3 * 384) return launch_shallow_t<3, 3, 3, 3, 1, 3, 4>(P, mgroups, st, implicit, plan);
         }
-        if (wm == 1 && S <= 2 * 128) return launch_shallow_t<3, 3, 3, 1, 1, 2>(P, mgroups, st, implicit);
-        if (wm == 2 && S <= 1 * 256) return launch_shallow_t<3, 3, 3, 2, 1, 1>(P, mgroups, st, implicit);
-        if (wm == 3 && S <= 1 * 384) return launch_shallow_t<3, 3, 3, 3, 1, 1>(P, mgroups, st, implicit);
+        if (wm == 1 && S <= 2 * 128) return launch_shallow_t<3, 3, 3, 1, 1, 2>(P, mgroups, st, implicit, plan);
+        if (wm == 2 && S <= 1 * 256) return launch_shallow_t<3, 3, 3, 2, 1, 1>(P, mgroups, st, implicit, plan);
+        if (wm == 3 && S <= 1 * 384) return launch_shallow_t<3, 3, 3, 3, 1, 1>(P, mgroups, st, implicit, plan);
     }
     return hipErrorNotSupported;
 }

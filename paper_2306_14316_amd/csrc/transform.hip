@@ -186,13 +186,16 @@ static int lds_pitch(int Wp, int Hf)
 // Output rows per workgroup for the LDS variant: as many as keep the strip within budget.
 static int lds_rows_per_block(const Shape &sh, int LW, size_t budget_bytes)
 {
+    auto bytes = [&](int mr) {   // (64 bits: the stride has no upper bound)
+        return ((unsigned long long)(mr - 1) * (unsigned long long)sh.s + (unsigned long long)sh.Hf) * (unsigned long long)LW * 4ull;
+    };
     int mr = 16;
-    while (mr > 1 && (size_t)((mr - 1) * sh.s + sh.Hf) * LW * 4u > budget_bytes) mr >>= 1;
-    if ((size_t)((mr - 1) * sh.s + sh.Hf) * LW * 4u > budget_bytes) return 0;
+    while (mr > 1 && bytes(mr) > budget_bytes) mr >>= 1;
+    if (bytes(mr) > budget_bytes) return 0;
     return mr;
 }
 
-hipError_t launch_transform(const float *in, float *win, const Shape &sh, hipStream_t st)
+hipError_t launch_transform(const float *in, float *win, const Shape &sh, hipStream_t st, LaunchPlan *plan)
 {
     // Which kernel (measured on the layers of Table 2 and on sweeps of 3x3 shapes): tall windows
     // over wide rows take the LDS-staged kernel; so do short windows (3x3) once the tensors are
@@ -220,6 +223,7 @@ hipError_t launch_transform(const float *in, float *win, const Shape &sh, hipStr
             Q.d_rowlen = make_fastdiv(Q.rowlen);
             Q.d_hf = make_fastdiv((uint32_t)sh.Hf);
             const size_t lds = (size_t)((MR - 1) * sh.s + sh.Hf) * LW * 4u;
+            if (plan) { plan_record(plan, dim3((uint32_t)blocks), 256, lds, "transform_lds_kernel"); return hipSuccess; }
             hipLaunchKernelGGL(transform_lds_kernel, dim3((uint32_t)blocks), dim3(256), lds, st, Q);
             return hipGetLastError();
         }
@@ -241,9 +245,11 @@ hipError_t launch_transform(const float *in, float *win, const Shape &sh, hipStr
     if (vec4) {
         uint32_t chunks = (P.total + 3u) / 4u;
         uint32_t blocks = (chunks + 255u) / 256u;
+        if (plan) { plan_record(plan, dim3(blocks), 256, 0, "transform_kernel<4>"); return hipSuccess; }
         hipLaunchKernelGGL(transform_kernel<4>, dim3(blocks), dim3(256), 0, st, P);
     } else {
         uint32_t blocks = (P.total + 255u) / 256u;
+        if (plan) { plan_record(plan, dim3(blocks), 256, 0, "transform_kernel<1>"); return hipSuccess; }
         hipLaunchKernelGGL(transform_kernel<1>, dim3(blocks), dim3(256), 0, st, P);
     }
     return hipGetLastError();

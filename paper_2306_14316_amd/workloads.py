@@ -35,22 +35,6 @@ class Layer:
     filter_dist: str  # "uniform_pm1" | "he_normal"
 
     @property
-    def Ho(self) -> int:
-        return (self.Hi + 2 * self.pad - self.Hf) // self.stride + 1
-
-    @property
-    def Wo(self) -> int:
-        return (self.Wi + 2 * self.pad - self.Wf) // self.stride + 1
-
-    @property
-    def Wp(self) -> int:
-        return self.Wi + 2 * self.pad
-
-    @property
-    def flops(self) -> int:
-        return 2 * self.N * self.Co * self.Ho * self.Wo * self.Ci * self.Hf * self.Wf
-
-    @property
     def dims(self):
         """Arguments in the order the C ABI takes them."""
         return (self.N, self.Ci, self.Hi, self.Wi, self.Co, self.Hf, self.Wf, self.stride, self.pad)

@@ -92,11 +92,12 @@ def test_baselines_on_headline_layer_small_batch():
     N, Ci, Hi, Wi, Co, Hf, Wf, s, p = L.dims
     O_ref, B_ref = oracle.conv2d_direct(I.numpy(), F.numpy(), s, p)
     dI, dF = I.cuda(), F.cuda()
-    dO = torch.full((N, Co, L.Ho, L.Wo), POISON, dtype=torch.float32, device="cuda")
+    Ho, Wo = oracle.out_shape(Hi, Wi, Hf, Wf, s, p)
+    dO = torch.full((N, Co, Ho, Wo), POISON, dtype=torch.float32, device="cuda")
     im2win.conv2d_direct_fwd(dI, dF, dO, *L.dims)
     torch.cuda.synchronize()
     assert_conv_close(dO.cpu().numpy(), O_ref, B_ref)
-    col = torch.full((N * L.Ho * L.Wo * Ci * Hf * Wf,), POISON, dtype=torch.float32, device="cuda")
+    col = torch.full((N * Ho * Wo * Ci * Hf * Wf,), POISON, dtype=torch.float32, device="cuda")
     dO.fill_(POISON)
     im2win.im2col_transform(dI, col, N, Ci, Hi, Wi, Hf, Wf, s, p)
     im2win.conv2d_im2col_fwd(col, dF, dO, *L.dims)

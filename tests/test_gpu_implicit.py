@@ -66,7 +66,7 @@ def test_implicit_matches_two_call_path_bitwise():
     I, F = workloads.make_inputs(L)
     N, Ci, Hi, Wi, Co, Hf, Wf, s, p = L.dims
     dO = _run(I, F, s, p)
-    dW = torch.empty((N, Ci, L.Ho, L.Wp * Hf), dtype=torch.float32, device="cuda")
+    dW = torch.empty(oracle.im2win_elems(N, Ci, Hi, Wi, Hf, Wf, s, p), dtype=torch.float32, device="cuda")
     dO2 = torch.full_like(dO, POISON)
     im2win.im2win_transform(I.cuda(), dW, N, Ci, Hi, Wi, Hf, Wf, s, p)
     im2win.conv2d_im2win_fwd(dW, F.cuda(), dO2, *L.dims)
@@ -111,6 +111,9 @@ OTHER_SHAPES = [
     (1, 3, 36, 280, 100, 3, 3, 1, 1),
     (4, 3, 3, 70, 8, 3, 3, 1, 1),      # short images: a tile spans three images
     (1, 4, 70, 6, 8, 9, 1, 1, 2),      # 9x1, padded
+    # layers no tiled kernel takes: the direct one-thread-per-output kernel computes them
+    (3, 8, 3, 3, 5, 3, 3, 1 << 26, 0),   # a stride far beyond the image
+    (1, 2, 30, 28, 6, 25, 25, 1, 0),     # a 25x25 window
 ]
 
 

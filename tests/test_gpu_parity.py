@@ -52,6 +52,11 @@ EDGE_SHAPES = [
     (2, 3, 50, 290, 64, 11, 11, 4, 0),
     (1, 3, 30, 200, 16, 3, 3, 1, 1),   # 3x3 on three channels
     (1, 3, 36, 280, 100, 3, 3, 1, 1),  # Co = 100: two filter groups in the grid
+    # layers no tiled kernel takes: computed by the one-thread-per-output kernels
+    (3, 8, 3, 3, 5, 3, 3, 1 << 26, 0),   # a stride far beyond the image (one output per image)
+    (2, 8, 5, 3, 5, 3, 3, 2, 0),         # ... and an ordinary one on the same tiny image
+    (1, 2, 30, 28, 6, 25, 25, 1, 0),     # a 25x25 window: too large for an LDS filter tile
+    (1, 1, 26, 40, 3, 26, 23, 2, 1),
 ]
 
 

@@ -29,12 +29,18 @@ def test_header_symbols_are_exported(lib):
     assert declared == set(binding.EXPORTS)
     for name in declared:
         assert getattr(lib, name) is not None
+    probes = open(os.path.join(ROOT, "include", "im2win_probe.h")).read()
+    probes = re.sub(r"/\*.*?\*/", "", probes, flags=re.S)
+    declared = set(re.findall(r"\b(im2win_\w+)\s*\(", probes))
+    assert declared == set(binding.PROBE_EXPORTS)
+    for name in declared:
+        assert getattr(lib, name) is not None
 
 
 def test_shapes_and_footprints_match_oracle(lib, golden_dir):
     for L in workloads.LAYERS:
         assert im2win.im2win_out_shape(L.Hi, L.Wi, L.Hf, L.Wf, L.stride, L.pad) == \
-            oracle.out_shape(L.Hi, L.Wi, L.Hf, L.Wf, L.stride, L.pad) == (L.Ho, L.Wo)
+            oracle.out_shape(L.Hi, L.Wi, L.Hf, L.Wf, L.stride, L.pad)
         a = (L.N, L.Ci, L.Hi, L.Wi, L.Hf, L.Wf, L.stride, L.pad)
         assert im2win.im2win_workspace_bytes(*a) == 4 * oracle.im2win_elems(*a)
         assert im2win.im2col_footprint_bytes(*a) == 4 * oracle.im2col_elems(*a)
@@ -115,3 +121,47 @@ def test_binding_rejects_host_tensors(lib):
     w = torch.zeros(1, 1, 3, 8)
     with pytest.raises(TypeError):
         im2win.im2win_transform(x, w, 1, 1, 4, 4, 2, 2, 1, 0)
+
+
+def test_launch_info_names_the_dispatch(lib):
+    """The planning calls run the library's own dispatch and launch nothing (no GPU needed: the
+    grid is then planned for 256 compute units)."""
+    want = {1: "conv_mfma_kernel<9>", 2: "conv_mfma_fast_kernel<3, 3, 8,", 3: "conv_mfma_fast_kernel<3, 3, 8,",
+            4: "conv_mfma_shallow_kernel<7, 7, 3,", 5: "conv_mfma_shallow_kernel<11, 11, 3,"}
+    for idx, prefix in want.items():
+        L = workloads.layer(idx)
+        info = im2win.conv2d_im2win_fwd_launch_info(*L.dims)
+        assert info["kernel"].startswith(prefix), info
+        assert info["grid"][0] >= 1 and info["block"] in (256, 512, 768)
+        t = im2win.im2win_transform_launch_info(L.N, L.Ci, L.Hi, L.Wi, L.Hf, L.Wf, L.stride, L.pad)
+        assert t["kernel"] == ("transform_lds_kernel" if idx >= 4 else "transform_kernel<4>")
+    L = workloads.layer(2)
+    assert im2win.conv2d_im2win_fwd_launch_info(*L.dims, variant=im2win.VARIANT_NO_MFMA)["kernel"] == "conv_basic_kernel"
+    assert im2win.conv2d_im2win_fwd_launch_info(*L.dims, variant=im2win.VARIANT_NO_PIPELINE)["kernel"] == "conv_mfma_kernel<9>"
+    assert ", true, " in im2win.conv2d_im2win_fwd_launch_info(*L.dims, workspace_free=True)["kernel"]
+    # layers that no tiled kernel takes go to the one-thread-per-output kernels instead of failing
+    assert im2win.conv2d_im2win_fwd_launch_info(1, 2, 30, 28, 6, 25, 25, 1, 0)["kernel"] == "conv_basic_kernel"
+    assert im2win.conv2d_im2win_fwd_launch_info(1, 2, 30, 28, 6, 25, 25, 1, 0, workspace_free=True)["kernel"] == "conv_direct_kernel"
+    # a stride far beyond the image, one output per image: the strips of a tile are 64 windows
+    info = im2win.conv2d_im2win_fwd_launch_info(3, 8, 3, 3, 5, 3, 3, 1 << 26, 0)
+    assert info["kernel"] == "conv_mfma_kernel<9>" and info["lds_bytes"] <= 160 * 1024
+    # ... and with two outputs per row the window step no longer fits the tiled kernels' indices
+    assert im2win.conv2d_im2win_fwd_launch_info(1, 1, 1, (1 << 28) + 1, 1, 1, 1, 1 << 28, 0)["kernel"] == "conv_basic_kernel"
+    # errors as for the calls they describe
+    info = binding.LaunchInfo()
+    assert lib.conv2d_im2win_fwd_launch_info(1, 1, 4, 4, 1, 5, 5, 1, 0, 0, 0, ctypes.byref(info)) == -2
+    assert lib.conv2d_im2win_fwd_launch_info(1, 1, 4, 4, 1, 2, 2, 1, 0, 9, 0, ctypes.byref(info)) == -4
+    assert lib.conv2d_im2win_fwd_launch_info(1, 1, 4, 4, 1, 2, 2, 1, 0, 1, 1, ctypes.byref(info)) == -4
+    assert lib.conv2d_im2win_fwd_launch_info(1, 1, 4, 4, 1, 2, 2, 1, 0, 0, 0, None) == -1
+    assert lib.im2win_transform_launch_info(1, 1, 4, 4, 2, 2, 1, 0, None) == -1
+
+
+def test_probe_arguments_are_validated(lib):
+    one = ctypes.c_void_p(16)
+    fl = ctypes.c_double()
+    assert lib.im2win_probe_mfma_f32(None, 64, ctypes.byref(fl), None) == -1
+    assert lib.im2win_probe_mfma_f32(one, 2, ctypes.byref(fl), None) == -2
+    assert lib.im2win_probe_stream(3, one, one, 1024, None) == -4
+    assert lib.im2win_probe_stream(0, None, one, 1024, None) == -1
+    assert lib.im2win_probe_stream(0, one, one, 1000, None) == -2
+    assert lib.im2win_probe_stream(2, None, ctypes.c_void_p(20), 1024, None) == -2
