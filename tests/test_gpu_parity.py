@@ -332,15 +332,26 @@ def test_transform_copies_bit_patterns():
         assert_bitwise_equal(dW, oracle.im2win(I.numpy(), Hf, Wf, s, p))
 
 
-# (N, Ci, Hi, Wi, Hf, s, p): tall windows over wide rows, the LDS-staged transform
+# (N, Ci, Hi, Wi, Hf, s, p): the transform kernel that assembles a workgroup's stretch of the
+# tensor in LDS (row blocks of one plane, or groups of whole small planes), and its fallbacks
 TALL_WINDOW_SHAPES = [
-    (2, 3, 37, 65, 5, 1, 0),     # odd row length: workgroup ranges start at every word offset mod 4
-    (1, 2, 50, 71, 7, 2, 3),     # Ho not a multiple of the rows per workgroup
-    (3, 1, 23, 64, 5, 6, 0),     # stride wider than the window: input rows skipped
+    (2, 3, 37, 65, 5, 1, 0),     # odd row length: workgroup stretches start at every word offset mod 4
+    (1, 2, 50, 71, 7, 2, 3),     # Ho not a multiple of the rows per workgroup; the 7/2 instance with padding
+    (3, 1, 23, 64, 5, 6, 0),     # stride wider than the window: input rows that no window uses
     (1, 2, 9, 90, 9, 1, 0),      # one output row per plane
-    (1, 1, 30, 500, 11, 4, 5),   # wide rows: few output rows fit the strip
-    (1, 1, 12, 1100, 9, 1, 1),   # a row too wide for any strip: falls back to the gather
+    (1, 1, 30, 500, 11, 4, 5),   # wide rows: one or two output rows per workgroup; the 11/4 instance
+    (1, 1, 12, 1100, 9, 1, 1),   # more than 256 sixteen-byte pieces per input row: falls back to the gather
+    (1, 1, 20, 1000, 17, 1, 0),  # an im2win row too long for LDS: falls back to the gather
     (1, 1, 5, 64, 5, 1, 0),      # a single output row, fewer words than threads
+    (5, 13, 9, 7, 3, 1, 0),      # small planes in groups: 65 planes of 147 words, a ragged last group
+    (3, 7, 6, 6, 3, 1, 1),       # ... all planes in one workgroup, padded
+    (4, 6, 5, 9, 3, 1, 2),       # ... padding wider than the reach of the filter
+    (2, 9, 11, 5, 4, 1, 0),      # rows of five words: the second piece overlaps the first; generic instance
+    (2, 5, 10, 4, 2, 2, 1),      # rows of exactly one piece
+    (1, 3, 40, 6, 1, 1, 0),      # Hf = 1: the identity copy
+    (2, 2, 33, 130, 3, 2, 1),    # 3-row windows at stride 2: generic instance, row blocks
+    (1, 2, 300, 31, 5, 1, 2),    # tall narrow planes, 5/1 instance, many row blocks
+    (1, 1, 4, 3, 2, 1, 0),       # rows shorter than one piece: the gather
 ]
 
 
@@ -359,8 +370,7 @@ def test_transform_tall_windows(shape):
     assert torch.isnan(buf[:32]).all() and torch.isnan(buf[32 + n:]).all()   # nothing written outside
 
 
-# (N, Ci, Hi, Wi, Hf, s, p): short windows on tensors large enough (input + im2win tensor of
-# 192 MiB or more, rows of 48 words or more) for the LDS-staged transform to be chosen
+# (N, Ci, Hi, Wi, Hf, s, p): short windows on large tensors (input + im2win tensor of 192 MiB or more)
 LARGE_SHORT_WINDOW_SHAPES = [
     (64, 20, 150, 131, 3, 1, 1),   # odd row length (399 words): stretches start at every word offset mod 4
     (96, 24, 150, 131, 3, 2, 2),   # stride 2, two rows and columns of padding

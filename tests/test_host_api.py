@@ -134,7 +134,13 @@ def test_launch_info_names_the_dispatch(lib):
         assert info["kernel"].startswith(prefix), info
         assert info["grid"][0] >= 1 and info["block"] in (256, 512, 768)
         t = im2win.im2win_transform_launch_info(L.N, L.Ci, L.Hi, L.Wi, L.Hf, L.Wf, L.stride, L.pad)
-        assert t["kernel"] == ("transform_lds_kernel" if idx >= 4 else "transform_kernel<4>")
+        assert t["kernel"].startswith("transform_assemble_kernel<%d, %d, " % (L.Hf, L.stride)), t
+        assert t["kernel"].endswith("true>" if idx in (1, 3) else "false>"), t   # small planes go in groups
+    assert im2win.im2win_transform_launch_info(1, 1, 12, 1100, 9, 1, 1, 1)["kernel"] == "transform_kernel<4>"
+    assert im2win.im2win_transform_launch_info(1, 1, 4, 3, 2, 2, 1, 0)["kernel"] == "transform_kernel<4>"
+    for L in workloads.TABLE2:
+        t = im2win.im2win_transform_launch_info(L.N, L.Ci, L.Hi, L.Wi, L.Hf, L.Wf, L.stride, L.pad)
+        assert t["kernel"].startswith("transform_assemble_kernel<") and t["lds_bytes"] <= 24 * 1024 + 32, t
     L = workloads.layer(2)
     assert im2win.conv2d_im2win_fwd_launch_info(*L.dims, variant=im2win.VARIANT_NO_MFMA)["kernel"] == "conv_basic_kernel"
     assert im2win.conv2d_im2win_fwd_launch_info(*L.dims, variant=im2win.VARIANT_NO_PIPELINE)["kernel"] == "conv_mfma_kernel<9>"
