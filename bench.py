@@ -203,7 +203,10 @@ def time_variants(L, steps):
     dO = torch.empty(sz["output_elems"], dtype=torch.float32, device="cuda")
     im2win.im2win_transform(dI, dW, N, Ci, Hi, Wi, Hf, Wf, s, p)
     names = {0: "default", 3: "narrow_loads (8-byte instead of 16-byte filter fetches)",
-             1: "no_pipeline (one LDS stage, no prefetch)", 2: "no_mfma (one thread per output)"}
+             5: "scalar_loads (4-byte filter fetches)",
+             1: "no_pipeline (one LDS stage, no prefetch; matrix cores)",
+             4: "valu_microkernel (no_pipeline's tiling with a 4x4 register tile per thread on the vector ALUs)",
+             2: "no_mfma (Algorithm 2: one thread per output, no LDS, no register tile)"}
     out = {}
     _ramp(lambda: im2win.conv2d_im2win_fwd(dW, dF, dO, N, Ci, Hi, Wi, Co, Hf, Wf, s, p))
     for v, name in names.items():

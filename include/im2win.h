@@ -109,20 +109,32 @@ im2win_status conv2d_im2win_fwd_basic(const float *window_dev, const float *filt
  *   IM2WIN_VARIANT_DEFAULT           the kernel conv2d_im2win_fwd would pick;
  *   IM2WIN_VARIANT_NO_PIPELINE       no double buffer / prefetch: one LDS stage,
  *                                    staging outside the MFMA chain (any layer);
- *   IM2WIN_VARIANT_NO_MFMA           no matrix cores, no register tile: one thread
- *                                    per output (Algorithm 2);
- *   IM2WIN_VARIANT_NARROW_LOADS      the default kernel with the filter rows fetched in
- *                                    8-byte instead of 16-byte pieces (the vector loads
- *                                    of Section 3.3 at half width); only the pipelined 3x3
- *                                    kernel has such an instance, other layers run the
- *                                    default kernel.
+ *   IM2WIN_VARIANT_VALU_MICROKERNEL  no matrix cores: the tiling, LDS strips and
+ *                                    filter tile of NO_PIPELINE, but every thread
+ *                                    keeps a 4x4 register tile of outputs and advances
+ *                                    it with scalar fused multiply-adds (the M_T x N_T
+ *                                    micro-kernel of Section 3.3 on the vector ALUs);
+ *                                    compare with NO_PIPELINE, which differs from it in
+ *                                    the arithmetic unit only;
+ *   IM2WIN_VARIANT_NARROW_LOADS,     the default kernel with the filter rows fetched in
+ *   IM2WIN_VARIANT_SCALAR_LOADS      8-byte / 4-byte instead of 16-byte pieces (the vector
+ *                                    loads of Section 3.3 at half and quarter width; the
+ *                                    strips are staged in 4-byte words in every variant,
+ *                                    their runs being 4-byte aligned only); the pipelined
+ *                                    3x3 kernel alone has such instances, other layers
+ *                                    run the default kernel;
+ *   IM2WIN_VARIANT_NO_MFMA           none of the above at once -- no LDS, no register
+ *                                    tile, no matrix cores: one thread per output
+ *                                    (Algorithm 2, conv2d_im2win_fwd_basic).
  */
 enum {
     IM2WIN_VARIANT_DEFAULT = 0,
     IM2WIN_VARIANT_NO_PIPELINE = 1,
     IM2WIN_VARIANT_NO_MFMA = 2,
     IM2WIN_VARIANT_NARROW_LOADS = 3,
-    IM2WIN_VARIANT_LAST = IM2WIN_VARIANT_NARROW_LOADS
+    IM2WIN_VARIANT_VALU_MICROKERNEL = 4,
+    IM2WIN_VARIANT_SCALAR_LOADS = 5,
+    IM2WIN_VARIANT_LAST = IM2WIN_VARIANT_SCALAR_LOADS
 };
 im2win_status conv2d_im2win_fwd_variant(const float *window_dev, const float *filter_dev,
                                         float *output_dev,

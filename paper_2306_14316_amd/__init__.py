@@ -17,6 +17,8 @@ from .binding import (  # noqa: F401
     VARIANT_NO_PIPELINE,
     VARIANT_NO_MFMA,
     VARIANT_NARROW_LOADS,
+    VARIANT_SCALAR_LOADS,
+    VARIANT_VALU_MICROKERNEL,
     PROBE_COPY,
     PROBE_NONTEMPORAL,
     PROBE_READ,

@@ -181,6 +181,7 @@ def conv2d_im2win_fwd_basic(window, filter, output, N, Ci, Hi, Wi, Co, Hf, Wf, s
 
 
 VARIANT_DEFAULT, VARIANT_NO_PIPELINE, VARIANT_NO_MFMA, VARIANT_NARROW_LOADS = 0, 1, 2, 3
+VARIANT_VALU_MICROKERNEL, VARIANT_SCALAR_LOADS = 4, 5
 
 
 def conv2d_im2win_fwd_variant(window, filter, output, N, Ci, Hi, Wi, Co, Hf, Wf, stride, pad, variant,

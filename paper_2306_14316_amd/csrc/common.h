@@ -91,7 +91,8 @@ hipError_t launch_conv_implicit(const float *in, const float *flt, float *out, c
                                 hipStream_t st, LaunchPlan *plan = nullptr);
 // Kernel selection for the MFMA convolution (the values of the public
 // IM2WIN_VARIANT_* constants).
-enum ConvVariant { kVariantDefault = 0, kVariantNoPipeline = 1, kVariantNoMfma = 2, kVariantNarrowLoads = 3 };
+enum ConvVariant { kVariantDefault = 0, kVariantNoPipeline = 1, kVariantNoMfma = 2, kVariantNarrowLoads = 3,
+                   kVariantValuMicrokernel = 4, kVariantScalarLoads = 5 };
 // Returns hipErrorInvalidConfiguration when no tile configuration fits in LDS.
 hipError_t launch_conv_mfma(const float *win, const float *flt, float *out, const Shape &sh,
                             hipStream_t st, int variant = kVariantDefault, LaunchPlan *plan = nullptr);

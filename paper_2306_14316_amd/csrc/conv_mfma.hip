@@ -32,7 +32,12 @@ namespace im2win {
 
 constexpr int PITCH = 65;    // LDS floats per filter-tile row [k][0..63], +1 against bank conflicts
 
-template <int KHW_T>
+// VALU_MK: the ablation variant "no matrix cores" (Section 4.4 takes out one optimisation at a
+// time).  Tiling, staging and LDS layouts are the same; only the arithmetic differs: in place of
+// the wave-level MFMA every thread keeps an M_T x N_T = 4 x 4 register tile of outputs and
+// advances it with scalar v_fma_f32 outer products, the micro-kernel of Section 3.3 on the
+// vector ALUs.
+template <int KHW_T, bool VALU_MK = false>
 __global__ __launch_bounds__(256) void conv_mfma_kernel(MfmaParams P)
 {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -113,6 +118,25 @@ __global__ __launch_bounds__(256) void conv_mfma_kernel(MfmaParams P)
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
 
+    // register-tile variant: thread (tid / 16, tid % 16) owns output channels 4*(tid/16) .. +3 and
+    // pixels 4*(tid%16) .. +3 of the tile; bb[j]: LDS strip position of pixel j's window
+    constexpr int MT = 4, NT = 4;
+    const int mt0 = (tid >> 4) * MT, nt0 = (tid & 15) * NT;
+    int bb[NT];
+    float racc[MT][NT];
+    if (VALU_MK) {
+#pragma unroll
+        for (int j = 0; j < NT; ++j) {
+            const uint32_t Pl = min(P0 + (uint32_t)(nt0 + j), Pend);
+            const uint32_t ql = fdiv(Pl, P.d_wo);
+            const int nl = (int)(Pl - ql * (uint32_t)P.Wo);
+            const int rho = (int)(ql - q0);
+            bb[j] = rho == 0 ? (nl - nlo0) * sHf : len0 + (rho - 1) * P.fullseg + nl * sHf;
+#pragma unroll
+            for (int i = 0; i < MT; ++i) racc[i][j] = 0.0f;
+        }
+    }
+
     for (int c0 = 0; c0 < P.Ci; c0 += P.cb) {
         const int nch = min(P.cb, P.Ci - c0);
         __syncthreads();   // tables ready (first pass) / previous block's reads done
@@ -153,6 +177,27 @@ __global__ __launch_bounds__(256) void conv_mfma_kernel(MfmaParams P)
         if ((nch & 1) && (khw & 1) && tid < MB) sF[ne * PITCH + tid] = 0.0f;   // zero K slice of a split step
         __syncthreads();
 
+        if (VALU_MK) {
+            // ---- register-tile micro-kernel: one 4 x 4 outer product per K element ----
+            for (int c = 0; c < nch; ++c) {
+                const float *ar = sF + (size_t)(c * khw) * PITCH + mt0;
+                const float *br = sI + c * S;
+#pragma unroll 3
+                for (int t = 0; t < khw; ++t) {
+                    float a[MT], b[NT];
+#pragma unroll
+                    for (int i = 0; i < MT; ++i) a[i] = ar[t * PITCH + i];
+#pragma unroll
+                    for (int j = 0; j < NT; ++j) b[j] = br[bb[j] + t];
+#pragma unroll
+                    for (int i = 0; i < MT; ++i)
+#pragma unroll
+                        for (int j = 0; j < NT; ++j) racc[i][j] = fmaf(a[i], b[j], racc[i][j]);
+                }
+            }
+            continue;
+        }
+
         // ---- pair steps: lanes 0-31 take channel 2j, lanes 32-63 channel 2j+1 ----
         const int npairs = nch >> 1;
         for (int pr = 0; pr < npairs; ++pr) {
@@ -182,6 +227,19 @@ __global__ __launch_bounds__(256) void conv_mfma_kernel(MfmaParams P)
         }
     }
 
+    if (VALU_MK) {
+#pragma unroll
+        for (int j = 0; j < NT; ++j) {
+            const uint32_t Pm = P0 + (uint32_t)(nt0 + j);
+            if (Pm > Pend) continue;
+            const uint32_t img = fdiv(Pm, P.d_howo);
+            float *o = P.out + (size_t)img * P.Co * P.howo + (Pm - img * P.howo);
+#pragma unroll
+            for (int i = 0; i < MT; ++i)
+                if (m0 + mt0 + i < P.Co) o[(size_t)(m0 + mt0 + i) * P.howo] = racc[i][j];
+        }
+        return;
+    }
     store_tile(P, acc, P0, Pend, m0, wm, wn, h, l32);
 }
 
@@ -190,18 +248,22 @@ static size_t lds_bytes(int cb, int S, int khw)
     return 4u * ((size_t)round4(S) + round4(cb * khw) + round4(cb * S) + 4 + (size_t)(cb * khw + 1) * PITCH);
 }
 
-template <int KHW_T>
+template <int KHW_T, bool VALU_MK = false>
 static hipError_t launch_t(const MfmaParams &P, size_t lds, uint32_t blocks, hipStream_t st, LaunchPlan *plan)
 {
-    if (plan) { plan_record(plan, dim3(blocks), 256, lds, "conv_mfma_kernel<%d>", KHW_T); return hipSuccess; }
+    if (plan) {
+        if (VALU_MK) plan_record(plan, dim3(blocks), 256, lds, "conv_mfma_kernel<%d, true>", KHW_T);
+        else plan_record(plan, dim3(blocks), 256, lds, "conv_mfma_kernel<%d, false>", KHW_T);
+        return hipSuccess;
+    }
     if (lds > 48 * 1024) {
         static KernelCache kc;
         int dev = 0;
         hipError_t e = hipGetDevice(&dev);
-        if (e == hipSuccess) e = allow_dynamic_lds(kc, reinterpret_cast<const void *>(&conv_mfma_kernel<KHW_T>), lds, dev);
+        if (e == hipSuccess) e = allow_dynamic_lds(kc, reinterpret_cast<const void *>(&conv_mfma_kernel<KHW_T, VALU_MK>), lds, dev);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(conv_mfma_kernel<KHW_T>, dim3(blocks), dim3(256), lds, st, P);
+    hipLaunchKernelGGL((conv_mfma_kernel<KHW_T, VALU_MK>), dim3(blocks), dim3(256), lds, st, P);
     return hipGetLastError();
 }
 
@@ -251,7 +313,8 @@ static bool fill_params(MfmaParams &P, const float *win, const float *flt, float
 }
 
 // The generic kernel: picks the channels per K block that fit in LDS and launches.
-static hipError_t launch_generic(MfmaParams &P, const Shape &sh, uint32_t blocks, hipStream_t st, LaunchPlan *plan)
+static hipError_t launch_generic(MfmaParams &P, const Shape &sh, uint32_t blocks, hipStream_t st, LaunchPlan *plan,
+                                 bool valu_microkernel = false)
 {
     const size_t lds_max = 160 * 1024;
     int cb = sh.Ci < 8 ? sh.Ci : 8;
@@ -262,6 +325,7 @@ static hipError_t launch_generic(MfmaParams &P, const Shape &sh, uint32_t blocks
     P.vec4 = (sh.Ci % cb == 0) && ((cb * sh.khw) % 4 == 0) && (sh.K % 4 == 0) &&
              ((reinterpret_cast<uintptr_t>(P.flt) & 15u) == 0);
     P.d_cpr = make_fastdiv((uint32_t)((cb * sh.khw) / 4 > 0 ? (cb * sh.khw) / 4 : 1));
+    if (valu_microkernel) return sh.khw == 9 ? launch_t<9, true>(P, lds, blocks, st, plan) : launch_t<0, true>(P, lds, blocks, st, plan);
     switch (sh.khw) {
         case 9:   return launch_t<9>(P, lds, blocks, st, plan);
         case 49:  return launch_t<49>(P, lds, blocks, st, plan);
@@ -283,7 +347,7 @@ hipError_t launch_conv_implicit(const float *in, const float *flt, float *out, c
     const uint32_t blocks = ((P.npix + NB - 1) / NB) * (uint32_t)P.tiles_m;
     hipError_t fe = launch_conv_mfma_shallow(in, flt, out, sh, st, true, plan);
     if (fe != hipErrorNotSupported) return fe;
-    fe = launch_conv_mfma_fast(P, sh, blocks, st, true, false, plan);
+    fe = launch_conv_mfma_fast(P, sh, blocks, st, true, 4, plan);
     if (fe != hipErrorNotSupported) return fe;
     fe = launch_generic(P, sh, blocks, st, plan);
     if (fe == hipErrorInvalidConfiguration) return launch_conv_direct(in, flt, out, sh, st, plan);
@@ -299,14 +363,15 @@ hipError_t launch_conv_mfma(const float *win, const float *flt, float *out, cons
 
     const uint32_t tiles_n = (P.npix + NB - 1) / NB;
     const uint32_t blocks = tiles_n * (uint32_t)P.tiles_m;
-    if (variant == kVariantDefault || variant == kVariantNarrowLoads) {
+    if (variant == kVariantDefault || variant == kVariantNarrowLoads || variant == kVariantScalarLoads) {
         hipError_t fe = launch_conv_mfma_shallow(win, flt, out, sh, st, false, plan);
         if (fe != hipErrorNotSupported) return fe;
-        fe = launch_conv_mfma_fast(P, sh, blocks, st, false, variant == kVariantNarrowLoads, plan);
+        fe = launch_conv_mfma_fast(P, sh, blocks, st, false,
+                                   variant == kVariantNarrowLoads ? 2 : (variant == kVariantScalarLoads ? 1 : 4), plan);
         if (fe != hipErrorNotSupported) return fe;
     }
     // (a window too large for the generic kernel's LDS filter tile: the basic kernel computes it)
-    const hipError_t ge = launch_generic(P, sh, blocks, st, plan);
+    const hipError_t ge = launch_generic(P, sh, blocks, st, plan, variant == kVariantValuMicrokernel);
     if (ge == hipErrorInvalidConfiguration) return launch_conv_basic(win, flt, out, sh, st, plan);
     return ge;
 }

@@ -184,7 +184,8 @@ __device__ __forceinline__ void tail_piece(const MfmaParams &P, uint32_t lt, int
     }
 }
 
-// CW: floats per filter staging chunk (4: 16-byte loads, 2: 8-byte loads).
+// CW: floats per filter staging chunk (4: 16-byte loads; 2 and 1: the 8- and 4-byte loads of the
+// load-width ablation).
 // OCC: workgroups per CU the register allocation should leave room for.
 // IMP: workspace-free variant.  P.win is the NCHW input; the tile's im2win strips
 // (Section 3.1) are built directly in LDS -- same LDS layout, same MFMA loop -- by
@@ -213,7 +214,7 @@ __global__ __launch_bounds__(256, OCC) void conv_mfma_fast_kernel(MfmaParams P)
     constexpr int STAGE = SF_FLOATS + CB * SS;   // floats per LDS stage
     constexpr int R = HALF ? pick_ring_half((CB / 2) * KHW) : pick_ring((CB / 2) * KHW);
     static_assert(R > 0, "no ring length divides the MFMAs per block");
-    static_assert(CW == 4 || CW == 2, "chunks are 16 or 8 bytes");
+    static_assert(CW == 4 || CW == 2 || CW == 1, "chunks are 16, 8 or 4 bytes");
     static_assert(KB % CW == 0, "K block must be a whole number of chunks");
     static_assert(CB % 2 == 0, "pair steps need an even channel count");
 
@@ -429,18 +430,21 @@ __global__ __launch_bounds__(256, OCC) void conv_mfma_fast_kernel(MfmaParams P)
     float fr[JF][CW];
 
     auto load_f = [&](int kb, int j, const __amdgpu_buffer_rsrc_t &rf) __attribute__((always_inline)) {
-        if (CW == 4) {
+        if constexpr (CW == 4) {
             const float4v w = __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(rf, goffb[j], kb * (KB * 4), 0));
             fr[j][0] = w.x; fr[j][1] = w.y; fr[j][CW - 2] = w.z; fr[j][CW - 1] = w.w;
-        } else {
+        } else if constexpr (CW == 2) {
             const float2v w = __builtin_bit_cast(float2v, __builtin_amdgcn_raw_buffer_load_b64(rf, goffb[j], kb * (KB * 4), 0));
             fr[j][0] = w.x; fr[j][1] = w.y;
+        } else {
+            fr[j][0] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rf, goffb[j], kb * (KB * 4), 0));
         }
     };
-    auto store_f = [&](int st, int j, int half) __attribute__((always_inline)) {   // words 2*half, 2*half+1 of chunk j
-        lds_float *d = (lds_float *)lds + st * STAGE + loff[j] + 2 * half;
-        d[0] = fr[j][2 * half];
-        d[1] = fr[j][2 * half + 1];
+    constexpr int WPS = CW >= 2 ? 2 : 1;   // words per filter store slot
+    auto store_f = [&](int st, int j, int half) __attribute__((always_inline)) {   // words WPS*half .. of chunk j
+        lds_float *d = (lds_float *)lds + st * STAGE + loff[j] + WPS * half;
+        d[0] = fr[j][WPS * half];
+        if constexpr (WPS == 2) d[1] = fr[j][WPS * half + 1];
     };
     auto store_i = [&](int st, int set, int c, int j, const int (&loffI)[JX], uint32_t zero) __attribute__((always_inline)) {
         if (IMP)
@@ -462,7 +466,7 @@ __global__ __launch_bounds__(256, OCC) void conv_mfma_fast_kernel(MfmaParams P)
     constexpr int NG = CB / 2;            // channel pairs per block
     constexpr int NM = NG * KHW;          // MFMAs per block
     constexpr int NSLOT = NM - R;         // MFMAs before the barrier
-    constexpr int HPC = CW / 2;           // two-word stores per filter chunk
+    constexpr int HPC = CW >= 2 ? CW / 2 : 1;   // store slots per filter chunk (two words each; one for 4-byte chunks)
     constexpr int NFW = HPC * JF;         // filter store slots
     constexpr int NIW = CB * JX;          // strip stores / loads
     constexpr int NIWS = (NIW + 1) / 2;   // slots that store strip words (two each)
@@ -738,9 +742,10 @@ static hipError_t launch_fast_i(const MfmaParams &P, uint32_t blocks, hipStream_
 
 // Returns hipErrorNotSupported when the layer does not meet the fast path's conditions.
 // implicit: P.win is the NCHW input (P.Hi, P.Wi, P.p, P.in_plane set; P.win_elems = its size).
-// narrow: the ablation instance that fetches the filter in 8-byte pieces, where there is one.
+// filter_fetch_floats: 4, or 2 / 1 for the load-width ablation instances (8- and 4-byte filter
+// fetches), which exist for 3x3 layers only; other layers then run their default instance.
 hipError_t launch_conv_mfma_fast(MfmaParams P, const Shape &sh, uint32_t blocks, hipStream_t st, bool implicit,
-                                 bool narrow, LaunchPlan *plan)
+                                 int filter_fetch_floats, LaunchPlan *plan)
 {
     const uintptr_t fa = reinterpret_cast<uintptr_t>(P.flt);
     const bool al16 = (fa & 15u) == 0 && (sh.K % 4 == 0);   // filter rows readable as aligned float4
@@ -757,9 +762,13 @@ hipError_t launch_conv_mfma_fast(MfmaParams P, const Shape &sh, uint32_t blocks,
     // output words: 32-bit byte offsets from (image of the tile's first pixel, first channel of the wave)
     if (((unsigned long long)sh.Co * (unsigned long long)P.rmax + 64ull) * (unsigned long long)sh.Ho * sh.Wo * 4ull >= (1ull << 32))
         return hipErrorNotSupported;
-    if (narrow && !implicit && sh.Hf == 3 && sh.Wf == 3 && sh.Ci % 8 == 0 && al16) {   // ablation: 8-byte filter chunks
+    if (filter_fetch_floats == 2 && !implicit && sh.Hf == 3 && sh.Wf == 3 && sh.Ci % 8 == 0 && al16) {   // ablation: 8-byte filter chunks
         if (P.S <= 256) return launch_fast_t<3, 3, 8, 1, 2, 3, false>(P, blocks, st, plan);
         if (P.S <= 512) return launch_fast_t<3, 3, 8, 2, 2, 3, false>(P, blocks, st, plan);
+    }
+    if (filter_fetch_floats == 1 && !implicit && sh.Hf == 3 && sh.Wf == 3 && sh.Ci % 8 == 0 && al16) {   // ablation: 4-byte filter chunks
+        if (P.S <= 256) return launch_fast_t<3, 3, 8, 1, 1, 3, false>(P, blocks, st, plan);
+        if (P.S <= 512) return launch_fast_t<3, 3, 8, 2, 1, 3, false>(P, blocks, st, plan);
     }
     if (sh.Hf == 3 && sh.Wf == 3 && sh.Ci % 8 == 0 && al16) {
         if (P.S <= 256) return launch_fast_i<3, 3, 8, 1, 4, 3>(P, blocks, st, implicit, plan);

@@ -101,7 +101,7 @@ __device__ __forceinline__ void store_tile_desc(const MfmaParams &P, const float
 }
 
 hipError_t launch_conv_mfma_fast(MfmaParams P, const Shape &sh, uint32_t blocks, hipStream_t st,
-                                 bool implicit = false, bool narrow = false, LaunchPlan *plan = nullptr);
+                                 bool implicit = false, int filter_fetch_floats = 4, LaunchPlan *plan = nullptr);
 hipError_t launch_conv_mfma_shallow(const float *win, const float *flt, float *out, const Shape &sh,
                                     hipStream_t st, bool implicit = false, LaunchPlan *plan = nullptr);
 

@@ -26,7 +26,7 @@ int main(void)
     if (im2win_out_shape(4, 4, 5, 5, 1, 0, &Ho, &Wo) != IM2WIN_ERR_SHAPE) return 4;
     if (im2win_transform(NULL, NULL, 1, 1, 4, 4, 2, 2, 1, 0, NULL) != IM2WIN_ERR_NULL) return 5;
     if (conv2d_im2win_fwd_variant((const float *)16, (const float *)16, (float *)16, 1, 1, 4, 4, 1, 2, 2, 1, 0,
-                                  IM2WIN_VARIANT_NARROW_LOADS + 1, NULL) != IM2WIN_ERR_UNSUPPORTED) return 6;
+                                  IM2WIN_VARIANT_LAST + 1, NULL) != IM2WIN_ERR_UNSUPPORTED) return 6;
     if (strlen(im2win_status_str(IM2WIN_ERR_OVERFLOW)) == 0) return 7;
     printf("c abi ok\n");
     return 0;

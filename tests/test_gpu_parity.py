@@ -293,11 +293,13 @@ VARIANT_SHAPES = [
     (2, 16, 20, 20, 40, 3, 3, 1, 1),     # ragged Co
     (1, 3, 40, 260, 64, 7, 7, 2, 3),     # a three-channel 7x7 layer
     (2, 5, 9, 9, 7, 2, 3, 2, 1),         # a small odd layer
+    (2, 16, 30, 150, 70, 3, 3, 1, 1),    # wide rows: two strip words per thread in the 3x3 instances
+    (3, 13, 12, 12, 96, 5, 5, 1, 2),     # odd channel count, 5x5
 ]
 
 
 @pytest.mark.parametrize("shape", VARIANT_SHAPES, ids=lambda s: "x".join(map(str, s)))
-@pytest.mark.parametrize("variant", [0, 1, 2, 3])
+@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4, 5])
 def test_ablation_variants(shape, variant):
     """Every ablation variant computes the same convolution."""
     N, Ci, Hi, Wi, Co, Hf, Wf, s, p = shape
@@ -316,7 +318,7 @@ def test_unknown_variant_is_rejected():
     I, F = workloads.random_layer_inputs(5, N, Ci, Hi, Wi, Co, Hf, Wf)
     dW = run_transform(I, Hf, Wf, s, p)
     dO = torch.zeros((N, Co, 4, 4), dtype=torch.float32, device="cuda")
-    for bad in (-1, 4, 99):
+    for bad in (-1, 6, 99):
         with pytest.raises(im2win.Im2winError):
             im2win.conv2d_im2win_fwd_variant(dW, F.cuda(), dO, N, Ci, Hi, Wi, Co, Hf, Wf, s, p, bad)
     assert not bool(dO.any())      # nothing was launched

@@ -93,6 +93,7 @@ def test_null_pointers_and_overflow(lib):
     assert lib.im2win_out_shape(4, 4, 2, 2, 1, 0, None, None) == -1
     assert lib.conv2d_im2win_fwd_variant(one, one, None, 1, 1, 4, 4, 1, 2, 2, 1, 0, 0, None) == -1
     assert lib.conv2d_im2win_fwd_variant(one, one, one, 1, 1, 4, 4, 1, 2, 2, 1, 0, 7, None) == -4
+    assert lib.conv2d_im2win_fwd_variant(one, one, one, 1, 1, 4, 4, 1, 2, 2, 1, 0, -1, None) == -4
     # 2^31 or more elements in the im2win tensor / the output
     assert lib.im2win_transform(one, one, 4096, 64, 224, 224, 7, 7, 2, 0, None) == -3
     assert lib.conv2d_im2win_fwd(one, one, one, 128, 3, 1024, 1024, 64, 1, 1, 1, 0, None) == -3
@@ -126,7 +127,7 @@ def test_binding_rejects_host_tensors(lib):
 def test_launch_info_names_the_dispatch(lib):
     """The planning calls run the library's own dispatch and launch nothing (no GPU needed: the
     grid is then planned for 256 compute units)."""
-    want = {1: "conv_mfma_kernel<9>", 2: "conv_mfma_fast_kernel<3, 3, 8,", 3: "conv_mfma_fast_kernel<3, 3, 8,",
+    want = {1: "conv_mfma_kernel<9, false>", 2: "conv_mfma_fast_kernel<3, 3, 8,", 3: "conv_mfma_fast_kernel<3, 3, 8,",
             4: "conv_mfma_shallow_kernel<7, 7, 3,", 5: "conv_mfma_shallow_kernel<11, 11, 3,"}
     for idx, prefix in want.items():
         L = workloads.layer(idx)
@@ -143,14 +144,18 @@ def test_launch_info_names_the_dispatch(lib):
         assert t["kernel"].startswith("transform_assemble_kernel<") and t["lds_bytes"] <= 24 * 1024 + 32, t
     L = workloads.layer(2)
     assert im2win.conv2d_im2win_fwd_launch_info(*L.dims, variant=im2win.VARIANT_NO_MFMA)["kernel"] == "conv_basic_kernel"
-    assert im2win.conv2d_im2win_fwd_launch_info(*L.dims, variant=im2win.VARIANT_NO_PIPELINE)["kernel"] == "conv_mfma_kernel<9>"
+    assert im2win.conv2d_im2win_fwd_launch_info(*L.dims, variant=im2win.VARIANT_NO_PIPELINE)["kernel"] == "conv_mfma_kernel<9, false>"
+    assert im2win.conv2d_im2win_fwd_launch_info(*L.dims, variant=im2win.VARIANT_VALU_MICROKERNEL)["kernel"] == "conv_mfma_kernel<9, true>"
+    for v, cw in ((im2win.VARIANT_DEFAULT, 4), (im2win.VARIANT_NARROW_LOADS, 2), (im2win.VARIANT_SCALAR_LOADS, 1)):
+        assert im2win.conv2d_im2win_fwd_launch_info(*L.dims, variant=v)["kernel"].startswith(
+            "conv_mfma_fast_kernel<3, 3, 8, 1, %d, 3," % cw)
     assert ", true, " in im2win.conv2d_im2win_fwd_launch_info(*L.dims, workspace_free=True)["kernel"]
     # layers that no tiled kernel takes go to the one-thread-per-output kernels instead of failing
     assert im2win.conv2d_im2win_fwd_launch_info(1, 2, 30, 28, 6, 25, 25, 1, 0)["kernel"] == "conv_basic_kernel"
     assert im2win.conv2d_im2win_fwd_launch_info(1, 2, 30, 28, 6, 25, 25, 1, 0, workspace_free=True)["kernel"] == "conv_direct_kernel"
     # a stride far beyond the image, one output per image: the strips of a tile are 64 windows
     info = im2win.conv2d_im2win_fwd_launch_info(3, 8, 3, 3, 5, 3, 3, 1 << 26, 0)
-    assert info["kernel"] == "conv_mfma_kernel<9>" and info["lds_bytes"] <= 160 * 1024
+    assert info["kernel"] == "conv_mfma_kernel<9, false>" and info["lds_bytes"] <= 160 * 1024
     # ... and with two outputs per row the window step no longer fits the tiled kernels' indices
     assert im2win.conv2d_im2win_fwd_launch_info(1, 1, 1, (1 << 28) + 1, 1, 1, 1, 1 << 28, 0)["kernel"] == "conv_basic_kernel"
     # errors as for the calls they describe
