@@ -57,6 +57,9 @@ def parse_args():
     ap.add_argument("--baselines", action="store_true",
                     help="also time the comparison baselines (direct convolution; im2col + GEMM) on the five layers "
                          "(listed under 'baselines')")
+    ap.add_argument("--extra", action="store_true",
+                    help="also time layers off the specialised kernels' grid (ragged channel counts, 1x1, "
+                         "asymmetric filters; listed under 'extra')")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (known traffic) so that a rocprofv3 --pmc "
@@ -453,6 +456,8 @@ def main():
             out["baselines_table2"] = [time_baselines(l, max(3, min(a.steps, 10))) for l in workloads.TABLE2]
     if a.table2:
         out["table2"] = [layer_report(t2, time_layer(t2, max(5, min(a.steps, 20)), 3)) for t2 in workloads.TABLE2]
+    if a.extra:
+        out["extra"] = [layer_report(x, time_layer(x, max(5, min(a.steps, 20)), 3)) for x in workloads.EXTRA]
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(L)
         if a.layers == "all":   # the oracle on every layer, whole workloads (a second or less each)

@@ -200,7 +200,11 @@ __device__ __forceinline__ void tail_piece(const MfmaParams &P, uint32_t lt, int
 // LDS before the store).  For leftovers too many for the sixteenths: a half tile is staged
 // through LDS like a whole one, at 3/4 of its traffic.
 // TAIL: a workgroup takes one sixteenth of its tile (tail_piece above).
-template <int HF, int WF, int CB, int JX, int CW, int OCC, bool IMP, bool PER, bool TAIL, bool HALF = false>
+// RAG: Ci is not a multiple of CB.  The last K block then holds Ci % CB real channels; the words
+// of the missing ones -- strip words and filter columns, whatever the loads brought in from the
+// neighbouring channel planes and filter rows -- are replaced by +0.0 when that block is written
+// to LDS, so the MFMA loop itself is unchanged.  (Whole tiles only: not combined with PER, TAIL, HALF.)
+template <int HF, int WF, int CB, int JX, int CW, int OCC, bool IMP, bool PER, bool TAIL, bool HALF = false, bool RAG = false>
 __global__ __launch_bounds__(256, OCC) void conv_mfma_fast_kernel(MfmaParams P)
 {
     constexpr int KHW = HF * WF;
@@ -217,6 +221,7 @@ __global__ __launch_bounds__(256, OCC) void conv_mfma_fast_kernel(MfmaParams P)
     static_assert(CW == 4 || CW == 2 || CW == 1, "chunks are 16, 8 or 4 bytes");
     static_assert(KB % CW == 0, "K block must be a whole number of chunks");
     static_assert(CB % 2 == 0, "pair steps need an even channel count");
+    static_assert(!RAG || (!PER && !TAIL && !HALF), "a ragged last K block comes with whole tiles only");
 
     // two LDS stages, each [filter tile MB x PF][CB strips of SS floats]
     extern __shared__ __align__(16) unsigned char smem[];
@@ -377,7 +382,8 @@ __global__ __launch_bounds__(256, OCC) void conv_mfma_fast_kernel(MfmaParams P)
     };
     // The strip words of the first tile's first two K blocks are requested here, before the
     // filter staging coordinates are worked out: they have the longest way to come.
-    const int nkb = P.Ci / CB;
+    const int nkb = RAG ? (P.Ci + CB - 1) / CB : P.Ci / CB;
+    const int last_ch = P.Ci - (nkb - 1) * CB;   // channels of the last K block (CB unless RAG)
 #pragma unroll
     for (int w = 0; w < CB * JX; ++w) load_i(0, 0, w / JX, w % JX, rw_c, soffb_c);
     if (nkb > 1) {
@@ -418,6 +424,17 @@ __global__ __launch_bounds__(256, OCC) void conv_mfma_fast_kernel(MfmaParams P)
     // A thread with no chunk in the last round repeats its first chunk (same data to
     // the same place), which keeps the staging code free of branches.
     if (tid + 256 * (JF - 1) >= NFC) { goffb[JF - 1] = goffb[0]; loff[JF - 1] = loff[0]; }
+    // RAG: bit j*CW + w set when word w of chunk j lies in a channel the last K block does not have
+    uint32_t fzero = 0;
+    if (RAG) {
+        static_assert(!RAG || JF * CW <= 32, "one mask bit per staged filter word");
+#pragma unroll
+        for (int j = 0; j < JF; ++j) {
+            const int e = (loff[j] % PF);   // first K element of the chunk within the block
+#pragma unroll
+            for (int w = 0; w < CW; ++w) fzero |= (e + w >= last_ch * KHW) ? (1u << (j * CW + w)) : 0u;
+        }
+    }
 
     const lds_float *ap0 = (const lds_float *)lds + (wm * 32 + l32) * PF + h * KHW + hk * ((CB / 2) * KHW);
     float *wI0 = lds + SF_FLOATS + tid;
@@ -441,16 +458,19 @@ __global__ __launch_bounds__(256, OCC) void conv_mfma_fast_kernel(MfmaParams P)
         }
     };
     constexpr int WPS = CW >= 2 ? 2 : 1;   // words per filter store slot
-    auto store_f = [&](int st, int j, int half) __attribute__((always_inline)) {   // words WPS*half .. of chunk j
+    // last: the K block being written is the ragged last one (RAG instances only)
+    auto store_f = [&](int st, int j, int half, bool last = false) __attribute__((always_inline)) {   // words WPS*half .. of chunk j
         lds_float *d = (lds_float *)lds + st * STAGE + loff[j] + WPS * half;
-        d[0] = fr[j][WPS * half];
-        if constexpr (WPS == 2) d[1] = fr[j][WPS * half + 1];
+        const int b = j * CW + WPS * half;
+        d[0] = (RAG && last && ((fzero >> b) & 1u)) ? 0.0f : fr[j][WPS * half];
+        if constexpr (WPS == 2) d[1] = (RAG && last && ((fzero >> (b + 1)) & 1u)) ? 0.0f : fr[j][WPS * half + 1];
     };
-    auto store_i = [&](int st, int set, int c, int j, const int (&loffI)[JX], uint32_t zero) __attribute__((always_inline)) {
+    auto store_i = [&](int st, int set, int c, int j, const int (&loffI)[JX], uint32_t zero, bool last = false) __attribute__((always_inline)) {
+        const bool gone = RAG && last && c >= last_ch;   // wave-uniform
         if (IMP)
-            ((lds_float *)lds)[SF_FLOATS + loffI[j] + st * STAGE + c * SS] = ((zero >> j) & 1u) ? 0.0f : ir[set][c * JX + j];
+            ((lds_float *)lds)[SF_FLOATS + loffI[j] + st * STAGE + c * SS] = (((zero >> j) & 1u) || gone) ? 0.0f : ir[set][c * JX + j];
         else
-            ((lds_float *)wI0)[st * STAGE + c * SS + 256 * j] = ir[set][c * JX + j];
+            ((lds_float *)wI0)[st * STAGE + c * SS + 256 * j] = gone ? 0.0f : ir[set][c * JX + j];
     };
 
     // ---- one K block --------------------------------------------------------------
@@ -495,6 +515,7 @@ __global__ __launch_bounds__(256, OCC) void conv_mfma_fast_kernel(MfmaParams P)
         constexpr int ST = decltype(stc)::value;
         constexpr bool HAS1 = decltype(has1c)::value, HAS2 = decltype(has2c)::value;
         constexpr bool NX1 = decltype(nx1c)::value, NX2 = decltype(nx2c)::value;
+        constexpr bool LAST = RAG && HAS1 && !HAS2;   // this block writes the tile's last K block to LDS
 #pragma unroll
         for (int i = 0; i < NM; ++i) {
             if (HAS1 && i == NSLOT) __syncthreads();
@@ -504,7 +525,7 @@ __global__ __launch_bounds__(256, OCC) void conv_mfma_fast_kernel(MfmaParams P)
             if (i + R < NM) lds_op(ST, i + R, bp_c);
             else if (HAS1) { if (NX1) lds_op(ST ^ 1, i + R - NM, bp_n); else lds_op(ST ^ 1, i + R - NM, bp_c); }
             if (i < NFW) {                       // filter chunk i/HPC: store a half, then reload it
-                if (HAS1) store_f(ST ^ 1, i / HPC, i % HPC);
+                if (HAS1) store_f(ST ^ 1, i / HPC, i % HPC, LAST);
                 if (HAS2 && (i % HPC == HPC - 1)) { if (NX2) load_f(kb2, i / HPC, rf_n); else load_f(kb2, i / HPC, rf_c); }
             } else if (i < NFW + NIWS) {   // strip words of the next block: two stores per slot
                 if (HAS1) {
@@ -513,8 +534,8 @@ __global__ __launch_bounds__(256, OCC) void conv_mfma_fast_kernel(MfmaParams P)
                         store_i(ST ^ 1, ST ^ 1, w / JX, w % JX, loffI_n, zero_n);
                         if (w + 1 < NIW) store_i(ST ^ 1, ST ^ 1, (w + 1) / JX, (w + 1) % JX, loffI_n, zero_n);
                     } else {
-                        store_i(ST ^ 1, ST ^ 1, w / JX, w % JX, loffI_c, zero_c);
-                        if (w + 1 < NIW) store_i(ST ^ 1, ST ^ 1, (w + 1) / JX, (w + 1) % JX, loffI_c, zero_c);
+                        store_i(ST ^ 1, ST ^ 1, w / JX, w % JX, loffI_c, zero_c, LAST);
+                        if (w + 1 < NIW) store_i(ST ^ 1, ST ^ 1, (w + 1) / JX, (w + 1) % JX, loffI_c, zero_c, LAST);
                     }
                 }
             } else if (i < NFW + NIWS + NILS) {   // strip words of the block after that: LPS loads per slot
@@ -672,6 +693,28 @@ static hipError_t launch_fast_t(const MfmaParams &P, uint32_t blocks, hipStream_
     constexpr int KB = CB * HF * WF;
     constexpr int PF = KB | 1;
     constexpr size_t lds = 2u * 4u * (size_t)(((MB * PF + 3) & ~3) + CB * 256 * JX);
+    if (P.Ci % CB != 0) {
+        // ragged last K block: whole tiles, one per workgroup (only the 16-byte filter-fetch instances exist)
+        if constexpr (CW == (HF == 7 ? 2 : 4)) {
+            MfmaParams Q = P;
+            Q.nblocks = blocks; Q.nmain = blocks; Q.nhalf = 0;
+            void (*kern)(MfmaParams) = &conv_mfma_fast_kernel<HF, WF, CB, JX, CW, OCC, IMP, false, false, false, true>;
+            if (plan) {
+                plan_record(plan, dim3(blocks), 256, lds, "conv_mfma_fast_kernel<%d, %d, %d, %d, %d, %d, %s, false, false, false, true>",
+                            HF, WF, CB, JX, CW, OCC, tf(IMP));
+                return hipSuccess;
+            }
+            static KernelCache kcr;
+            int dev = 0;
+            hipError_t e = hipGetDevice(&dev);
+            if (e != hipSuccess) return e;
+            if ((e = allow_dynamic_lds(kcr, reinterpret_cast<const void *>(kern), lds, dev)) != hipSuccess) return e;
+            hipLaunchKernelGGL(kern, dim3(blocks), dim3(256), lds, st, Q);
+            return hipGetLastError();
+        } else {
+            return hipErrorNotSupported;
+        }
+    }
     // Several tiles per workgroup (the pipeline then runs across tile boundaries) when every tile
     // starts in LDS stage 0 (an even number of K blocks), every filter row of every tile exists,
     // and there are at least three tiles per resident workgroup.  It pays for short K loops --
@@ -723,7 +766,7 @@ static hipError_t launch_fast_t(const MfmaParams &P, uint32_t blocks, hipStream_
     if (nhalf && npiece) { kern = &conv_mfma_fast_kernel<HF, WF, CB, JX, CW, OCC, IMP, false, PIECEABLE, HALFABLE>; which = 4; }
     if (plan) {
         const bool per = which == 1, tail = (which == 2 || which == 4) && PIECEABLE, half = (which == 3 || which == 4) && HALFABLE;
-        plan_record(plan, dim3(grid), 256, lds, "conv_mfma_fast_kernel<%d, %d, %d, %d, %d, %d, %s, %s, %s, %s>",
+        plan_record(plan, dim3(grid), 256, lds, "conv_mfma_fast_kernel<%d, %d, %d, %d, %d, %d, %s, %s, %s, %s, false>",
                     HF, WF, CB, JX, CW, OCC, tf(IMP), tf(per), tf(tail), tf(half));
         return hipSuccess;
     }
@@ -747,9 +790,12 @@ static hipError_t launch_fast_i(const MfmaParams &P, uint32_t blocks, hipStream_
 hipError_t launch_conv_mfma_fast(MfmaParams P, const Shape &sh, uint32_t blocks, hipStream_t st, bool implicit,
                                  int filter_fetch_floats, LaunchPlan *plan)
 {
+    // Filter rows are fetched in 16-byte (7x7: 8-byte) pieces from a 16-byte (8-byte) aligned filter.
+    // With K = Ci*Hf*Wf not a multiple of four the rows themselves start at odd multiples of four
+    // bytes: the buffer loads take that (the ablation instances ask for aligned rows).
     const uintptr_t fa = reinterpret_cast<uintptr_t>(P.flt);
-    const bool al16 = (fa & 15u) == 0 && (sh.K % 4 == 0);   // filter rows readable as aligned float4
-    const bool al8 = (fa & 7u) == 0 && (sh.K % 2 == 0);     // ... as aligned float2
+    const bool al16 = (fa & 15u) == 0, al8 = (fa & 7u) == 0;
+    const bool rows16 = al16 && (sh.K % 4 == 0);
     // Strip words are addressed with 32-bit byte offsets from the tile's first strip word (from
     // its first image in the workspace-free variant): the rows of a tile (at most P.rmax of
     // them, in at most that many images) must span < 4 GiB.
@@ -762,23 +808,24 @@ hipError_t launch_conv_mfma_fast(MfmaParams P, const Shape &sh, uint32_t blocks,
     // output words: 32-bit byte offsets from (image of the tile's first pixel, first channel of the wave)
     if (((unsigned long long)sh.Co * (unsigned long long)P.rmax + 64ull) * (unsigned long long)sh.Ho * sh.Wo * 4ull >= (1ull << 32))
         return hipErrorNotSupported;
-    if (filter_fetch_floats == 2 && !implicit && sh.Hf == 3 && sh.Wf == 3 && sh.Ci % 8 == 0 && al16) {   // ablation: 8-byte filter chunks
+    if (filter_fetch_floats == 2 && !implicit && sh.Hf == 3 && sh.Wf == 3 && sh.Ci % 8 == 0 && rows16) {   // ablation: 8-byte filter chunks
         if (P.S <= 256) return launch_fast_t<3, 3, 8, 1, 2, 3, false>(P, blocks, st, plan);
         if (P.S <= 512) return launch_fast_t<3, 3, 8, 2, 2, 3, false>(P, blocks, st, plan);
     }
-    if (filter_fetch_floats == 1 && !implicit && sh.Hf == 3 && sh.Wf == 3 && sh.Ci % 8 == 0 && al16) {   // ablation: 4-byte filter chunks
+    if (filter_fetch_floats == 1 && !implicit && sh.Hf == 3 && sh.Wf == 3 && sh.Ci % 8 == 0 && rows16) {   // ablation: 4-byte filter chunks
         if (P.S <= 256) return launch_fast_t<3, 3, 8, 1, 1, 3, false>(P, blocks, st, plan);
         if (P.S <= 512) return launch_fast_t<3, 3, 8, 2, 1, 3, false>(P, blocks, st, plan);
     }
-    if (sh.Hf == 3 && sh.Wf == 3 && sh.Ci % 8 == 0 && al16) {
+    // (Ci need not be a multiple of the K block: the last block is then zero-filled)
+    if (sh.Hf == 3 && sh.Wf == 3 && sh.Ci >= 8 && al16) {
         if (P.S <= 256) return launch_fast_i<3, 3, 8, 1, 4, 3>(P, blocks, st, implicit, plan);
         if (P.S <= 512) return launch_fast_i<3, 3, 8, 2, 4, 3>(P, blocks, st, implicit, plan);
     }
-    if (sh.Hf == 5 && sh.Wf == 5 && sh.Ci % 4 == 0 && al16) {
+    if (sh.Hf == 5 && sh.Wf == 5 && sh.Ci >= 4 && al16) {
         if (P.S <= 256) return launch_fast_i<5, 5, 4, 1, 4, 2>(P, blocks, st, implicit, plan);
         if (P.S <= 512) return launch_fast_i<5, 5, 4, 2, 4, 2>(P, blocks, st, implicit, plan);
     }
-    if (sh.Hf == 7 && sh.Wf == 7 && sh.Ci % 2 == 0 && al8) {
+    if (sh.Hf == 7 && sh.Wf == 7 && sh.Ci >= 2 && al8) {
         if (P.S <= 512) return launch_fast_i<7, 7, 2, 2, 2, 2>(P, blocks, st, implicit, plan);
         if (P.S <= 1024) return launch_fast_i<7, 7, 2, 4, 2, 2>(P, blocks, st, implicit, plan);
     }

@@ -65,11 +65,21 @@ TABLE2 = (
 )
 
 
+# Layers off the specialised kernels' grid, timed by `bench.py --extra`: a channel count that is not a
+# multiple of the pipelined kernel's K block, a 1x1 layer, an asymmetric filter.
+EXTRA = (
+    Layer("extra_3x3_c60_56", 32, 60, 56, 56, 64, 3, 3, 1, 1, 3001, "uniform01", "he_normal"),
+    Layer("extra_3x3_c100_28", 64, 100, 28, 28, 128, 3, 3, 1, 1, 3002, "uniform01", "he_normal"),
+    Layer("extra_1x1_c256_28", 64, 256, 28, 28, 256, 1, 1, 1, 0, 3003, "uniform01", "he_normal"),
+    Layer("extra_1x7_c64_28", 64, 64, 28, 28, 64, 1, 7, 1, 0, 3004, "uniform01", "he_normal"),
+)
+
+
 def layer(index_or_name) -> Layer:
     """Layer by 1-based index (1..5) or by name."""
     if isinstance(index_or_name, int):
         return LAYERS[index_or_name - 1]
-    for l in LAYERS + TABLE2:
+    for l in LAYERS + TABLE2 + EXTRA:
         if l.name == index_or_name:
             return l
     raise KeyError(index_or_name)

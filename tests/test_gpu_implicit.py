@@ -25,6 +25,10 @@ SHAPES = [
     (1, 2, 9, 140, 8, 7, 7, 2, 3),
     (1, 6, 30, 70, 33, 7, 7, 2, 3),
     (3, 8, 11, 13, 20, 3, 3, 2, 2),      # stride 2, padding 2: tiles of nine short rows
+    (2, 9, 14, 14, 70, 3, 3, 1, 1),      # channel counts off the K block: zero-filled last block
+    (1, 60, 56, 56, 64, 3, 3, 1, 1),
+    (2, 6, 16, 16, 40, 5, 5, 1, 2),
+    (1, 5, 30, 70, 33, 7, 7, 2, 3),
 ]
 
 

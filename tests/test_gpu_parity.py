@@ -52,6 +52,14 @@ EDGE_SHAPES = [
     (2, 3, 50, 290, 64, 11, 11, 4, 0),
     (1, 3, 30, 200, 16, 3, 3, 1, 1),   # 3x3 on three channels
     (1, 3, 36, 280, 100, 3, 3, 1, 1),  # Co = 100: two filter groups in the grid
+    # channel counts that are not a multiple of the pipelined kernel's K block: zero-filled last block
+    (2, 9, 14, 14, 70, 3, 3, 1, 1),      # 3x3, 9 channels: one real channel in the second block
+    (2, 12, 30, 30, 64, 3, 3, 1, 1),
+    (1, 60, 56, 56, 64, 3, 3, 1, 1),     # the headline layer's shape with 60 channels
+    (1, 15, 20, 150, 40, 3, 3, 2, 0),    # wide rows (two strip words per thread), stride 2
+    (2, 6, 16, 16, 40, 5, 5, 1, 2),      # 5x5, 6 channels (K block of 4)
+    (1, 5, 30, 70, 33, 7, 7, 2, 3),      # 7x7, 5 channels (K block of 2): odd K, 8-byte fetches at 4-byte alignment
+    (1, 256 + 8 + 1, 7, 7, 64, 3, 3, 1, 1),   # 33 whole K blocks and one channel
     # layers no tiled kernel takes: computed by the one-thread-per-output kernels
     (3, 8, 3, 3, 5, 3, 3, 1 << 26, 0),   # a stride far beyond the image (one output per image)
     (2, 8, 5, 3, 5, 3, 3, 2, 0),         # ... and an ordinary one on the same tiny image

@@ -150,6 +150,10 @@ def test_launch_info_names_the_dispatch(lib):
         assert im2win.conv2d_im2win_fwd_launch_info(*L.dims, variant=v)["kernel"].startswith(
             "conv_mfma_fast_kernel<3, 3, 8, 1, %d, 3," % cw)
     assert ", true, " in im2win.conv2d_im2win_fwd_launch_info(*L.dims, workspace_free=True)["kernel"]
+    # a channel count off the K block still takes the pipelined kernel (its ragged instance)
+    assert im2win.conv2d_im2win_fwd_launch_info(128, 60, 56, 56, 64, 3, 3, 1, 1)["kernel"] == \
+        "conv_mfma_fast_kernel<3, 3, 8, 1, 4, 3, false, false, false, false, true>"
+    assert im2win.conv2d_im2win_fwd_launch_info(8, 7, 56, 56, 64, 3, 3, 1, 1)["kernel"] == "conv_mfma_kernel<9, false>"
     # layers that no tiled kernel takes go to the one-thread-per-output kernels instead of failing
     assert im2win.conv2d_im2win_fwd_launch_info(1, 2, 30, 28, 6, 25, 25, 1, 0)["kernel"] == "conv_basic_kernel"
     assert im2win.conv2d_im2win_fwd_launch_info(1, 2, 30, 28, 6, 25, 25, 1, 0, workspace_free=True)["kernel"] == "conv_direct_kernel"
