@@ -28,18 +28,24 @@ if ROOT not in sys.path:
 PEAK_FP32_MATRIX_TFLOPS = 157.3   # MI355X dense fp32 MFMA: 256 CU x 256 flop/clk x 2.4 GHz
 PEAK_HBM_GBS = 8000.0             # MI355X HBM3E
 
-# HBM traffic of one launch of each kernel, bytes, keyed by layer name: measured
-# with two rocprofv3 --pmc runs (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch)
-# of this script and scaled by what the same counters read for a plain 256 MiB
-# device copy (factors 2.000 and 1.000).  The summaries with the commands are
-# profiles/conv_mfma_fast_and_transform_cfg2_3x3_c64_56.md (headline layer) and
-# profiles/all_layers_default_bench.md.  Layers that were not measured report null.
+# HBM traffic of one launch of each kernel, bytes, keyed by layer name: measured with two
+# rocprofv3 --pmc runs of this script (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch) and scaled by
+# what the same counters read for a plain 256 MiB device copy in the same runs (factors 2.000 and
+# 1.000).  The values are the TRAFFIC_BYTES lines of profiles/all_layers_default_bench.md, which
+# gives the commands; tests/test_host_api.py holds the two to each other.  Layers that were not
+# measured report null.
 MEASURED_CONV_TRAFFIC_BYTES = {
-    "cfg1_tiny_3x3": 205824, "cfg2_3x3_c64_56": 107761653, "cfg3_3x3_c256_14": 206840729,
-    "cfg4_7x7_s2_c3_224": 688850223, "cfg5_11x11_s4_c3_227": 412440742}
+    "cfg1_tiny_3x3": 206109,
+    "cfg2_3x3_c64_56": 107743370,
+    "cfg3_3x3_c256_14": 214675152,
+    "cfg4_7x7_s2_c3_224": 688850715,
+    "cfg5_11x11_s4_c3_227": 412480371}
 MEASURED_TRANSFORM_TRAFFIC_BYTES = {
-    "cfg1_tiny_3x3": 85500, "cfg2_3x3_c64_56": 106936518, "cfg3_3x3_c256_14": 114459371,
-    "cfg4_7x7_s2_c3_224": 369831431, "cfg5_11x11_s4_c3_227": 309585768}
+    "cfg1_tiny_3x3": 63485,
+    "cfg2_3x3_c64_56": 105599216,
+    "cfg3_3x3_c256_14": 113849701,
+    "cfg4_7x7_s2_c3_224": 362295374,
+    "cfg5_11x11_s4_c3_227": 298434154}
 
 
 def parse_args():

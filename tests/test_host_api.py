@@ -180,3 +180,18 @@ def test_probe_arguments_are_validated(lib):
     assert lib.im2win_probe_stream(0, None, one, 1024, None) == -1
     assert lib.im2win_probe_stream(0, one, one, 1000, None) == -2
     assert lib.im2win_probe_stream(2, None, ctypes.c_void_p(20), 1024, None) == -2
+
+
+def test_bench_traffic_constants_are_the_profiled_ones():
+    """bench.py reports HBM traffic per launch from constants; they must be the figures of the
+    kept rocprofv3 summary, not numbers from some other run."""
+    import bench
+    path = os.path.join(ROOT, "profiles", "all_layers_default_bench.md")
+    got = {"conv": {}, "transform": {}}
+    for ln in open(path):
+        m = re.match(r"\s+TRAFFIC_BYTES (\w+) (\w+) (\d+)", ln)
+        if m:
+            got[m.group(1)][m.group(2)] = int(m.group(3))
+    assert got["conv"] == bench.MEASURED_CONV_TRAFFIC_BYTES
+    assert got["transform"] == bench.MEASURED_TRANSFORM_TRAFFIC_BYTES
+    assert set(got["conv"]) == {L.name for L in workloads.LAYERS}
