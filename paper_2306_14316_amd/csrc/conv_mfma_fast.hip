@@ -236,18 +236,27 @@ __global__ __launch_bounds__(256, OCC) void conv_mfma_fast_kernel(MfmaParams P)
                   "half tiles: the channel pairs of a K block split evenly between two waves");
     // half-tile workgroups: which tile, which half; waves 0/1 take the first half of the channel
     // pairs of every K block, waves 2/3 the second (hk = 1)
-    const bool hmode = HALF && blockIdx.x >= P.nmain && blockIdx.x < P.nmain + 2u * P.nhalf;   // workgroup-uniform
-    const uint32_t vb_first = hmode ? P.nmain + ((blockIdx.x - P.nmain) >> 1) : blockIdx.x;
-    const int hpix = hmode ? (int)((blockIdx.x - P.nmain) & 1u) * 32 : 0;   // first pixel of the half, within the tile
+    // bid: the workgroup's place in the order "whole tiles, halves, sixteenths".  In the grid itself
+    // the sixteenths sit at blocks P.tail_at ... (a multiple of 8, so XCDs are unchanged): dispatched
+    // in the middle of the layer, their cold loads are covered by the whole tiles running beside them.
+    uint32_t bid = blockIdx.x;
+    if constexpr (TAIL) {
+        const uint32_t end_main = P.nmain + 2u * P.nhalf, npb = gridDim.x - end_main;
+        if (bid >= P.tail_at && bid < P.tail_at + npb) bid = end_main + (bid - P.tail_at);
+        else if (bid >= P.tail_at + npb) bid -= npb;
+    }
+    const bool hmode = HALF && bid >= P.nmain && bid < P.nmain + 2u * P.nhalf;   // workgroup-uniform
+    const uint32_t vb_first = hmode ? P.nmain + ((bid - P.nmain) >> 1) : bid;
+    const int hpix = hmode ? (int)((bid - P.nmain) & 1u) * 32 : 0;   // first pixel of the half, within the tile
     const int wn_g = hmode ? 0 : wn;             // pixel block of the wave within the (half) tile
     const int hk = hmode ? (wave >> 1) : 0, hk_u = hmode ? (wave_u >> 1) : 0;
 
-    if constexpr (TAIL) if (blockIdx.x >= P.nmain + 2u * P.nhalf) {
+    if constexpr (TAIL) if (bid >= P.nmain + 2u * P.nhalf) {
         // Piece q of leftover tile t.  Workgroup b runs on XCD b % 8 and the pieces start at a
         // multiple of 8: the sixteen pieces of a tile are dealt to the same XCD, whose L2 then
         // serves their shared filter rows and windows (the last L % 8 tiles aside).
         const uint32_t first = P.nmain + P.nhalf;   // first tile computed in pieces
-        const uint32_t sub = blockIdx.x - (P.nmain + 2u * P.nhalf), L = P.nblocks - first, full = L & ~7u;
+        const uint32_t sub = bid - (P.nmain + 2u * P.nhalf), L = P.nblocks - first, full = L & ~7u;
         uint32_t t, q;
         if (sub < 16u * full) {
             t = (sub & 7u) + ((sub >> 7) << 3);
@@ -647,7 +656,7 @@ __global__ __launch_bounds__(256, OCC) void conv_mfma_fast_kernel(MfmaParams P)
     // ---- tiles of this workgroup ----
     // The host gives a workgroup more than one tile only when nkb is even (every tile then
     // starts in LDS stage 0) and Co is a multiple of the tile height.
-    for (uint32_t vb = blockIdx.x;;) {
+    for (uint32_t vb = bid;;) {
         const bool has_next = PER && vb + gridDim.x < ntiles;   // wave-uniform
         if (has_next) tile_geometry(vb + gridDim.x, P0_n, Pend_n, m0_n, bp_n, soffb_n, loffI_n, zero_n, rf_n, rw_n);
 
@@ -697,7 +706,7 @@ static hipError_t launch_fast_t(const MfmaParams &P, uint32_t blocks, hipStream_
         // ragged last K block: whole tiles, one per workgroup (only the 16-byte filter-fetch instances exist)
         if constexpr (CW == (HF == 7 ? 2 : 4)) {
             MfmaParams Q = P;
-            Q.nblocks = blocks; Q.nmain = blocks; Q.nhalf = 0;
+            Q.nblocks = blocks; Q.nmain = blocks; Q.nhalf = 0; Q.tail_at = blocks;
             void (*kern)(MfmaParams) = &conv_mfma_fast_kernel<HF, WF, CB, JX, CW, OCC, IMP, false, false, false, true>;
             if (plan) {
                 plan_record(plan, dim3(blocks), 256, lds, "conv_mfma_fast_kernel<%d, %d, %d, %d, %d, %d, %s, false, false, false, true>",
@@ -758,6 +767,7 @@ static hipError_t launch_fast_t(const MfmaParams &P, uint32_t blocks, hipStream_
         grid = Q.nmain + 2 * nhalf + 16 * npiece;
     }
     Q.nhalf = nhalf;
+    Q.tail_at = Q.nmain + 2 * nhalf;
     void (*kern)(MfmaParams) = &conv_mfma_fast_kernel<HF, WF, CB, JX, CW, OCC, IMP, false, false>;
     int which = 0;   // which of this launcher's five kernel instances
     if (grid < blocks) { kern = &conv_mfma_fast_kernel<HF, WF, CB, JX, CW, OCC, IMP, true, false>; which = 1; }

@@ -177,6 +177,19 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
     for (int g = 0; g < G; ++g) { nwpos[g] = 0; nooff[g] = 0; nroom[g] = 0; cwpos[g] = 0; croom[g] = 0; proom[g] = 0; cooff[g] = 0; pooff[g] = 0; }
     floatx16 acc[2][G];
     float own[8];           // (KS == 2) this wave's partial sums of that half, kept from the previous tile
+    // (KS == 2) this lane's slots in the exchange area: where it leaves the partner's half of a tile's
+    // sums and where it finds its own half of the partner's.  One register each, computed once and made
+    // opaque, so that every access is base + immediate (parity and register index are compile-time);
+    // left to itself the compiler kept a separate address register per access and spilled them, and
+    // every reload then waited for all memory traffic in flight.
+    const lds_f32 *xmine = lds, *xtheirs = lds;
+    if (KS == 2) {
+        uint32_t om = (uint32_t)(2 * STAGE + ((wn * WM + wm) * 2 + ks) * 512 + lane) * 4u;
+        uint32_t ot = (uint32_t)(2 * STAGE + ((wn * WM + wm) * 2 + (ks ^ 1)) * 512 + lane) * 4u;
+        asm volatile("" : "+v"(om), "+v"(ot));
+        xmine = (const lds_f32 *)((const __attribute__((address_space(3))) char *)lds + om);
+        xtheirs = (const lds_f32 *)((const __attribute__((address_space(3))) char *)lds + ot);
+    }
 
     const uint32_t per = (P.ntiles + gridDim.x - 1) / gridDim.x;
     const uint32_t tile0 = blockIdx.x * per;
@@ -312,12 +325,22 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
                 noff[j] = (uint32_t)(xc + d) * 4u;
             }
         } else if constexpr (p >= P_LD && p < P_WPOS) {
-            // descriptor on the tile's first strip word; the channel is a scalar offset
+            // descriptor on the tile's first strip word; the channel is a scalar offset.  The strips are
+            // copied as they lie in memory, lane after lane, so the loads write LDS directly (no staging
+            // registers, no LDS store instructions): the wave's 64 words land at the uniform address in M0.
+            // The workspace-free variant permutes the words and takes them through registers.
             const __amdgpu_buffer_rsrc_t rw = make_desc(const_cast<float *>(P.win + nbase), P.win_elems - nbase);
 #pragma unroll
-            for (int w = 2 * (p - P_LD); w < 2 * (p - P_LD) + 2 && w < NIW; ++w)
-                ir[w] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
-                                                      rw, noff[w % JX], (uint32_t)(w / JX) * (IMP ? (uint32_t)P.in_plane : P.chan_stride) * 4u, 0));
+            for (int w = 2 * (p - P_LD); w < 2 * (p - P_LD) + 2 && w < NIW; ++w) {
+                const uint32_t soff = (uint32_t)(w / JX) * (IMP ? (uint32_t)P.in_plane : P.chan_stride) * 4u;
+                if constexpr (IMP) {
+                    ir[w] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rw, noff[w % JX], soff, 0));
+                } else {
+                    lds_f32 *dst = lds + st_next * STAGE + (w / JX) * SS + NT * (w % JX) + wave * 64;
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, (__attribute__((address_space(3))) void *)dst, 4,
+                                                             noff[w % JX], soff, 0, 0);
+                }
+            }
         } else if constexpr (p >= P_WPOS && p < P_OPTR) {
             constexpr int g = p - P_WPOS;
             const uint32_t Pl = min(nP0 + (uint32_t)(g * NB + wn * 32 + l32), nPend);
@@ -343,8 +366,7 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
             if constexpr (KS == 2) {
                 // add the partner's partial sum to this wave's (kept in own[]) first; these
                 // instances are short of scalar registers and rebuild the descriptor here
-                const lds_f32 *theirs = lds + 2 * STAGE + xpar * (WM * 2 * 2 * 512) + ((wn * WM + wm) * 2 + (ks ^ 1)) * 512 + lane;
-                const float val = own[q] + *(const volatile lds_f32 *)(theirs + q * 64);
+                const float val = own[q] + *(const volatile lds_f32 *)(xtheirs + xpar * (WM * 2 * 2 * 512) + q * 64);
                 const size_t left = (P.out_elems - pobase) * 4u;
                 const __amdgpu_buffer_rsrc_t ro = __builtin_amdgcn_make_buffer_rsrc(
                     P.out + pobase, 0, left < 0xffffffffull ? left : 0xffffffffull, 0x00020000);
@@ -355,14 +377,17 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
                 store_one(pacc[g][q], q, pdesc, pobase, pooff[g], proom[g], (pfull >> g) & 1u);
             }
         } else if constexpr (p >= P_LDS && p < NP) {
-            lds_f32 *d = lds + st_next * STAGE + tid;
+            if constexpr (IMP) {
 #pragma unroll
-            for (int w = 2 * (p - P_LDS); w < 2 * (p - P_LDS) + 2 && w < NIW; ++w) {
-                if (IMP) lds[st_next * STAGE + (w / JX) * SS + nlpos[w % JX]] = ((nzero >> (w % JX)) & 1u) ? 0.0f : ir[w];
-                else d[(w / JX) * SS + NT * (w % JX)] = ir[w];
+                for (int w = 2 * (p - P_LDS); w < 2 * (p - P_LDS) + 2 && w < NIW; ++w)
+                    lds[st_next * STAGE + (w / JX) * SS + nlpos[w % JX]] = ((nzero >> (w % JX)) & 1u) ? 0.0f : ir[w];
             }
         }
     };
+    // The next tile's strips must be in LDS before the barrier that ends a tile: the direct loads
+    // are complete when the wave's vector-memory counter is back at zero (vmcnt(0); the other
+    // counters are left alone).
+    auto strips_landed = []() __attribute__((always_inline)) { if (!IMP) __builtin_amdgcn_s_waitcnt(0x0F70); };
     // pieces lo..hi-1
     auto pieces = [&](auto loc, auto hic, uint32_t t, int st_next, const floatx16 (&pacc)[G], int xpar) __attribute__((always_inline)) {
         constexpr int lo = decltype(loc)::value, hi = decltype(hic)::value;
@@ -381,6 +406,7 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
         pieces(std::integral_constant<int, P_GEO>{}, std::integral_constant<int, P_ST>{}, tile0, 0, acc[0], 0);
         pieces(std::integral_constant<int, P_LDS>{}, std::integral_constant<int, NP>{}, tile0, 0, acc[0], 0);
     }
+    strips_landed();
     __syncthreads();
 
     // ---- one tile: the MFMA chain with the pieces in its shadow -------------------
@@ -442,7 +468,7 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
             if (KS == 2) {
                 // hand the partner the half of this tile's accumulators that it owns, keep the other
                 // (register indices are compile-time constants here: KSI is this wave's K share)
-                lds_f32 *mine = lds + 2 * STAGE + PAR * (WM * 2 * 2 * 512) + ((wn * WM + wm) * 2 + KSI) * 512 + lane;
+                lds_f32 *mine = const_cast<lds_f32 *>(xmine) + PAR * (WM * 2 * 2 * 512);   // (ks == KSI in this instance of run)
 #pragma unroll
                 for (int v = 0; v < 8; ++v) mine[v * 64] = acc[0][0][KSI ? v : 8 + v];
 #pragma unroll
@@ -460,6 +486,7 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
         if (KS == 1) pdesc = cdesc;
 #pragma unroll
         for (int g = 0; g < G; ++g) { pooff[g] = cooff[g]; proom[g] = croom[g]; }
+        strips_landed();
         __syncthreads();
     };
 

@@ -25,12 +25,14 @@ struct MfmaParams {
     uint32_t in_plane;  // Hi*Wi
     int cb;          // channels per K block
     int S;           // LDS floats reserved per channel strip
+    int SP;          // the same rounded up to a multiple of 64 (pipelined generic kernel)
     int rmax;        // output rows a tile may touch
     int fullseg;     // ((Wo-1)*s + Wf)*Hf : strip floats of a fully covered output row
     int tiles_m;
     uint32_t nblocks;   // tiles of the whole layer (the pipelined kernel may run fewer workgroups)
     uint32_t nmain;     // pipelined kernel: tiles below this one are computed whole,
     uint32_t nhalf;     // the next nhalf tiles as two halves each, the rest in sixteenths
+    uint32_t tail_at;   // grid position (block index) of the first sixteenth
     int vec4;        // filter rows can be read as aligned float4 in every K block
     FastDiv d_wo, d_ho, d_howo, d_khw, d_wf, d_cpr, d_tm;
 };

@@ -60,6 +60,18 @@ EDGE_SHAPES = [
     (2, 6, 16, 16, 40, 5, 5, 1, 2),      # 5x5, 6 channels (K block of 4)
     (1, 5, 30, 70, 33, 7, 7, 2, 3),      # 7x7, 5 channels (K block of 2): odd K, 8-byte fetches at 4-byte alignment
     (1, 256 + 8 + 1, 7, 7, 64, 3, 3, 1, 1),   # 33 whole K blocks and one channel
+    # the generic kernel, pipelined (two LDS stages) and, for the largest windows, single-stage
+    (2, 256, 14, 14, 70, 1, 1, 1, 0),    # 1x1, four blocks of 64 channels
+    (2, 64, 14, 14, 70, 1, 1, 1, 0),     # 1x1, one block: single-stage kernel
+    (1, 230, 9, 9, 40, 1, 1, 2, 0),      # 1x1 strided, 64 + 64 + 64 + 38 channels
+    (1, 193, 12, 12, 20, 1, 1, 1, 1),    # 1x1 padded, odd channel count: a split step in the last block
+    (2, 34, 9, 30, 40, 1, 7, 1, 0),      # 1x7: eight channels per block, five blocks, the last with two
+    (2, 27, 30, 9, 40, 7, 1, 1, 3),      # 7x1 padded, odd channel count: a split step in the last block
+    (1, 37, 12, 14, 24, 2, 4, 2, 1),     # 2x4 stride 2: eight channels per block, five blocks, the last with five
+    (1, 7, 24, 24, 12, 9, 9, 1, 0),      # 9x9: two channels per block, four blocks, a split step in the last
+    (1, 3, 24, 24, 12, 9, 9, 1, 0),      # 9x9 with three channels: too few blocks, single-stage kernel
+    (2, 7, 12, 14, 24, 2, 4, 1, 1),      # 2x4, seven channels: one block, single-stage kernel
+    (1, 2, 40, 40, 8, 17, 17, 1, 0),     # 17x17: two stages do not fit LDS, single-stage kernel
     # layers no tiled kernel takes: computed by the one-thread-per-output kernels
     (3, 8, 3, 3, 5, 3, 3, 1 << 26, 0),   # a stride far beyond the image (one output per image)
     (2, 8, 5, 3, 5, 3, 3, 2, 0),         # ... and an ordinary one on the same tiny image

@@ -68,11 +68,14 @@ def test_random_shape_all_routes(shape):
     dO = run_conv(dW, F, N, Ci, Hi, Wi, s, p)
     assert_conv_close(dO.cpu().numpy(), O_ref, B_ref)
 
-    # workspace-free variant: same strips, same summation order -> same bits
+    # workspace-free variant: same strips, same summation order -> same bits (where the two-call path
+    # takes the two-stage generic kernel, which has no workspace-free form, the K blocks differ)
     dO2 = torch.full_like(dO, POISON)
     im2win.conv2d_im2win_implicit_fwd(dI, dF, dO2, N, Ci, Hi, Wi, Co, Hf, Wf, s, p)
     torch.cuda.synchronize()
-    assert torch.equal(dO.view(torch.int32), dO2.view(torch.int32))
+    assert_conv_close(dO2.cpu().numpy(), O_ref, B_ref)
+    if not im2win.conv2d_im2win_fwd_launch_info(*shape)["kernel"].startswith("conv_mfma_pipe_kernel"):
+        assert torch.equal(dO.view(torch.int32), dO2.view(torch.int32))
 
     # baselines
     dO3 = torch.full_like(dO, POISON)
