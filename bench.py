@@ -35,17 +35,17 @@ PEAK_HBM_GBS = 8000.0             # MI355X HBM3E
 # gives the commands; tests/test_host_api.py holds the two to each other.  Layers that were not
 # measured report null.
 MEASURED_CONV_TRAFFIC_BYTES = {
-    "cfg1_tiny_3x3": 206109,
-    "cfg2_3x3_c64_56": 107743370,
-    "cfg3_3x3_c256_14": 214675152,
-    "cfg4_7x7_s2_c3_224": 688850715,
-    "cfg5_11x11_s4_c3_227": 412480371}
+    "cfg1_tiny_3x3": 209022,
+    "cfg2_3x3_c64_56": 107721506,
+    "cfg3_3x3_c256_14": 220524876,
+    "cfg4_7x7_s2_c3_224": 690897981,
+    "cfg5_11x11_s4_c3_227": 380547287}
 MEASURED_TRANSFORM_TRAFFIC_BYTES = {
     "cfg1_tiny_3x3": 63485,
-    "cfg2_3x3_c64_56": 105599216,
-    "cfg3_3x3_c256_14": 113849701,
-    "cfg4_7x7_s2_c3_224": 362295374,
-    "cfg5_11x11_s4_c3_227": 298434154}
+    "cfg2_3x3_c64_56": 105605733,
+    "cfg3_3x3_c256_14": 113849400,
+    "cfg4_7x7_s2_c3_224": 362283010,
+    "cfg5_11x11_s4_c3_227": 298425084}
 
 
 def parse_args():
