@@ -41,6 +41,9 @@ __device__ __forceinline__ void static_for(F &&f)
 
 constexpr int SH_RMAX = 3;   // a 64-pixel tile may touch at most this many output rows
 constexpr int SH_G_MAX = 8;  // B operands are fetched from LDS up to this many steps ahead
+// A byte offset that no output descriptor of this kernel covers (their sizes are capped at it, and
+// the launcher keeps real offsets below it): the buffer unit drops a store at or beyond the size.
+constexpr uint32_t OOB = 0xFFFFFF00u;
 
 struct ShallowParams {
     const float *win;
@@ -76,8 +79,21 @@ struct Steps {
 // the same filter registers (step by step, G MFMAs per step), and the per-tile work (geometry,
 // barrier, state hand-over) is paid once per 64*G pixels -- what layers with a very short K
 // (3x3x3 = 14 MFMA steps) need.
-template <int HF, int WF, int CI, int WM, int KS, int JX, bool IMP, int G>
-__global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(ShallowParams P)
+// WIDE (with G == 4, output planes of a multiple of four pixels, a 16-byte aligned output): lane
+// l32 of a wave takes pixels 4*l32 .. 4*l32+3 of the wave's 128, one per group, so the four
+// accumulators of a channel that a lane holds are neighbours in memory and leave in one 16-byte
+// store: a wave's store instruction then writes 512 contiguous bytes per channel instead of 128.
+// Such layers are bound by their output stream, and 128-byte runs that do not start on a line
+// boundary (planes of 222x222) are written at well under half the rate of long runs.
+// Waves per SIMD the register allocation of an instance is held to (its minimum occupancy).
+// The 7x7 instances run three waves per SIMD; left alone the allocator takes a few registers
+// too many for the third.  (The workspace-free ones would spill.)
+template <int HF, bool IMP, int G>
+constexpr int shallow_waves_per_simd() { return (HF == 7 && G == 1 && !IMP) ? 3 : 1; }
+
+template <int HF, int WF, int CI, int WM, int KS, int JX, bool IMP, int G, bool WIDE>
+__global__ __launch_bounds__(64 * WM * 2 * KS) __attribute__((amdgpu_waves_per_eu(shallow_waves_per_simd<HF, IMP, G>())))
+void conv_mfma_shallow_kernel(ShallowParams P)
 {
     using St = Steps<HF, WF, CI>;
     constexpr int KHW = St::KHW, KH2 = St::KH2, NPAIR = St::NPAIR, T = St::T;
@@ -85,10 +101,11 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
     constexpr int NT = 64 * WM * 2 * KS;       // threads per workgroup
     constexpr int SS = JX * NT;                // LDS floats per channel strip
     constexpr int STAGE = CI * SS + 4;         // one LDS stage: CI strips + a zero slot
-    constexpr int SH_G = (KS == 2) ? 4 : SH_G_MAX;   // shorter ring where registers are scarce
+    constexpr int SH_G = (KS == 2 || WIDE) ? 4 : SH_G_MAX;   // shorter rings where registers are scarce
     constexpr int NBT = NB * G;                // pixels per tile
     static_assert(T % KS == 0, "K steps must split evenly between the waves of a block");
     static_assert(G == 1 || KS == 1, "pixel groups are not combined with a split K");
+    static_assert(!WIDE || G == 4, "16-byte stores take one pixel from each of four groups");
 
     extern __shared__ __align__(16) unsigned char smem[];
     lds_f32 *lds = (lds_f32 *)reinterpret_cast<float *>(smem);   // [2][STAGE] then the exchange area
@@ -144,8 +161,12 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
     constexpr int NIW = CI * JX;                 // strip words per thread and tile
     constexpr int NL = (NIW + 1) / 2;            // pieces that load / store two words each
     constexpr int NE = (KS == 2) ? 8 : 16;       // output-store pieces
+    constexpr int NOP = WIDE ? 1 : G;            // output positions a lane keeps per tile
+    constexpr int NSTP = WIDE ? 0 : NE * G;      // store pieces that ride in the next tile's chain
     constexpr int P_GEO = 0, P_OFF = 4, P_LD = P_OFF + JX, P_WPOS = P_LD + NL, P_OPTR = P_WPOS + G,
-                  P_ST = P_OPTR + G, P_LDS = P_ST + NE * G, NP = P_LDS + NL;
+                  P_ST = P_OPTR + NOP, P_LDS = P_ST + NSTP, NP = P_LDS + NL;
+    // pixel of the tile that lane l32 of pixel half wn computes in group g
+    auto tile_pixel = [&](int g) __attribute__((always_inline)) { return WIDE ? wn * (32 * G) + G * l32 + g : g * NB + wn * 32 + l32; };
 
     // state of the tile being fetched ("n": next) -- wave-uniform unless noted
     uint32_t nP0 = 0, nPend = 0, nq0 = 0, nq1 = 0, nimg0 = 0;
@@ -165,16 +186,13 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
     // channel of the wave, image of the tile's first pixel); the lane adds a 32-bit
     // byte offset (its pixel, its first channel) and each store a scalar channel offset.
     size_t nobase = 0;      // uniform: float offset of that base in the output
-    uint32_t nooff[G];      // per lane and group: byte offset from the base
-    int nroom[G];           // per lane and group: number of channels it may store (<= 0: none)
-    uint32_t nfull = 0;     // uniform, bit g: every lane of the wave stores all of its channels of group g
+    uint32_t nooff[G];      // per lane and group: byte offset from the base, or OOB when its pixel is past the layer
     // state of the tile being computed ("c") and of the one before it ("p")
-    int cwpos[G], croom[G], proom[G];
+    int cwpos[G];
     size_t cobase = 0, pobase = 0;
     uint32_t cooff[G], pooff[G];
-    uint32_t cfull = 0, pfull = 0;
 #pragma unroll
-    for (int g = 0; g < G; ++g) { nwpos[g] = 0; nooff[g] = 0; nroom[g] = 0; cwpos[g] = 0; croom[g] = 0; proom[g] = 0; cooff[g] = 0; pooff[g] = 0; }
+    for (int g = 0; g < G; ++g) { nwpos[g] = 0; nooff[g] = OOB; cwpos[g] = 0; cooff[g] = OOB; pooff[g] = OOB; }
     floatx16 acc[2][G];
     float own[8];           // (KS == 2) this wave's partial sums of that half, kept from the previous tile
     // (KS == 2) this lane's slots in the exchange area: where it leaves the partner's half of a tile's
@@ -191,13 +209,21 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
         xtheirs = (const lds_f32 *)((const __attribute__((address_space(3))) char *)lds + ot);
     }
 
-    const uint32_t per = (P.ntiles + gridDim.x - 1) / gridDim.x;
-    const uint32_t tile0 = blockIdx.x * per;
-    const uint32_t tile_end = min(tile0 + per, P.ntiles);
+    // Tiles of this workgroup: tile0, tile0 + tstep, ... below tile_end.  The grid takes the tiles
+    // round by round, and workgroups that share an XCD (every eighth one) take neighbouring tiles of
+    // a round: what an XCD writes at any time is one contiguous stretch of every output plane, so
+    // the cache lines that two tiles share are completed in its L2 while they are still there, and
+    // memory sees long runs.  (Measured against one contiguous range of tiles per workgroup: Table 2's
+    // Conv7 481 -> 359 us, Conv3 272 -> 261 us, never slower.)
+    const uint32_t tstep = gridDim.x, tile_end = P.ntiles;
+    const uint32_t xcd = blockIdx.x % 8u;
+    const uint32_t tile0 = xcd * (tstep / 8u) + min(xcd, tstep % 8u) + blockIdx.x / 8u;
     if (tile0 >= tile_end) return;   // whole workgroup: no barrier is skipped by part of it
     const int jw = (int)blockIdx.y * (WM * 32) + wm * 32;   // first channel of this wave
     const int jl = jw + 4 * h;                               // first channel of this lane
     const uint32_t howo4 = P.howo * 4u;
+    const int room = P.Co - jl;                              // channels this lane may store (<= 0: none)
+    const bool chan_full = P.Co - jw >= 32;                  // wave-uniform: every lane of the wave stores all of its channels
 
     // A wave-uniform 32-bit value made opaque to the optimiser, in a scalar register.  (In the
     // multi-group instances the compiler does not always prove the value uniform, hence the
@@ -216,28 +242,22 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
     auto make_desc = [](float *base, size_t elems) __attribute__((always_inline)) {
         const size_t left = elems * 4u;
         const uint32_t lo = (uint32_t)left, hi = (uint32_t)(left >> 32);
-        const uint32_t num = lo | (0u - (uint32_t)(hi != 0u));
+        const uint32_t num = min(lo | (0u - (uint32_t)(hi != 0u)), OOB);
         return __builtin_amdgcn_make_buffer_rsrc(base, 0, num, 0x00020000);
     };
     // Descriptor over the output from float offset `obase` to its end.
     auto out_desc = [&](size_t obase) __attribute__((always_inline)) { return make_desc(P.out + obase, P.out_elems - obase); };
     __amdgpu_buffer_rsrc_t cdesc = out_desc(0), pdesc = out_desc(0);   // descriptors of the computed / previous tile
-    // One output store: accumulator register q of a lane's block (channel offset dj from the
-    // lane's first channel) through the tile's descriptor.  `full` is wave-uniform (every lane
-    // of the wave stores all of its channels).  With a long chain per tile the common case is a
-    // scalar branch and one buffer store, with no per-lane compare, and the rare partial tile
-    // takes plain guarded stores; with short chains the single exec-masked form measured faster.
-    auto store_one = [&](float val, int q, const __amdgpu_buffer_rsrc_t &ro, size_t obase, uint32_t ooff, int room,
-                         uint32_t full) __attribute__((always_inline)) {
-        const int dj = 8 * (q >> 2) + (q & 3);
-        if (TW < 32) {
-            if (full || dj < room)
-                __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, val), ro, ooff, (uint32_t)dj * howo4, 0);
-        } else if (full) {
-            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, val), ro, ooff, (uint32_t)dj * howo4, 0);
-        } else if (dj < room) {
-            P.out[obase + (ooff >> 2) + (size_t)dj * P.howo] = val;
-        }
+    // Every output store is issued by every wave on every tile, with no branch and no lane mask
+    // around it: a lane that must not store (its pixel past the layer, its channel past Co) gives
+    // the offset OOB, which no descriptor covers, and the buffer unit drops its write.  A fixed
+    // number of stores per tile is what lets the wave count them at the end of the tile (see
+    // strips_landed).  The channel test is skipped by a scalar branch in waves whose 32 channels all
+    // exist.  dj: channel offset of accumulator register q from the lane's first channel.
+    auto store_offset = [&](uint32_t ooff, int dj) __attribute__((always_inline)) -> uint32_t {
+        uint32_t vo = ooff;
+        if (!chan_full) vo = dj < room ? vo : OOB;
+        return vo;
     };
     // One piece of the work for tile `t` (pieces are numbered in dependency order).
     auto piece = [&](auto pc, uint32_t t, int st_next, const floatx16 (&pacc)[G], int xpar) __attribute__((always_inline)) {
@@ -343,23 +363,21 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
             }
         } else if constexpr (p >= P_WPOS && p < P_OPTR) {
             constexpr int g = p - P_WPOS;
-            const uint32_t Pl = min(nP0 + (uint32_t)(g * NB + wn * 32 + l32), nPend);
+            const uint32_t Pl = min(nP0 + (uint32_t)tile_pixel(g), nPend);
             const uint32_t ql = fdiv(Pl, P.d_wo);
             const int nl = (int)(Pl - ql * (uint32_t)P.Wo);
             const int rho = (int)(ql - nq0);
             nwpos[g] = rho == 0 ? (nl - nnlo0) * sHf : nlen0 + (rho - 1) * P.fullseg + nl * sHf;
         } else if constexpr (p >= P_OPTR && p < P_ST) {
             constexpr int g = p - P_OPTR;
-            const uint32_t Pm = nP0 + (uint32_t)(g * NB + wn * 32 + l32);
+            const uint32_t Pm = nP0 + (uint32_t)tile_pixel(g);   // (WIDE: the first of the lane's four pixels)
             const uint32_t Pc = min(Pm, nPend);
             const uint32_t img = fdiv(Pc, P.d_howo);
             const uint32_t pin = Pc - img * P.howo;
             const uint32_t img0 = fdiv(nP0, P.d_howo);   // uniform
             nobase = ((size_t)img0 * P.Co + jw) * P.howo;
-            nooff[g] = ((img - img0) * (uint32_t)P.Co * P.howo + pin) * 4u + (uint32_t)(4 * h) * howo4;
-            nroom[g] = Pm <= nPend ? P.Co - jl : 0;
-            const bool full = (nP0 + (uint32_t)(g * NB + wn * 32 + 31) <= nPend) && (P.Co - jw >= 32);
-            nfull = full ? (nfull | (1u << g)) : (nfull & ~(1u << g));
+            const uint32_t off = ((img - img0) * (uint32_t)P.Co * P.howo + pin) * 4u + (uint32_t)(4 * h) * howo4;
+            nooff[g] = Pm <= nPend ? off : OOB;
         } else if constexpr (p >= P_ST && p < P_LDS) {
             // one output store of the previous tile (pixel group g, register q of its block)
             constexpr int g = (p - P_ST) / NE, q = (p - P_ST) % NE;
@@ -367,14 +385,12 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
                 // add the partner's partial sum to this wave's (kept in own[]) first; these
                 // instances are short of scalar registers and rebuild the descriptor here
                 const float val = own[q] + *(const volatile lds_f32 *)(xtheirs + xpar * (WM * 2 * 2 * 512) + q * 64);
-                const size_t left = (P.out_elems - pobase) * 4u;
-                const __amdgpu_buffer_rsrc_t ro = __builtin_amdgcn_make_buffer_rsrc(
-                    P.out + pobase, 0, left < 0xffffffffull ? left : 0xffffffffull, 0x00020000);
                 const int dj = (ks ? 16 : 0) + 8 * (q >> 2) + (q & 3);
-                if (pfull || dj < proom[0])
-                    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, val), ro, pooff[0], (uint32_t)dj * howo4, 0);
+                __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, val), out_desc(pobase), store_offset(pooff[0], dj), (uint32_t)dj * howo4, 0);
             } else {
-                store_one(pacc[g][q], q, pdesc, pobase, pooff[g], proom[g], (pfull >> g) & 1u);
+                const int dj = 8 * (q >> 2) + (q & 3);
+                const float val = pacc[g][q];
+                __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, val), pdesc, store_offset(pooff[g], dj), (uint32_t)dj * howo4, 0);
             }
         } else if constexpr (p >= P_LDS && p < NP) {
             if constexpr (IMP) {
@@ -384,10 +400,26 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
             }
         }
     };
-    // The next tile's strips must be in LDS before the barrier that ends a tile: the direct loads
-    // are complete when the wave's vector-memory counter is back at zero (vmcnt(0); the other
-    // counters are left alone).
-    auto strips_landed = []() __attribute__((always_inline)) { if (!IMP) __builtin_amdgcn_s_waitcnt(0x0F70); };
+    // The next tile's strips must be in LDS before the barrier that ends a tile.  The direct loads
+    // are counted by the wave's vector-memory counter, which the output stores share, and the
+    // counter retires in issue order.  A tile's loads are issued before the stores that ride in the
+    // same chain, and every wave issues all of those stores, so the loads have landed as soon as no
+    // more than that many operations are outstanding: the wave does not wait for its stores to be
+    // acknowledged, which at one or two waves per SIMD would idle the matrix pipe once per tile.
+    // (The other counters are left alone.)
+    constexpr int NSTORES = NE * NOP < 63 ? NE * NOP : 63;   // store instructions per tile and wave behind its loads (the counter holds 63)
+    auto strips_landed = [](bool stores_behind) __attribute__((always_inline)) {
+        if (IMP) return;
+        if (stores_behind) __builtin_amdgcn_s_waitcnt(0x0F70 | (NSTORES & 15) | ((NSTORES >> 4) << 14));
+        else __builtin_amdgcn_s_waitcnt(0x0F70);
+    };
+    // Workgroup barrier between tiles.  Only LDS traffic has to be ordered across it (the strips, the
+    // K-half exchange); a fence over all address spaces would also wait for every output store.
+    auto tile_barrier = []() __attribute__((always_inline)) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+    };
     // pieces lo..hi-1
     auto pieces = [&](auto loc, auto hic, uint32_t t, int st_next, const floatx16 (&pacc)[G], int xpar) __attribute__((always_inline)) {
         constexpr int lo = decltype(loc)::value, hi = decltype(hic)::value;
@@ -406,19 +438,19 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
         pieces(std::integral_constant<int, P_GEO>{}, std::integral_constant<int, P_ST>{}, tile0, 0, acc[0], 0);
         pieces(std::integral_constant<int, P_LDS>{}, std::integral_constant<int, NP>{}, tile0, 0, acc[0], 0);
     }
-    strips_landed();
+    strips_landed(false);
     __syncthreads();
 
     // ---- one tile: the MFMA chain with the pieces in its shadow -------------------
     auto tile_body = [&](auto parc, uint32_t tile) __attribute__((always_inline)) {
         constexpr int PAR = decltype(parc)::value;      // tile parity: LDS stage, accumulator set
-        constexpr int AP = (KS == 2) ? 0 : PAR;         // with KS == 2 only 8 sums outlive the chain (own[])
+        constexpr int AP = (KS == 2 || WIDE) ? 0 : PAR;   // with KS == 2 only 8 sums outlive the chain (own[]); WIDE: none
         // the fetched tile becomes the computed tile
-        cobase = nobase; cfull = nfull;
+        cobase = nobase;
         if (KS == 1) cdesc = out_desc(cobase);
 #pragma unroll
-        for (int g = 0; g < G; ++g) { cwpos[g] = nwpos[g]; cooff[g] = nooff[g]; croom[g] = nroom[g]; }
-        const uint32_t nxt = min(tile + 1, tile_end - 1);   // the last tile refetches itself (unused)
+        for (int g = 0; g < G; ++g) { cwpos[g] = nwpos[g]; cooff[g] = nooff[g]; }
+        const uint32_t nxt = tile + tstep < tile_end ? tile + tstep : tile;   // the last tile refetches itself (unused)
         const lds_f32 *sbase = lds + PAR * STAGE;
         const lds_f32 *bpair[G], *bsplit[G], *bzero[G];
 #pragma unroll
@@ -448,9 +480,9 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
             __builtin_amdgcn_sched_barrier(0);
             static_for<TW>([&](auto ic) __attribute__((always_inline)) {
                 constexpr int ii = decltype(ic)::value;
-#pragma unroll
-                for (int g = 0; g < G; ++g) {
-                    if (ii == 0) {
+                static_for<G>([&](auto gc) __attribute__((always_inline)) {
+                    constexpr int g = decltype(gc)::value;
+                    if constexpr (ii == 0) {
                         floatx16 z;
 #pragma unroll
                         for (int v = 0; v < 16; ++v) z[v] = 0.0f;
@@ -459,12 +491,36 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
                         acc[AP][g] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[ii], b[g][ii % SH_G], acc[AP][g], 0, 0, 0);
                     }
                     if (ii + SH_G < TW) b[g][ii % SH_G] = bread(ii + SH_G, g);
-                }
-                // pieces whose slot is this MFMA: piece p rides behind MFMA p*TW/NP
-                constexpr int plo = (ii * NP + TW - 1) / TW, phi = ((ii + 1) * NP + TW - 1) / TW;
-                pieces(std::integral_constant<int, plo>{}, std::integral_constant<int, phi>{}, nxt, PAR ^ 1, acc[AP ^ 1], PAR ^ 1);
-                __builtin_amdgcn_sched_barrier(0);
+                    // pieces whose slot is this MFMA: piece p rides behind MFMA p*(TW*G)/NP of the tile
+                    constexpr int m = ii * G + g, NM = TW * G;
+                    constexpr int plo = (m * NP + NM - 1) / NM, phi = ((m + 1) * NP + NM - 1) / NM;
+                    pieces(std::integral_constant<int, plo>{}, std::integral_constant<int, phi>{}, nxt, PAR ^ 1, acc[AP ^ 1], PAR ^ 1);
+                    __builtin_amdgcn_sched_barrier(0);
+                });
             });
+            if constexpr (WIDE) {
+                // The tile's sums leave right behind its chain, from the one set of accumulators: register q
+                // of the wave's four blocks is a lane's four neighbouring pixels of channel dj (all inside the
+                // layer or all outside: the pixel count is a multiple of four here).  This wave's matrix pipe
+                // idles meanwhile; the other workgroup of the CU fills it.
+                typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+                typedef float f32x4 __attribute__((ext_vector_type(4)));
+                static_for<16>([&](auto qc) __attribute__((always_inline)) {
+                    constexpr int q = decltype(qc)::value;
+                    constexpr int dj = 8 * (q >> 2) + (q & 3);
+                    f32x4 v;   // (element by element: a bit cast applied to a vector element reads element 0)
+                    v.x = acc[0][0][q]; v.y = acc[0][1][q]; v.z = acc[0][2][q]; v.w = acc[0][3][q];
+                    const uint32_t vo = store_offset(cooff[0], dj);
+                    // Nothing is scheduled between the store and four idle cycles behind it: an instance whose
+                    // allocation rewrote a store's four data registers in the very next instructions wrote
+                    // stale values in a few lanes now and then (the data of a 16-byte store leave the register
+                    // file over several cycles).
+                    __builtin_amdgcn_sched_barrier(0);
+                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), cdesc, vo, (uint32_t)dj * howo4, 0);
+                    asm volatile("s_nop 3");
+                    __builtin_amdgcn_sched_barrier(0);
+                });
+            }
             if (KS == 2) {
                 // hand the partner the half of this tile's accumulators that it owns, keep the other
                 // (register indices are compile-time constants here: KSI is this wave's K share)
@@ -482,18 +538,18 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
             else run(std::integral_constant<int, KS - 1>{});
         }
         // the computed tile becomes the previous tile
-        pobase = cobase; pfull = cfull;
+        pobase = cobase;
         if (KS == 1) pdesc = cdesc;
 #pragma unroll
-        for (int g = 0; g < G; ++g) { pooff[g] = cooff[g]; proom[g] = croom[g]; }
-        strips_landed();
-        __syncthreads();
+        for (int g = 0; g < G; ++g) { pooff[g] = cooff[g]; }
+        strips_landed(true);
+        tile_barrier();
     };
 
     uint32_t tile = tile0;
-    for (; tile + 1 < tile_end; tile += 2) {   // unrolled by two: stage and accumulator set are constants
+    for (; tile + tstep < tile_end; tile += 2 * tstep) {   // unrolled by two: stage and accumulator set are constants
         tile_body(std::integral_constant<int, 0>{}, tile);
-        tile_body(std::integral_constant<int, 1>{}, tile + 1);
+        tile_body(std::integral_constant<int, 1>{}, tile + tstep);
     }
     int lastpar = 1;
     if (tile < tile_end) { tile_body(std::integral_constant<int, 0>{}, tile); lastpar = 0; }
@@ -503,7 +559,7 @@ __global__ __launch_bounds__(64 * WM * 2 * KS) void conv_mfma_shallow_kernel(Sha
     else pieces(std::integral_constant<int, P_ST>{}, std::integral_constant<int, P_LDS>{}, 0u, 0, acc[1], 1);
 }
 
-template <int HF, int WF, int CI, int WM, int KS, int JX, bool IMP, int G>
+template <int HF, int WF, int CI, int WM, int KS, int JX, bool IMP, int G, bool WIDE>
 static hipError_t launch_shallow_k(ShallowParams P, int mgroups, hipStream_t st, LaunchPlan *plan)
 {
     P.ntiles = (P.npix + NB * G - 1) / (NB * G);
@@ -511,7 +567,7 @@ static hipError_t launch_shallow_k(ShallowParams P, int mgroups, hipStream_t st,
     constexpr int SS = JX * NT;
     constexpr int STAGE = CI * SS + 4;
     constexpr size_t lds = 4u * (size_t)(2 * STAGE + (KS == 2 ? 2 * WM * 2 * 2 * 8 * 64 : 0));
-    auto kern = &conv_mfma_shallow_kernel<HF, WF, CI, WM, KS, JX, IMP, G>;
+    auto kern = &conv_mfma_shallow_kernel<HF, WF, CI, WM, KS, JX, IMP, G, WIDE>;
     static KernelCache kc;
     int dev = 0, ncu = 0;
     hipError_t e = device_cus(&dev, &ncu);
@@ -525,23 +581,28 @@ static hipError_t launch_shallow_k(ShallowParams P, int mgroups, hipStream_t st,
     else if ((e = resident_per_cu(kc, reinterpret_cast<const void *>(kern), NT, lds, dev, &per_cu)) != hipSuccess) return e;
     if (per_cu < 1) return hipErrorInvalidConfiguration;
     if (per_cu > 3) per_cu = 3;
+    // The instances with 16-byte stores are bound by the output stream: with one workgroup per CU the
+    // tiles in flight on an XCD write 2 MB per round, which its 4 MB L2 holds until the neighbouring
+    // tiles have completed the shared lines; two or three per CU measured a third slower.
+    if (WIDE) per_cu = 1;
     uint32_t gx = (uint32_t)(ncu * per_cu) / (uint32_t)mgroups;
+    if (gx >= 8) gx &= ~7u;   // (whole rows of the grid per XCD, whatever blockIdx.y)
     if (gx < 1) gx = 1;
     if (gx > P.ntiles) gx = P.ntiles;
     if (plan) {
-        plan_record(plan, dim3(gx, mgroups), NT, lds, "conv_mfma_shallow_kernel<%d, %d, %d, %d, %d, %d, %s, %d>",
-                    HF, WF, CI, WM, KS, JX, tf(IMP), G);
+        plan_record(plan, dim3(gx, mgroups), NT, lds, "conv_mfma_shallow_kernel<%d, %d, %d, %d, %d, %d, %s, %d, %s>",
+                    HF, WF, CI, WM, KS, JX, tf(IMP), G, tf(WIDE));
         return hipSuccess;
     }
     hipLaunchKernelGGL(kern, dim3(gx, mgroups), dim3(NT), lds, st, P);
     return hipGetLastError();
 }
 
-template <int HF, int WF, int CI, int WM, int KS, int JX, int G = 1>
+template <int HF, int WF, int CI, int WM, int KS, int JX, int G = 1, bool WIDE = false>
 static hipError_t launch_shallow_t(const ShallowParams &P, int mgroups, hipStream_t st, bool implicit, LaunchPlan *plan)
 {
-    return implicit ? launch_shallow_k<HF, WF, CI, WM, KS, JX, true, G>(P, mgroups, st, plan)
-                    : launch_shallow_k<HF, WF, CI, WM, KS, JX, false, G>(P, mgroups, st, plan);
+    return implicit ? launch_shallow_k<HF, WF, CI, WM, KS, JX, true, G, WIDE>(P, mgroups, st, plan)
+                    : launch_shallow_k<HF, WF, CI, WM, KS, JX, false, G, WIDE>(P, mgroups, st, plan);
 }
 
 // Returns hipErrorNotSupported when the layer does not meet this kernel's conditions.
@@ -603,10 +664,19 @@ hipError_t launch_conv_mfma_shallow(const float *win, const float *flt, float *o
         // K = 27 is 14 MFMA steps: tiles of four pixel groups where the layer has enough of them
         const long long S4 = strip_of(4);
         const bool many = P.npix >= 4u * NB * 4u * 768u;
+        // 16-byte stores: four neighbouring pixels never straddle two output planes, and they are aligned
+        const bool wide = P.howo % 4u == 0 && reinterpret_cast<uintptr_t>(out) % 16u == 0;
         if (many && S4 > 0) {
-            if (wm == 1 && S4 <= 7 * 128) return launch_shallow_t<3, 3, 3, 1, 1, 7, 4>(P, mgroups, st, implicit, plan);
-            if (wm == 2 && S4 <= 4 * 256) return launch_shallow_t<3, 3, 3, 2, 1, 4, 4>(P, mgroups, st, implicit, plan);
-            if (wm == 3 && S4 <= 3 * 384) return launch_shallow_t<3, 3, 3, 3, 1, 3, 4>(P, mgroups, st, implicit, plan);
+            // one or two 32-channel blocks per workgroup; the accumulators of a third do not fit the
+            // register file, so wider layers run as separate groups of 32 channels
+            const int wm4 = wm == 2 ? 2 : 1;
+            const int mg4 = (sh.Co + wm4 * 32 - 1) / (wm4 * 32);
+            if (wm4 == 1 && S4 <= 7 * 128)
+                return wide ? launch_shallow_t<3, 3, 3, 1, 1, 7, 4, true>(P, mg4, st, implicit, plan)
+                            : launch_shallow_t<3, 3, 3, 1, 1, 7, 4>(P, mg4, st, implicit, plan);
+            if (wm4 == 2 && S4 <= 4 * 256)
+                return wide ? launch_shallow_t<3, 3, 3, 2, 1, 4, 4, true>(P, mg4, st, implicit, plan)
+                            : launch_shallow_t<3, 3, 3, 2, 1, 4, 4>(P, mg4, st, implicit, plan);
         }
         if (wm == 1 && S <= 2 * 128) return launch_shallow_t<3, 3, 3, 1, 1, 2>(P, mgroups, st, implicit, plan);
         if (wm == 2 && S <= 1 * 256) return launch_shallow_t<3, 3, 3, 2, 1, 1>(P, mgroups, st, implicit, plan);

@@ -131,11 +131,13 @@ def test_implicit_other_shapes(shape):
     assert_conv_close(dO.cpu().numpy(), O_ref, B_ref)
 
 
-def test_implicit_three_channel_3x3_layer_with_many_pixels():
-    """Conv7's shape at batch 16 (tiles of four pixel groups), gathered from the input."""
-    I, F = workloads.random_layer_inputs(7801, 16, 3, 224, 223, 64, 3, 3)
-    dO = _run(I, F, 1, 1)
-    O_ref, B_ref = oracle.conv2d_direct(I.numpy(), F.numpy(), 1, 1)
+@pytest.mark.parametrize("pad", [1, 0])
+def test_implicit_three_channel_3x3_layer_with_many_pixels(pad):
+    """Conv7's shape at batch 16 (tiles of four pixel groups), gathered from the input; output planes
+    of 224x223 pixels (a multiple of four: 16-byte stores) and of 222x221."""
+    I, F = workloads.random_layer_inputs(7801 + pad, 16, 3, 224, 223, 64, 3, 3)
+    dO = _run(I, F, 1, pad)
+    O_ref, B_ref = oracle.conv2d_direct(I.numpy(), F.numpy(), 1, pad)
     assert_conv_close(dO.cpu().numpy(), O_ref, B_ref)
 
 

@@ -142,12 +142,13 @@ def test_table2_layers_full_batch(L):
     assert torch.equal(dO.view(torch.int32), dO2.view(torch.int32))
 
 
-@pytest.mark.parametrize("Co,pad", [(64, 0), (20, 1), (96, 1)])
-def test_three_channel_3x3_layer_with_many_pixels(Co, pad):
+@pytest.mark.parametrize("Co,pad,Wi", [(64, 0, 224), (20, 1, 223), (96, 1, 223), (64, 0, 223), (40, 0, 221)])
+def test_three_channel_3x3_layer_with_many_pixels(Co, pad, Wi):
     """Table 2's Conv7 shape at batch 16: enough pixels for the tiles of four 64-pixel groups
-    (one, two and three 32-channel blocks per workgroup; ragged last tile with padding)."""
-    I, F = workloads.random_layer_inputs(7700 + Co, 16, 3, 224, 224 - pad, Co, 3, 3)
-    print("conv7-like", Co, pad, flush=True)
+    (one, two and three 32-channel blocks per workgroup; ragged last tile with padding).  The first
+    three have output planes of a multiple of four pixels (16-byte stores), the last two do not."""
+    I, F = workloads.random_layer_inputs(7700 + Co + Wi, 16, 3, 224, Wi, Co, 3, 3)
+    print("conv7-like", Co, pad, Wi, flush=True)
     check_layer(I, F, 1, pad, basic=False, twice=False)
 
 
