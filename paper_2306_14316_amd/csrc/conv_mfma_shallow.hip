@@ -256,7 +256,10 @@ void conv_mfma_shallow_kernel(ShallowParams P)
     // exist.  dj: channel offset of accumulator register q from the lane's first channel.
     auto store_offset = [&](uint32_t ooff, int dj) __attribute__((always_inline)) -> uint32_t {
         uint32_t vo = ooff;
-        if (!chan_full) vo = dj < room ? vo : OOB;
+        if (__builtin_expect(!chan_full, 0)) {
+            vo = dj < room ? vo : OOB;
+            asm volatile("" : "+v"(vo));   // (keeps this a branch: as a select it is one more vector instruction per store)
+        }
         return vo;
     };
     // One piece of the work for tile `t` (pieces are numbered in dependency order).
