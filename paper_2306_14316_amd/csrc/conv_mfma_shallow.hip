@@ -366,11 +366,27 @@ void conv_mfma_shallow_kernel(ShallowParams P)
             }
         } else if constexpr (p >= P_WPOS && p < P_OPTR) {
             constexpr int g = p - P_WPOS;
-            const uint32_t Pl = min(nP0 + (uint32_t)tile_pixel(g), nPend);
-            const uint32_t ql = fdiv(Pl, P.d_wo);
-            const int nl = (int)(Pl - ql * (uint32_t)P.Wo);
-            const int rho = (int)(ql - nq0);
-            nwpos[g] = rho == 0 ? (nl - nnlo0) * sHf : nlen0 + (rho - 1) * P.fullseg + nl * sHf;
+            if constexpr (WIDE) {
+                // The lane's four neighbouring pixels: one division for the first, the others follow it in its
+                // row or (rows are at least four pixels long here) start the next row's strip.  A lane whose
+                // pixels are past the layer computes the layer's last four again (never stored).
+                if constexpr (g == 0) {
+                    const uint32_t Pl = min(nP0 + (uint32_t)tile_pixel(0), nPend - 3u);
+                    const uint32_t ql = fdiv(Pl, P.d_wo);
+                    const int nl = (int)(Pl - ql * (uint32_t)P.Wo);
+                    const int rho = (int)(ql - nq0);
+                    const int w0 = (rho == 0 ? -nnlo0 * sHf : nlen0 + (rho - 1) * P.fullseg) + nl * sHf;
+                    const int wrapped = nlen0 + rho * P.fullseg + (nl - P.Wo) * sHf;   // counted from the next row's strip
+#pragma unroll
+                    for (int gg = 0; gg < G; ++gg) nwpos[gg] = (nl + gg >= P.Wo ? wrapped : w0) + gg * sHf;
+                }
+            } else {
+                const uint32_t Pl = min(nP0 + (uint32_t)tile_pixel(g), nPend);
+                const uint32_t ql = fdiv(Pl, P.d_wo);
+                const int nl = (int)(Pl - ql * (uint32_t)P.Wo);
+                const int rho = (int)(ql - nq0);
+                nwpos[g] = rho == 0 ? (nl - nnlo0) * sHf : nlen0 + (rho - 1) * P.fullseg + nl * sHf;
+            }
         } else if constexpr (p >= P_OPTR && p < P_ST) {
             constexpr int g = p - P_OPTR;
             const uint32_t Pm = nP0 + (uint32_t)tile_pixel(g);   // (WIDE: the first of the lane's four pixels)
@@ -508,21 +524,26 @@ void conv_mfma_shallow_kernel(ShallowParams P)
                 // idles meanwhile; the other workgroup of the CU fills it.
                 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
                 typedef float f32x4 __attribute__((ext_vector_type(4)));
-                static_for<16>([&](auto qc) __attribute__((always_inline)) {
-                    constexpr int q = decltype(qc)::value;
-                    constexpr int dj = 8 * (q >> 2) + (q & 3);
-                    f32x4 v;   // (element by element: a bit cast applied to a vector element reads element 0)
-                    v.x = acc[0][0][q]; v.y = acc[0][1][q]; v.z = acc[0][2][q]; v.w = acc[0][3][q];
-                    const uint32_t vo = store_offset(cooff[0], dj);
-                    // Nothing is scheduled between the store and four idle cycles behind it: an instance whose
-                    // allocation rewrote a store's four data registers in the very next instructions wrote
-                    // stale values in a few lanes now and then (the data of a 16-byte store leave the register
-                    // file over several cycles).
-                    __builtin_amdgcn_sched_barrier(0);
-                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), cdesc, vo, (uint32_t)dj * howo4, 0);
-                    asm volatile("s_nop 3");
-                    __builtin_amdgcn_sched_barrier(0);
-                });
+                auto store_all = [&](auto fullc) __attribute__((always_inline)) {
+                    static_for<16>([&](auto qc) __attribute__((always_inline)) {
+                        constexpr int q = decltype(qc)::value;
+                        constexpr int dj = 8 * (q >> 2) + (q & 3);
+                        f32x4 v;   // (element by element: a bit cast applied to a vector element reads element 0)
+                        v.x = acc[0][0][q]; v.y = acc[0][1][q]; v.z = acc[0][2][q]; v.w = acc[0][3][q];
+                        uint32_t vo = cooff[0];
+                        if constexpr (!decltype(fullc)::value) vo = dj < room ? vo : OOB;
+                        // Nothing is scheduled between the store and four idle cycles behind it: an instance whose
+                        // allocation rewrote a store's four data registers in the very next instructions wrote
+                        // stale values in a few lanes now and then (the data of a 16-byte store leave the register
+                        // file over several cycles).
+                        __builtin_amdgcn_sched_barrier(0);
+                        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), cdesc, vo, (uint32_t)dj * howo4, 0);
+                        asm volatile("s_nop 3");
+                        __builtin_amdgcn_sched_barrier(0);
+                    });
+                };
+                if (chan_full) store_all(std::true_type{});   // (one branch per tile: all 32 channels of the wave exist)
+                else store_all(std::false_type{});
             }
             if (KS == 2) {
                 // hand the partner the half of this tile's accumulators that it owns, keep the other
@@ -668,7 +689,7 @@ hipError_t launch_conv_mfma_shallow(const float *win, const float *flt, float *o
         const long long S4 = strip_of(4);
         const bool many = P.npix >= 4u * NB * 4u * 768u;
         // 16-byte stores: four neighbouring pixels never straddle two output planes, and they are aligned
-        const bool wide = P.howo % 4u == 0 && reinterpret_cast<uintptr_t>(out) % 16u == 0;
+        const bool wide = P.howo % 4u == 0 && sh.Wo >= 4 && reinterpret_cast<uintptr_t>(out) % 16u == 0;
         if (many && S4 > 0) {
             // one or two 32-channel blocks per workgroup; the accumulators of a third do not fit the
             // register file, so wider layers run as separate groups of 32 channels
