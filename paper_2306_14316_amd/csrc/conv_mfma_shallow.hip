@@ -3,19 +3,23 @@
 // Conv1-Conv3/Conv7): K = Ci*Hf*Wf is small (27..363) while N = Ni*Ho*Wo is huge.
 //
 // Design (CDNA4's, not the paper's CUDA tiling):
-//   - persistent workgroups: each one walks a strided list of 64-pixel tiles;
+//   - persistent workgroups: the grid takes the 64-pixel tiles round by round, the
+//     workgroups of one XCD on neighbouring tiles (what an XCD writes at any time is
+//     one contiguous stretch of every output plane);
 //   - every wave keeps the A operand (its 32 filter rows, its share of K) in
 //     registers for the whole kernel -- the filter is read from memory once per
 //     wave, never staged per tile -- so each MFMA needs one LDS read only;
 //   - the B operand is the tile's contiguous im2win strips (Section 3.1) in LDS,
-//     double-buffered: the next tile's strips are loaded into registers while the
-//     matrix cores work and written to the other LDS stage at the end of the tile;
+//     double-buffered: the next tile's strips are copied into the other LDS stage by
+//     direct global-to-LDS loads while the matrix cores work;
 //   - K order: channel pairs ride the two lane halves of v_mfma_f32_32x32x2_f32
 //     ("pair" steps); an odd last channel is split in two halves of its window
 //     ("split" steps); every operand address is lane base + immediate;
 //   - when K is too large for one wave's registers (11x11x3 = 363) two waves
 //     share a 32x32 output block, each taking half of the K steps, and exchange
-//     half of their accumulators through LDS before the store (KS = 2).
+//     half of their accumulators through LDS before the store (KS = 2);
+//   - every output store is issued by every wave (masked lanes pass an offset the
+//     buffer unit rejects), so the wait for the strips can count past the stores.
 #include "conv_mfma_tile.h"
 #include "runtime_cache.h"
 

@@ -152,6 +152,23 @@ def test_three_channel_3x3_layer_with_many_pixels(Co, pad, Wi):
     check_layer(I, F, 1, pad, basic=False, twice=False)
 
 
+def test_three_channel_3x3_layer_output_off_16_byte_alignment():
+    """The Conv7 shape again with an output buffer that starts 4 bytes past a 16-byte boundary: the
+    16-byte stores are not used then, and the result is the same bit for bit."""
+    N, Co = 16, 64
+    I, F = workloads.random_layer_inputs(7790, N, 3, 224, 224, Co, 3, 3)
+    dW = run_transform(I, 3, 3, 1, 0)
+    dO = run_conv(dW, F, N, 3, 224, 224, 1, 0)
+    Ho, Wo = im2win.im2win_out_shape(224, 224, 3, 3, 1, 0)
+    buf = torch.full((N * Co * Ho * Wo + 1,), float("nan"), dtype=torch.float32, device="cuda")
+    dO2 = buf[1:].view(N, Co, Ho, Wo)
+    assert dO2.data_ptr() % 16 == 4
+    im2win.conv2d_im2win_fwd(dW, F.cuda(), dO2, N, 3, 224, 224, Co, 3, 3, 1, 0)
+    torch.cuda.synchronize()
+    assert torch.equal(dO.view(torch.int32), dO2.contiguous().view(torch.int32))
+    assert bool(torch.isnan(buf[0]))
+
+
 # (N, Ci, Hi, Wi, Co, Hf, Wf, s, p): short K loops and at least 2304 tiles, so that the pipelined
 # kernel gives every workgroup several tiles and runs its pipeline across tile boundaries
 MANY_TILE_SHAPES = [
