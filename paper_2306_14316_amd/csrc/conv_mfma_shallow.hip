@@ -654,8 +654,9 @@ hipError_t launch_conv_mfma_shallow(const float *win, const float *flt, float *o
     // 32-bit strip offsets: the rows of one tile must lie within 2 GiB of each other
     const long long span = (implicit ? (long long)sh.Ci * sh.Hi * sh.Wi : (long long)sh.Ci * sh.Ho * sh.rowlen) * 4LL * (SH_RMAX + 1);
     if (span >= (1LL << 31)) return hipErrorNotSupported;
-    // 32-bit output offsets from (image of the tile's first pixel, wave's first channel): up to two images ahead
-    if (((long long)sh.Co * (SH_RMAX + 1) + 64) * sh.Ho * sh.Wo * 4LL >= (1LL << 32)) return hipErrorNotSupported;
+    // 32-bit output offsets from (image of the tile's first pixel, wave's first channel): up to two images
+    // ahead, and all of them below the offset that stands for "no store"
+    if (((long long)sh.Co * (SH_RMAX + 1) + 64) * sh.Ho * sh.Wo * 4LL >= (long long)OOB) return hipErrorNotSupported;
 
     ShallowParams P;
     P.win = win; P.flt = flt; P.out = out;
