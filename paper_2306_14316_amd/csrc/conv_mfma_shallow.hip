@@ -154,16 +154,18 @@ void conv_mfma_shallow_kernel(ShallowParams P)
     // chain leaves the matrix pipe idle.  Everything a tile needs besides its MFMAs
     // is therefore cut into small pieces that ride inside the chain of the tile
     // before or after it:
-    //   chain of tile T carries   - geometry, offsets and global loads of tile T+1,
+    //   chain of tile T carries   - geometry, offsets and loads of tile T+1 (straight into the
+    //                               other LDS stage; the workspace-free variant loads into
+    //                               registers and writes LDS late in the chain, so that the
+    //                               loads have had most of it to arrive),
     //                             - window position / output pointer of tile T+1,
     //                             - the output stores of tile T-1 (with KS == 2 each one
-    //                               first adds the partner wave's partial sum from LDS),
-    //                             - the LDS writes of tile T+1's strips (late, so the
-    //                               loads have had most of the chain to arrive).
-    // Accumulators alternate between two register sets with the tile parity.
+    //                               first adds the partner wave's partial sum from LDS).
+    // Accumulators alternate between two register sets with the tile parity.  (The instances with
+    // 16-byte stores keep one set and store a tile right behind its own chain instead.)
     const int sHf = P.s * HF;
     constexpr int NIW = CI * JX;                 // strip words per thread and tile
-    constexpr int NL = (NIW + 1) / 2;            // pieces that load / store two words each
+    constexpr int NL = (NIW + 1) / 2;            // pieces that load (and, workspace-free, write to LDS) two words each
     constexpr int NE = (KS == 2) ? 8 : 16;       // output-store pieces
     constexpr int NOP = WIDE ? 1 : G;            // output positions a lane keeps per tile
     constexpr int NSTP = WIDE ? 0 : NE * G;      // store pieces that ride in the next tile's chain
