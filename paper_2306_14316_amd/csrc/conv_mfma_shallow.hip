@@ -245,9 +245,10 @@ void conv_mfma_shallow_kernel(ShallowParams P)
     };
     // Buffer descriptor over `elems` floats from `base`, its size saturated to 4 GiB - 1 with
     // word-sized scalar operations (a 64-bit compare would go to the vector ALU).
-    auto make_desc = [](float *base, size_t elems) __attribute__((always_inline)) {
+    auto make_desc = [&](float *base, size_t elems) __attribute__((always_inline)) {
         const size_t left = elems * 4u;
-        const uint32_t lo = (uint32_t)left, hi = (uint32_t)(left >> 32);
+        uint32_t lo = (uint32_t)left, hi = (uint32_t)(left >> 32);
+        pin(hi);   // (left alone, the two words are recombined into that 64-bit compare)
         const uint32_t num = min(lo | (0u - (uint32_t)(hi != 0u)), OOB);
         return __builtin_amdgcn_make_buffer_rsrc(base, 0, num, 0x00020000);
     };
