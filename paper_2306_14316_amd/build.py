@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libim2win.so")
 OBJDIR = os.path.join(HERE, "_build")
 SOURCES = ("api.hip", "transform.hip", "conv_basic.hip", "conv_mfma.hip", "conv_mfma_fast.hip", "conv_mfma_shallow.hip",
-           "baselines.hip", "probes.hip")
+           "conv_mfma_1x1.hip", "baselines.hip", "probes.hip")
 # Packed-fp32 VALU instructions are switched off for all device code.
 DEVICE_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
                 "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -371,6 +371,19 @@ __global__ __launch_bounds__(256) void conv_mfma_pipe_kernel(MfmaParams P)
         const float *bI = sS + b_base;
         // ---- pair steps: lanes 0-31 take channel 2j, lanes 32-63 channel 2j+1 ----
         const int npairs = nch >> 1;
+        if constexpr (HF_T == 1 && WF_T == 1) {
+            // 1x1, stride 1, a full block of 64 channels: the strip length is 64 and the filter pitch 65, so
+            // every operand address is lane base + immediate and the 32 steps unroll into one chain whose
+            // LDS reads run ahead of the MFMAs (the loop below waits for two fresh reads before every MFMA).
+            if (SP == 64 && cb == 64 && nch == 64) {
+                const float *bp = bI + h * 64;
+                const float *ap = aF + h;
+#pragma unroll
+                for (int pr = 0; pr < 32; ++pr)
+                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(ap[2 * pr], bp[2 * pr * 64], acc, 0, 0, 0);
+                continue;
+            }
+        }
         for (int pr = 0; pr < npairs; ++pr) {
             const float *bp = bI + (2 * pr + h) * SP;
             const float *ap = aF + (2 * pr + h) * khw;
@@ -562,6 +575,8 @@ hipError_t launch_conv_implicit(const float *in, const float *flt, float *out, c
     if (fe != hipErrorNotSupported) return fe;
     fe = launch_conv_mfma_fast(P, sh, blocks, st, true, 4, plan);
     if (fe != hipErrorNotSupported) return fe;
+    fe = launch_conv_mfma_1x1(in, flt, out, sh, st, plan);   // (a 1x1 layer's im2win tensor is its input)
+    if (fe != hipErrorNotSupported) return fe;
     fe = launch_generic(P, sh, blocks, st, plan);
     if (fe == hipErrorInvalidConfiguration) return launch_conv_direct(in, flt, out, sh, st, plan);
     return fe;
@@ -584,6 +599,8 @@ hipError_t launch_conv_mfma(const float *win, const float *flt, float *out, cons
         if (fe != hipErrorNotSupported) return fe;
     }
     if (variant == kVariantDefault) {
+        const hipError_t oe = launch_conv_mfma_1x1(win, flt, out, sh, st, plan);
+        if (oe != hipErrorNotSupported) return oe;
         const hipError_t pe = launch_generic_pipe(P, sh, blocks, st, plan);
         if (pe != hipErrorNotSupported) return pe;
     }

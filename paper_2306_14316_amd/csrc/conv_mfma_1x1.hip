@@ -1,0 +1,187 @@
+// 1x1 convolution (stride 1, no padding) on the fp32 matrix cores.  For such a layer the im2win
+// tensor of Eq. 2 has the input's own layout -- every window is one element, row m of the tensor is
+// row m of the input -- and the convolution is the GEMM O[Co x P] = F[Co x Ci] * I[Ci x P] over the
+// P = N*H*W pixels, with I read channel plane by channel plane.  The generic two-stage kernel runs
+// these layers at a third of the matrix peak: it copies its operands into LDS one word per lane, and
+// the address path of the memory pipeline takes four lanes per cycle whatever their width, so two
+// resident workgroups already saturate it.  This kernel moves the same bytes with 16-byte
+// direct-to-LDS loads (buffer_load_dwordx4 ... lds, new on gfx950):
+//   - tile 64 channels x 64 pixels, K blocks of 64 input channels, two LDS stages; the loads of
+//     block kb+1 are in flight while the matrix cores work on block kb; one barrier per block;
+//   - B (pixels): [channel][64 pixels], one wave instruction copies four channel rows (4 x 256
+//     contiguous bytes of four planes) into 1 KB of LDS; a lane's B read is base + immediate;
+//   - A (filter): [row][64 k], pitch 64 floats, the sixteen 16-byte chunks of a row stored at slot
+//     (chunk ^ (row & 7)) -- the permutation is applied to the source address of each lane, the
+//     LDS side of a load is always the wave's 1 KB in lane order -- so that the 16-byte A reads of
+//     eight neighbouring rows fall into eight different bank groups;
+//   - K order inside a block: step 4q+i multiplies channel 8q+i on lanes 0-31 with channel 8q+4+i
+//     on lanes 32-63, so one 16-byte A read serves four MFMAs of a lane half.
+// Conditions (the launcher checks them, other layers keep their kernels): Hf = Wf = 1, stride 1,
+// pad 0, Ci a multiple of 64, Co and the planes' pixel count multiples of four, 16-byte aligned tensors.
+#include "conv_mfma_tile.h"
+#include "runtime_cache.h"
+
+namespace im2win {
+
+typedef __attribute__((address_space(3))) void lds_void_t;
+typedef float float4v_t __attribute__((ext_vector_type(4)));
+
+constexpr int K1 = 64;                       // input channels per K block
+constexpr int STAGE1 = K1 * NB + MB * K1;    // floats per LDS stage: B [K1][NB], then A [MB][K1]
+
+struct OneByOneParams {
+    const float *in;     // [N][Ci][howo]
+    const float *flt;    // [Co][Ci]
+    MfmaParams T;        // the fields the shared epilogue reads (out, out_elems, Co, howo, d_howo)
+    int Ci;
+    uint32_t npix, howo, tiles_m;
+    size_t in_elems, flt_elems;
+    FastDiv d_howo, d_tm;
+};
+
+__global__ __launch_bounds__(256, 2) void conv_mfma_1x1_kernel(OneByOneParams P)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    float *lds = reinterpret_cast<float *>(smem);   // two stages
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave & 1, wn = wave >> 1;
+    const int h = lane >> 5, l32 = lane & 31;
+
+    const uint32_t lb = xcd_swizzle(blockIdx.x, gridDim.x);
+    const uint32_t tile_n = fdiv(lb, P.d_tm);
+    const uint32_t tile_m = lb - tile_n * P.tiles_m;
+    const int m0 = (int)tile_m * MB;
+    const uint32_t P0 = tile_n * NB;
+    const uint32_t Pend = min(P0 + NB - 1, P.npix - 1);
+
+    // ---- source offsets of this lane's 16-byte chunks (fixed for the whole kernel) ----
+    // B: lane = (channel of four: lane / 16, chunk of four pixels: lane % 16).  The tile's pixels may
+    // straddle images; a chunk never does (planes are a multiple of four pixels).  Chunks past the
+    // layer's last pixel re-read its last chunk (their outputs are never stored).
+    const uint32_t img0 = fdiv(P0, P.d_howo);
+    const size_t b_tile = (size_t)img0 * P.Ci * P.howo;            // floats: plane 0 of the tile's first image
+    uint32_t b_voff;
+    {
+        const uint32_t Pl = min(P0 + 4u * (uint32_t)(lane & 15), P.npix - 4u);
+        const uint32_t img = fdiv(Pl, P.d_howo);
+        const uint32_t pin = Pl - img * P.howo;
+        b_voff = ((img - img0) * (uint32_t)P.Ci * P.howo + pin + (uint32_t)(lane >> 4) * P.howo) * 4u;
+    }
+    // A: lane = (row of four: lane / 16, slot: lane % 16); instruction I of a wave covers rows 4I .. 4I+3,
+    // and (4I + r) & 7 = (4I & 4) | r, so the slot permutation has two forms, for even and odd I.
+    // Rows past Co re-read the last row (their accumulators are never stored).
+    uint32_t a_voff[2];
+    const uint32_t Ci4 = (uint32_t)P.Ci * 4u;
+#pragma unroll
+    for (int par = 0; par < 2; ++par) {
+        const int r = lane >> 4, slot = lane & 15;
+        const int chunk = slot ^ ((4 * par + r) & 7);
+        a_voff[par] = (uint32_t)r * Ci4 + (uint32_t)chunk * 16u;
+    }
+    auto desc = [](const float *base, size_t elems) __attribute__((always_inline)) {
+        const size_t left = elems * 4u;
+        return __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(base), 0,
+                                                 left < 0xffffffffull ? left : 0xffffffffull, 0x00020000);
+    };
+    const __amdgpu_buffer_rsrc_t rb = desc(P.in + b_tile, P.in_elems - b_tile);
+    const __amdgpu_buffer_rsrc_t ra = desc(P.flt, P.flt_elems);
+    const uint32_t plane4 = P.howo * 4u;
+
+    // K block kb on its way into stage st: wave w issues instructions w, w+4, w+8, w+12 of each operand
+    auto issue = [&](int kb, int st) __attribute__((always_inline)) {
+        float *sB = lds + st * STAGE1, *sA = sB + K1 * NB;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int I = wave + 4 * j;                       // channels 4I .. 4I+3 of the block
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (lds_void_t *)(sB + I * 256), 16, b_voff,
+                                                     (uint32_t)(kb * K1 + 4 * I) * plane4, 0, 0);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int I = wave + 4 * j;                       // filter rows 4I .. 4I+3 of the tile
+            const int row = min(m0 + 4 * I, P.T.Co - 4);      // (a tile's last rows: see above)
+            const uint32_t soff = (uint32_t)row * Ci4 + (uint32_t)kb * (K1 * 4);
+            // wave-uniform choice between the two slot permutations (I is uniform)
+            const uint32_t vo = (I & 1) ? a_voff[1] : a_voff[0];
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (lds_void_t *)(sA + I * 256), 16, vo, soff, 0, 0);
+        }
+    };
+
+    floatx16 acc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+
+    // operand bases of this lane, relative to a stage
+    const int row = wm * 32 + l32;                            // filter row of the tile
+    const int b_lane = wn * 32 + l32 + h * (4 * NB);          // pixel, plus the lane half's channel offset
+    const int a_lane = K1 * NB + row * K1;
+
+    const int nkb = P.Ci / K1;
+    issue(0, 0);
+    for (int kb = 0; kb < nkb; ++kb) {
+        const int st = kb & 1;
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's loads of block kb have landed
+        __syncthreads();                      // everyone's have, and stage st^1 is free again
+        if (kb + 1 < nkb) issue(kb + 1, st ^ 1);
+        const float *sS = lds + st * STAGE1;
+        const float *bp = sS + b_lane;
+        const float *ap = sS + a_lane;
+#pragma unroll
+        for (int q = 0; q < K1 / 8; ++q) {
+            // chunk 2q + h of the row sits at slot (2q + h) ^ (row & 7)
+            const float4v_t a = *reinterpret_cast<const float4v_t *>(ap + 4 * ((2 * q + h) ^ (row & 7)));
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, bp[(8 * q + 0) * NB], acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, bp[(8 * q + 1) * NB], acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, bp[(8 * q + 2) * NB], acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, bp[(8 * q + 3) * NB], acc, 0, 0, 0);
+        }
+    }
+    store_tile_desc(P.T, acc, P0, Pend, m0, wm, wn, h, l32);
+}
+
+// Returns hipErrorNotSupported when the layer does not meet this kernel's conditions.  `in` is the
+// im2win tensor of the layer, which for these layers is laid out exactly like the input.
+hipError_t launch_conv_mfma_1x1(const float *in, const float *flt, float *out, const Shape &sh,
+                                hipStream_t st, LaunchPlan *plan)
+{
+    if (sh.Hf != 1 || sh.Wf != 1 || sh.s != 1 || sh.p != 0) return hipErrorNotSupported;
+    if (sh.Ci % K1 != 0 || sh.Co % 4 != 0) return hipErrorNotSupported;   // (filter rows are copied four at a time)
+    const long long howo = (long long)sh.Ho * sh.Wo;
+    if (howo % 4 != 0) return hipErrorNotSupported;
+    if ((reinterpret_cast<uintptr_t>(in) | reinterpret_cast<uintptr_t>(flt)) % 16u != 0) return hipErrorNotSupported;
+    // 32-bit byte offsets: a tile's pixels span at most two consecutive images (plus one plane group
+    // per load), the filter is addressed from its start
+    if ((2LL * sh.Ci + 8) * howo * 4LL >= (1LL << 32)) return hipErrorNotSupported;
+    if ((long long)sh.Co * sh.Ci * 4LL >= (1LL << 32)) return hipErrorNotSupported;
+    if (howo < NB && (NB / howo + 2) * (long long)sh.Ci * howo * 4LL >= (1LL << 32)) return hipErrorNotSupported;
+
+    OneByOneParams P;
+    P.in = in; P.flt = flt;
+    P.Ci = sh.Ci;
+    P.npix = (uint32_t)sh.npix;
+    P.howo = (uint32_t)howo;
+    P.tiles_m = (uint32_t)((sh.Co + MB - 1) / MB);
+    P.in_elems = (size_t)sh.N * sh.Ci * (size_t)howo;
+    P.flt_elems = (size_t)sh.Co * sh.Ci;
+    P.d_howo = make_fastdiv(P.howo);
+    P.d_tm = make_fastdiv(P.tiles_m);
+    P.T = MfmaParams{};
+    P.T.out = out; P.T.Co = sh.Co; P.T.howo = P.howo; P.T.d_howo = P.d_howo;
+    P.T.out_elems = (size_t)sh.npix * sh.Co;
+    // (the epilogue's 32-bit output offsets: a tile's pixels within 4 GiB of its first image's first channel)
+    if ((((long long)(howo < NB ? NB / howo + 2 : 2)) * sh.Co + 64) * howo * 4LL >= (1LL << 32)) return hipErrorNotSupported;
+    const uint32_t blocks = ((P.npix + NB - 1) / NB) * P.tiles_m;
+    constexpr size_t lds = 2u * STAGE1 * sizeof(float);
+    if (plan) { plan_record(plan, dim3(blocks), 256, lds, "conv_mfma_1x1_kernel"); return hipSuccess; }
+    static KernelCache kc;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = allow_dynamic_lds(kc, reinterpret_cast<const void *>(&conv_mfma_1x1_kernel), lds, dev);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(conv_mfma_1x1_kernel, dim3(blocks), dim3(256), lds, st, P);
+    return hipGetLastError();
+}
+
+}  // namespace im2win

@@ -152,6 +152,43 @@ def test_three_channel_3x3_layer_with_many_pixels(Co, pad, Wi):
     check_layer(I, F, 1, pad, basic=False, twice=False)
 
 
+# (N, Ci, Hi, Wi, Co): 1x1 layers, stride 1, no padding; the second field of each pair says whether the
+# dedicated 1x1 kernel takes the layer (Ci a multiple of 64, Co and the plane size multiples of four)
+ONE_BY_ONE_SHAPES = [
+    ((2, 64, 8, 8, 64), True),       # one K block, one tile per image
+    ((3, 128, 14, 14, 100), True),   # two K blocks, ragged last tile, a partial block of output channels
+    ((5, 64, 6, 6, 68), True),       # planes of 36 pixels: a tile spans three images
+    ((1, 192, 10, 10, 8), True),     # three K blocks, eight output channels
+    ((8, 256, 28, 28, 256), True),   # four K blocks, four channel blocks
+    ((2, 64, 2, 2, 64), True),       # planes of four pixels, one ragged tile over both images
+    ((3, 64, 7, 7, 64), False),      # 49 pixels per plane
+    ((2, 64, 8, 8, 66), False),      # 66 output channels
+    ((2, 96, 8, 8, 64), False),      # 96 input channels
+]
+
+
+@pytest.mark.parametrize("dims,dedicated", ONE_BY_ONE_SHAPES, ids=lambda v: "x".join(map(str, v)) if isinstance(v, tuple) else str(v))
+def test_one_by_one_layers(dims, dedicated):
+    """1x1 convolutions: a plain GEMM over the channel planes (the im2win tensor is the input's own
+    layout); both calls and the workspace-free call, every element, bit-identical between the two."""
+    N, Ci, Hi, Wi, Co = dims
+    shape = (N, Ci, Hi, Wi, Co, 1, 1, 1, 0)
+    name = im2win.conv2d_im2win_fwd_launch_info(*shape)["kernel"]
+    assert (name == "conv_mfma_1x1_kernel") == dedicated, name
+    I, F = workloads.random_layer_inputs(8800 + sum(dims), N, Ci, Hi, Wi, Co, 1, 1)
+    print("1x1", dims, name, flush=True)
+    check_layer(I, F, 1, 0, basic=False)
+    dW = run_transform(I, 1, 1, 1, 0)
+    dO = run_conv(dW, F, N, Ci, Hi, Wi, 1, 0)
+    dO2 = torch.full_like(dO, float("nan"))
+    im2win.conv2d_im2win_implicit_fwd(I.cuda(), F.cuda(), dO2, N, Ci, Hi, Wi, Co, 1, 1, 1, 0)
+    torch.cuda.synchronize()
+    O_ref, B_ref = oracle.conv2d_direct(I.numpy(), F.numpy(), 1, 0)
+    assert_conv_close(dO2.cpu().numpy(), O_ref, B_ref)
+    if dedicated:
+        assert torch.equal(dO.view(torch.int32), dO2.view(torch.int32))
+
+
 def test_three_channel_3x3_layer_output_off_16_byte_alignment():
     """The Conv7 shape again with an output buffer that starts 4 bytes past a 16-byte boundary: the
     16-byte stores are not used then, and the result is the same bit for bit."""
