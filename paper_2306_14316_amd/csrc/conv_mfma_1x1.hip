@@ -6,7 +6,7 @@
 // the address path of the memory pipeline takes four lanes per cycle whatever their width, so two
 // resident workgroups already saturate it.  This kernel moves the same bytes with 16-byte
 // direct-to-LDS loads (buffer_load_dwordx4 ... lds, new on gfx950):
-//   - tile 64 channels x 64 pixels, K blocks of 64 input channels, two LDS stages; the loads of
+//   - tile 64 channels x 64 pixels, K blocks of 64 input channels (the last one may be shorter), two LDS stages; the loads of
 //     block kb+1 are in flight while the matrix cores work on block kb; one barrier per block;
 //   - B (pixels): [channel][64 pixels], one wave instruction copies four channel rows (4 x 256
 //     contiguous bytes of four planes) into 1 KB of LDS; a lane's B read is base + immediate;
@@ -17,7 +17,7 @@
 //   - K order inside a block: step 4q+i multiplies channel 8q+i on lanes 0-31 with channel 8q+4+i
 //     on lanes 32-63, so one 16-byte A read serves four MFMAs of a lane half.
 // Conditions (the launcher checks them, other layers keep their kernels): Hf = Wf = 1, stride 1,
-// pad 0, Ci a multiple of 64, Co and the planes' pixel count multiples of four, 16-byte aligned tensors.
+// pad 0, Ci a multiple of eight, Co and the planes' pixel count multiples of four, 16-byte aligned tensors.
 #include "conv_mfma_tile.h"
 #include "runtime_cache.h"
 
@@ -89,14 +89,19 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_1x1_kernel(OneByOneParams P)
     const __amdgpu_buffer_rsrc_t ra = desc(P.flt, P.flt_elems);
     const uint32_t plane4 = P.howo * 4u;
 
-    // K block kb on its way into stage st: wave w issues instructions w, w+4, w+8, w+12 of each operand
+    // K block kb on its way into stage st: wave w issues instructions w, w+4, w+8, w+12 of each operand.
+    // The last block may hold fewer than 64 channels (a multiple of eight): the channel groups it does
+    // not have are not fetched, and the filter chunks past the row's end (whatever follows in memory,
+    // zeros past the tensor) land in slots no MFMA of that block reads.
     auto issue = [&](int kb, int st) __attribute__((always_inline)) {
         float *sB = lds + st * STAGE1, *sA = sB + K1 * NB;
+        const int nch = min(K1, P.Ci - kb * K1);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int I = wave + 4 * j;                       // channels 4I .. 4I+3 of the block
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (lds_void_t *)(sB + I * 256), 16, b_voff,
-                                                     (uint32_t)(kb * K1 + 4 * I) * plane4, 0, 0);
+            if (4 * I < nch)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (lds_void_t *)(sB + I * 256), 16, b_voff,
+                                                         (uint32_t)(kb * K1 + 4 * I) * plane4, 0, 0);
         }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -118,7 +123,7 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_1x1_kernel(OneByOneParams P)
     const int b_lane = wn * 32 + l32 + h * (4 * NB);          // pixel, plus the lane half's channel offset
     const int a_lane = K1 * NB + row * K1;
 
-    const int nkb = P.Ci / K1;
+    const int nkb = (P.Ci + K1 - 1) / K1;
     issue(0, 0);
     for (int kb = 0; kb < nkb; ++kb) {
         const int st = kb & 1;
@@ -128,8 +133,10 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_1x1_kernel(OneByOneParams P)
         const float *sS = lds + st * STAGE1;
         const float *bp = sS + b_lane;
         const float *ap = sS + a_lane;
+        const int nq = min(K1, P.Ci - kb * K1) >> 3;   // groups of eight channels in this block
 #pragma unroll
         for (int q = 0; q < K1 / 8; ++q) {
+            if (q >= nq) break;
             // chunk 2q + h of the row sits at slot (2q + h) ^ (row & 7)
             const float4v_t a = *reinterpret_cast<const float4v_t *>(ap + 4 * ((2 * q + h) ^ (row & 7)));
             acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, bp[(8 * q + 0) * NB], acc, 0, 0, 0);
@@ -147,7 +154,7 @@ hipError_t launch_conv_mfma_1x1(const float *in, const float *flt, float *out, c
                                 hipStream_t st, LaunchPlan *plan)
 {
     if (sh.Hf != 1 || sh.Wf != 1 || sh.s != 1 || sh.p != 0) return hipErrorNotSupported;
-    if (sh.Ci % K1 != 0 || sh.Co % 4 != 0) return hipErrorNotSupported;   // (filter rows are copied four at a time)
+    if (sh.Ci % 8 != 0 || sh.Co % 4 != 0) return hipErrorNotSupported;   // (K steps come in groups of eight channels; filter rows are copied four at a time)
     const long long howo = (long long)sh.Ho * sh.Wo;
     if (howo % 4 != 0) return hipErrorNotSupported;
     if ((reinterpret_cast<uintptr_t>(in) | reinterpret_cast<uintptr_t>(flt)) % 16u != 0) return hipErrorNotSupported;

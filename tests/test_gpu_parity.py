@@ -153,7 +153,7 @@ def test_three_channel_3x3_layer_with_many_pixels(Co, pad, Wi):
 
 
 # (N, Ci, Hi, Wi, Co): 1x1 layers, stride 1, no padding; the second field of each pair says whether the
-# dedicated 1x1 kernel takes the layer (Ci a multiple of 64, Co and the plane size multiples of four)
+# dedicated 1x1 kernel takes the layer (Ci a multiple of eight, Co and the plane size multiples of four)
 ONE_BY_ONE_SHAPES = [
     ((2, 64, 8, 8, 64), True),       # one K block, one tile per image
     ((3, 128, 14, 14, 100), True),   # two K blocks, ragged last tile, a partial block of output channels
@@ -163,7 +163,10 @@ ONE_BY_ONE_SHAPES = [
     ((2, 64, 2, 2, 64), True),       # planes of four pixels, one ragged tile over both images
     ((3, 64, 7, 7, 64), False),      # 49 pixels per plane
     ((2, 64, 8, 8, 66), False),      # 66 output channels
-    ((2, 96, 8, 8, 64), False),      # 96 input channels
+    ((2, 96, 8, 8, 64), True),       # 96 input channels: a second K block of 32
+    ((4, 8, 16, 16, 32), True),      # eight input channels: one short block
+    ((2, 200, 12, 12, 72), True),    # 200 = 3 * 64 + 8
+    ((2, 100, 8, 8, 64), False),     # 100 input channels
 ]
 
 
