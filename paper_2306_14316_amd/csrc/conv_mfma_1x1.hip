@@ -6,8 +6,9 @@
 // the address path of the memory pipeline takes four lanes per cycle whatever their width, so two
 // resident workgroups already saturate it.  This kernel moves the same bytes with 16-byte
 // direct-to-LDS loads (buffer_load_dwordx4 ... lds, new on gfx950):
-//   - tile 64 channels x 64 pixels, K blocks of 64 input channels (the last one may be shorter), two LDS stages; the loads of
-//     block kb+1 are in flight while the matrix cores work on block kb; one barrier per block;
+//   - tile 64 channels x 64 pixels, K blocks of 64 input channels (the last one may be shorter), two LDS
+//     stages; persistent workgroups run their tiles as one sequence of blocks, the loads of the next block
+//     (of the next tile, after a tile's last) in flight while the matrix cores work; one barrier per block;
 //   - B (pixels): [channel][64 pixels], one wave instruction copies four channel rows (4 x 256
 //     contiguous bytes of four planes) into 1 KB of LDS; a lane's B read is base + immediate;
 //   - A (filter): [row][64 k], pitch 64 floats, the sixteen 16-byte chunks of a row stored at slot
@@ -34,7 +35,7 @@ struct OneByOneParams {
     const float *flt;    // [Co][Ci]
     MfmaParams T;        // the fields the shared epilogue reads (out, out_elems, Co, howo, d_howo)
     int Ci;
-    uint32_t npix, howo, tiles_m;
+    uint32_t npix, howo, tiles_m, ntiles;
     size_t in_elems, flt_elems;
     FastDiv d_howo, d_tm;
 };
@@ -49,103 +50,120 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_1x1_kernel(OneByOneParams P)
     const int wm = wave & 1, wn = wave >> 1;
     const int h = lane >> 5, l32 = lane & 31;
 
-    const uint32_t lb = xcd_swizzle(blockIdx.x, gridDim.x);
-    const uint32_t tile_n = fdiv(lb, P.d_tm);
-    const uint32_t tile_m = lb - tile_n * P.tiles_m;
-    const int m0 = (int)tile_m * MB;
-    const uint32_t P0 = tile_n * NB;
-    const uint32_t Pend = min(P0 + NB - 1, P.npix - 1);
+    // Persistent workgroups: the grid takes the tiles round by round, the workgroups of one XCD (every
+    // eighth one) on neighbouring tiles, so that the channel blocks of a pixel tile -- consecutive
+    // tile numbers -- read their shared pixels through one L2 at about the same time.
+    const uint32_t tstep = gridDim.x, xcd = blockIdx.x % 8u;
+    const uint32_t tile0 = xcd * (tstep / 8u) + min(xcd, tstep % 8u) + blockIdx.x / 8u;
+    if (tile0 >= P.ntiles) return;
 
-    // ---- source offsets of this lane's 16-byte chunks (fixed for the whole kernel) ----
+    // What the loads and the epilogue need to know about a tile.
+    struct Tile {
+        uint32_t P0, Pend;
+        int m0;
+        uint32_t b_voff;     // per lane: byte offset of its chunk of four pixels (and its channel of four)
+        size_t b_tile;       // floats: plane 0 of the image of the tile's first pixel
+    };
     // B: lane = (channel of four: lane / 16, chunk of four pixels: lane % 16).  The tile's pixels may
     // straddle images; a chunk never does (planes are a multiple of four pixels).  Chunks past the
     // layer's last pixel re-read its last chunk (their outputs are never stored).
-    const uint32_t img0 = fdiv(P0, P.d_howo);
-    const size_t b_tile = (size_t)img0 * P.Ci * P.howo;            // floats: plane 0 of the tile's first image
-    uint32_t b_voff;
-    {
-        const uint32_t Pl = min(P0 + 4u * (uint32_t)(lane & 15), P.npix - 4u);
+    auto geometry = [&](uint32_t t) __attribute__((always_inline)) {
+        Tile T;
+        const uint32_t tile_n = fdiv(t, P.d_tm);
+        T.m0 = (int)(t - tile_n * P.tiles_m) * MB;
+        T.P0 = tile_n * NB;
+        T.Pend = min(T.P0 + NB - 1, P.npix - 1);
+        const uint32_t img0 = fdiv(T.P0, P.d_howo);
+        T.b_tile = (size_t)img0 * P.Ci * P.howo;
+        const uint32_t Pl = min(T.P0 + 4u * (uint32_t)(lane & 15), P.npix - 4u);
         const uint32_t img = fdiv(Pl, P.d_howo);
         const uint32_t pin = Pl - img * P.howo;
-        b_voff = ((img - img0) * (uint32_t)P.Ci * P.howo + pin + (uint32_t)(lane >> 4) * P.howo) * 4u;
-    }
+        T.b_voff = ((img - img0) * (uint32_t)P.Ci * P.howo + pin + (uint32_t)(lane >> 4) * P.howo) * 4u;
+        return T;
+    };
     // A: lane = (row of four: lane / 16, slot: lane % 16); instruction I of a wave covers rows 4I .. 4I+3,
-    // and (4I + r) & 7 = (4I & 4) | r, so the slot permutation has two forms, for even and odd I.
-    // Rows past Co re-read the last row (their accumulators are never stored).
-    uint32_t a_voff[2];
+    // and (4I + r) & 7 = (4I & 4) | r, so the slot permutation has two forms, for even and odd I -- and
+    // I = wave + 4j has the parity of the wave.  Row groups past Co re-read the last four rows (their
+    // accumulators are never stored; Co is a multiple of four).
     const uint32_t Ci4 = (uint32_t)P.Ci * 4u;
-#pragma unroll
-    for (int par = 0; par < 2; ++par) {
-        const int r = lane >> 4, slot = lane & 15;
-        const int chunk = slot ^ ((4 * par + r) & 7);
-        a_voff[par] = (uint32_t)r * Ci4 + (uint32_t)chunk * 16u;
-    }
+    const uint32_t a_voff = (uint32_t)(lane >> 4) * Ci4 + (uint32_t)((lane & 15) ^ ((4 * (wave & 1) + (lane >> 4)) & 7)) * 16u;
     auto desc = [](const float *base, size_t elems) __attribute__((always_inline)) {
         const size_t left = elems * 4u;
         return __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(base), 0,
                                                  left < 0xffffffffull ? left : 0xffffffffull, 0x00020000);
     };
-    const __amdgpu_buffer_rsrc_t rb = desc(P.in + b_tile, P.in_elems - b_tile);
     const __amdgpu_buffer_rsrc_t ra = desc(P.flt, P.flt_elems);
     const uint32_t plane4 = P.howo * 4u;
 
-    // K block kb on its way into stage st: wave w issues instructions w, w+4, w+8, w+12 of each operand.
-    // The last block may hold fewer than 64 channels (a multiple of eight): the channel groups it does
-    // not have are not fetched, and the filter chunks past the row's end (whatever follows in memory,
-    // zeros past the tensor) land in slots no MFMA of that block reads.
-    auto issue = [&](int kb, int st) __attribute__((always_inline)) {
+    // K block kb of tile T on its way into stage st: wave w issues instructions w, w+4, w+8, w+12 of
+    // each operand.  The last block may hold fewer than 64 channels (a multiple of eight): the channel
+    // groups it does not have are not fetched, and the filter chunks past the row's end (whatever
+    // follows in memory, zeros past the tensor) land in slots no MFMA of that block reads.
+    auto issue = [&](const Tile &T, int kb, int st) __attribute__((always_inline)) {
         float *sB = lds + st * STAGE1, *sA = sB + K1 * NB;
+        const __amdgpu_buffer_rsrc_t rb = desc(P.in + T.b_tile, P.in_elems - T.b_tile);
         const int nch = min(K1, P.Ci - kb * K1);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int I = wave + 4 * j;                       // channels 4I .. 4I+3 of the block
             if (4 * I < nch)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (lds_void_t *)(sB + I * 256), 16, b_voff,
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (lds_void_t *)(sB + I * 256), 16, T.b_voff,
                                                          (uint32_t)(kb * K1 + 4 * I) * plane4, 0, 0);
         }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int I = wave + 4 * j;                       // filter rows 4I .. 4I+3 of the tile
-            const int row = min(m0 + 4 * I, P.T.Co - 4);      // (a tile's last rows: see above)
-            const uint32_t soff = (uint32_t)row * Ci4 + (uint32_t)kb * (K1 * 4);
-            // wave-uniform choice between the two slot permutations (I is uniform)
-            const uint32_t vo = (I & 1) ? a_voff[1] : a_voff[0];
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (lds_void_t *)(sA + I * 256), 16, vo, soff, 0, 0);
+            const int row = min(T.m0 + 4 * I, P.T.Co - 4);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (lds_void_t *)(sA + I * 256), 16, a_voff,
+                                                     (uint32_t)row * Ci4 + (uint32_t)kb * (K1 * 4), 0, 0);
         }
     };
-
-    floatx16 acc;
-#pragma unroll
-    for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
 
     // operand bases of this lane, relative to a stage
     const int row = wm * 32 + l32;                            // filter row of the tile
     const int b_lane = wn * 32 + l32 + h * (4 * NB);          // pixel, plus the lane half's channel offset
     const int a_lane = K1 * NB + row * K1;
-
     const int nkb = (P.Ci + K1 - 1) / K1;
-    issue(0, 0);
-    for (int kb = 0; kb < nkb; ++kb) {
-        const int st = kb & 1;
-        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's loads of block kb have landed
-        __syncthreads();                      // everyone's have, and stage st^1 is free again
-        if (kb + 1 < nkb) issue(kb + 1, st ^ 1);
-        const float *sS = lds + st * STAGE1;
-        const float *bp = sS + b_lane;
-        const float *ap = sS + a_lane;
-        const int nq = min(K1, P.Ci - kb * K1) >> 3;   // groups of eight channels in this block
+
+    // One flat sequence of K blocks over all of the workgroup's tiles: the loads of the next block -- the
+    // next tile's first one after a tile's last -- are always in flight while the matrix cores work, and
+    // a tile's stores go out while its successor's first block arrives.
+    Tile cur = geometry(tile0);
+    issue(cur, 0, 0);
+    int st = 0;
+    for (uint32_t t = tile0; t < P.ntiles; t += tstep) {
+        const bool more = t + tstep < P.ntiles;
+        Tile nxt = cur;
+        floatx16 acc;
 #pragma unroll
-        for (int q = 0; q < K1 / 8; ++q) {
-            if (q >= nq) break;
-            // chunk 2q + h of the row sits at slot (2q + h) ^ (row & 7)
-            const float4v_t a = *reinterpret_cast<const float4v_t *>(ap + 4 * ((2 * q + h) ^ (row & 7)));
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, bp[(8 * q + 0) * NB], acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, bp[(8 * q + 1) * NB], acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, bp[(8 * q + 2) * NB], acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, bp[(8 * q + 3) * NB], acc, 0, 0, 0);
+        for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+        for (int kb = 0; kb < nkb; ++kb, st ^= 1) {
+            __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's loads of the block have landed
+            __syncthreads();                      // everyone's have, and the other stage is free again
+            if (kb + 1 < nkb) {
+                issue(cur, kb + 1, st ^ 1);
+            } else if (more) {
+                nxt = geometry(t + tstep);
+                issue(nxt, 0, st ^ 1);
+            }
+            const float *sS = lds + st * STAGE1;
+            const float *bp = sS + b_lane;
+            const float *ap = sS + a_lane;
+            const int nq = min(K1, P.Ci - kb * K1) >> 3;   // groups of eight channels in this block
+#pragma unroll
+            for (int q = 0; q < K1 / 8; ++q) {
+                if (q >= nq) break;
+                // chunk 2q + h of the row sits at slot (2q + h) ^ (row & 7)
+                const float4v_t a = *reinterpret_cast<const float4v_t *>(ap + 4 * ((2 * q + h) ^ (row & 7)));
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, bp[(8 * q + 0) * NB], acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, bp[(8 * q + 1) * NB], acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, bp[(8 * q + 2) * NB], acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, bp[(8 * q + 3) * NB], acc, 0, 0, 0);
+            }
         }
+        store_tile_desc(P.T, acc, cur.P0, cur.Pend, cur.m0, wm, wn, h, l32);
+        cur = nxt;
     }
-    store_tile_desc(P.T, acc, P0, Pend, m0, wm, wn, h, l32);
 }
 
 // Returns hipErrorNotSupported when the layer does not meet this kernel's conditions.  `in` is the
@@ -179,14 +197,27 @@ hipError_t launch_conv_mfma_1x1(const float *in, const float *flt, float *out, c
     P.T.out_elems = (size_t)sh.npix * sh.Co;
     // (the epilogue's 32-bit output offsets: a tile's pixels within 4 GiB of its first image's first channel)
     if ((((long long)(howo < NB ? NB / howo + 2 : 2)) * sh.Co + 64) * howo * 4LL >= (1LL << 32)) return hipErrorNotSupported;
-    const uint32_t blocks = ((P.npix + NB - 1) / NB) * P.tiles_m;
+    P.ntiles = ((P.npix + NB - 1) / NB) * P.tiles_m;
     constexpr size_t lds = 2u * STAGE1 * sizeof(float);
+    int dev = 0, ncu = 0;
+    hipError_t e = device_cus(&dev, &ncu);
+    if (e != hipSuccess && plan) { e = hipSuccess; ncu = 256; }   // planning without a device: an MI355X's 256 compute units
+    if (e != hipSuccess) return e;
+    // Layers with one or two K blocks per tile run persistent workgroups (two per CU fit, 64 KB of LDS
+    // each; whole groups of eight so that every XCD gets its share): a tile is then as short as the wait
+    // for its first block, which only the prefetch across tiles hides (64 -> 256 channels at 56x56:
+    // 67 -> 76 TFLOP/s).  With longer K loops one workgroup per tile is faster (512 -> 512 channels at
+    // 14x14: 110 against 100 TFLOP/s): the hardware hands tiles out as workgroups finish, where the fixed
+    // rounds leave some workgroups a tile short.
+    uint32_t blocks = P.ntiles;
+    if ((sh.Ci + K1 - 1) / K1 <= 2) {
+        blocks = (uint32_t)ncu * 2u;
+        if (blocks >= 8) blocks &= ~7u;
+        if (blocks > P.ntiles) blocks = P.ntiles;
+    }
     if (plan) { plan_record(plan, dim3(blocks), 256, lds, "conv_mfma_1x1_kernel"); return hipSuccess; }
     static KernelCache kc;
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e == hipSuccess) e = allow_dynamic_lds(kc, reinterpret_cast<const void *>(&conv_mfma_1x1_kernel), lds, dev);
-    if (e != hipSuccess) return e;
+    if ((e = allow_dynamic_lds(kc, reinterpret_cast<const void *>(&conv_mfma_1x1_kernel), lds, dev)) != hipSuccess) return e;
     hipLaunchKernelGGL(conv_mfma_1x1_kernel, dim3(blocks), dim3(256), lds, st, P);
     return hipGetLastError();
 }
