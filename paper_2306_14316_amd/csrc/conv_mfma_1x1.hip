@@ -6,12 +6,12 @@
 // the address path of the memory pipeline takes four lanes per cycle whatever their width, so two
 // resident workgroups already saturate it.  This kernel moves the same bytes with 16-byte
 // direct-to-LDS loads (buffer_load_dwordx4 ... lds, new on gfx950):
-//   - tile 64 channels x 64 pixels, K blocks of 64 input channels (the last one may be shorter), two LDS
+//   - tile 64 channels x 64 pixels, K blocks of 32 (or 64) input channels (the last one may be shorter), two LDS
 //     stages; persistent workgroups run their tiles as one sequence of blocks, the loads of the next block
 //     (of the next tile, after a tile's last) in flight while the matrix cores work; one barrier per block;
 //   - B (pixels): [channel][64 pixels], one wave instruction copies four channel rows (4 x 256
 //     contiguous bytes of four planes) into 1 KB of LDS; a lane's B read is base + immediate;
-//   - A (filter): [row][64 k], pitch 64 floats, the sixteen 16-byte chunks of a row stored at slot
+//   - A (filter): [row][K1 k], pitch K1 floats, the 16-byte chunks of a row stored at slot
 //     (chunk ^ (row & 7)) -- the permutation is applied to the source address of each lane, the
 //     LDS side of a load is always the wave's 1 KB in lane order -- so that the 16-byte A reads of
 //     eight neighbouring rows fall into eight different bank groups;
@@ -27,8 +27,8 @@ namespace im2win {
 typedef __attribute__((address_space(3))) void lds_void_t;
 typedef float float4v_t __attribute__((ext_vector_type(4)));
 
-constexpr int K1 = 64;                       // input channels per K block
-constexpr int STAGE1 = K1 * NB + MB * K1;    // floats per LDS stage: B [K1][NB], then A [MB][K1]
+// K1: input channels per K block (64 or 32).  floats per LDS stage: B [K1][NB], then A [MB][K1]
+template <int K1> constexpr int stage1_floats() { return K1 * NB + MB * K1; }
 
 struct OneByOneParams {
     const float *in;     // [N][Ci][howo]
@@ -40,8 +40,21 @@ struct OneByOneParams {
     FastDiv d_howo, d_tm;
 };
 
-__global__ __launch_bounds__(256, 2) void conv_mfma_1x1_kernel(OneByOneParams P)
+// What the loads and the epilogue need to know about a tile.
+struct OneByOneTile {
+    uint32_t P0, Pend;
+    int m0;
+    uint32_t b_voff;     // per lane: byte offset of its chunk of four pixels (and its channel of four)
+    size_t b_tile;       // floats: plane 0 of the image of the tile's first pixel
+};
+
+template <int K1>
+__global__ __launch_bounds__(256) void conv_mfma_1x1_kernel(OneByOneParams P)
 {
+    constexpr int STAGE1 = stage1_floats<K1>();
+    constexpr int CPR = K1 / 4;          // 16-byte chunks per filter row and block
+    constexpr int RPI = 64 / CPR;        // filter rows per load instruction (a wave's 1 KB)
+    constexpr int NI = K1 / 16;          // load instructions per wave, block and operand
     extern __shared__ __align__(16) unsigned char smem[];
     float *lds = reinterpret_cast<float *>(smem);   // two stages
 
@@ -57,18 +70,11 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_1x1_kernel(OneByOneParams P)
     const uint32_t tile0 = xcd * (tstep / 8u) + min(xcd, tstep % 8u) + blockIdx.x / 8u;
     if (tile0 >= P.ntiles) return;
 
-    // What the loads and the epilogue need to know about a tile.
-    struct Tile {
-        uint32_t P0, Pend;
-        int m0;
-        uint32_t b_voff;     // per lane: byte offset of its chunk of four pixels (and its channel of four)
-        size_t b_tile;       // floats: plane 0 of the image of the tile's first pixel
-    };
     // B: lane = (channel of four: lane / 16, chunk of four pixels: lane % 16).  The tile's pixels may
     // straddle images; a chunk never does (planes are a multiple of four pixels).  Chunks past the
     // layer's last pixel re-read its last chunk (their outputs are never stored).
     auto geometry = [&](uint32_t t) __attribute__((always_inline)) {
-        Tile T;
+        OneByOneTile T;
         const uint32_t tile_n = fdiv(t, P.d_tm);
         T.m0 = (int)(t - tile_n * P.tiles_m) * MB;
         T.P0 = tile_n * NB;
@@ -81,12 +87,13 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_1x1_kernel(OneByOneParams P)
         T.b_voff = ((img - img0) * (uint32_t)P.Ci * P.howo + pin + (uint32_t)(lane >> 4) * P.howo) * 4u;
         return T;
     };
-    // A: lane = (row of four: lane / 16, slot: lane % 16); instruction I of a wave covers rows 4I .. 4I+3,
-    // and (4I + r) & 7 = (4I & 4) | r, so the slot permutation has two forms, for even and odd I -- and
-    // I = wave + 4j has the parity of the wave.  Row groups past Co re-read the last four rows (their
-    // accumulators are never stored; Co is a multiple of four).
+    // A: lane = (row of RPI: lane / CPR, slot: lane % CPR); instruction I of a wave covers rows RPI*I ..
+    // RPI*I + RPI-1.  With four rows per instruction (RPI*I + r) & 7 = (4I & 4) | r: the slot permutation
+    // has two forms, for even and odd I, and I = wave + 4j has the parity of the wave; with eight rows it
+    // is r.  Row groups past Co re-read the last rows (their accumulators are never stored).
     const uint32_t Ci4 = (uint32_t)P.Ci * 4u;
-    const uint32_t a_voff = (uint32_t)(lane >> 4) * Ci4 + (uint32_t)((lane & 15) ^ ((4 * (wave & 1) + (lane >> 4)) & 7)) * 16u;
+    const int a_r = lane / CPR;
+    const uint32_t a_voff = (uint32_t)a_r * Ci4 + (uint32_t)((lane % CPR) ^ ((RPI * (wave & 1) + a_r) & 7)) * 16u;
     auto desc = [](const float *base, size_t elems) __attribute__((always_inline)) {
         const size_t left = elems * 4u;
         return __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(base), 0,
@@ -99,21 +106,21 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_1x1_kernel(OneByOneParams P)
     // each operand.  The last block may hold fewer than 64 channels (a multiple of eight): the channel
     // groups it does not have are not fetched, and the filter chunks past the row's end (whatever
     // follows in memory, zeros past the tensor) land in slots no MFMA of that block reads.
-    auto issue = [&](const Tile &T, int kb, int st) __attribute__((always_inline)) {
+    auto issue = [&](const OneByOneTile &T, int kb, int st) __attribute__((always_inline)) {
         float *sB = lds + st * STAGE1, *sA = sB + K1 * NB;
         const __amdgpu_buffer_rsrc_t rb = desc(P.in + T.b_tile, P.in_elems - T.b_tile);
         const int nch = min(K1, P.Ci - kb * K1);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+        for (int j = 0; j < NI; ++j) {
             const int I = wave + 4 * j;                       // channels 4I .. 4I+3 of the block
             if (4 * I < nch)
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (lds_void_t *)(sB + I * 256), 16, T.b_voff,
                                                          (uint32_t)(kb * K1 + 4 * I) * plane4, 0, 0);
         }
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int I = wave + 4 * j;                       // filter rows 4I .. 4I+3 of the tile
-            const int row = min(T.m0 + 4 * I, P.T.Co - 4);
+        for (int j = 0; j < NI; ++j) {
+            const int I = wave + 4 * j;                       // filter rows RPI*I .. of the tile
+            const int row = min(T.m0 + RPI * I, P.T.Co - RPI);
             __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (lds_void_t *)(sA + I * 256), 16, a_voff,
                                                      (uint32_t)row * Ci4 + (uint32_t)kb * (K1 * 4), 0, 0);
         }
@@ -128,12 +135,12 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_1x1_kernel(OneByOneParams P)
     // One flat sequence of K blocks over all of the workgroup's tiles: the loads of the next block -- the
     // next tile's first one after a tile's last -- are always in flight while the matrix cores work, and
     // a tile's stores go out while its successor's first block arrives.
-    Tile cur = geometry(tile0);
+    OneByOneTile cur = geometry(tile0);
     issue(cur, 0, 0);
     int st = 0;
     for (uint32_t t = tile0; t < P.ntiles; t += tstep) {
         const bool more = t + tstep < P.ntiles;
-        Tile nxt = cur;
+        OneByOneTile nxt = cur;
         floatx16 acc;
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
@@ -164,6 +171,35 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_1x1_kernel(OneByOneParams P)
         store_tile_desc(P.T, acc, cur.P0, cur.Pend, cur.m0, wm, wn, h, l32);
         cur = nxt;
     }
+}
+
+template <int K1>
+static hipError_t launch_1x1_t(OneByOneParams &P, const Shape &sh, hipStream_t st, LaunchPlan *plan)
+{
+    constexpr size_t lds = 2u * stage1_floats<K1>() * sizeof(float);
+    constexpr int per_cu = 128 / K1;   // resident workgroups per CU (LDS)
+    int dev = 0, ncu = 0;
+    hipError_t e = device_cus(&dev, &ncu);
+    if (e != hipSuccess && plan) { e = hipSuccess; ncu = 256; }   // planning without a device: an MI355X's 256 compute units
+    if (e != hipSuccess) return e;
+    // Layers with up to 128 channels run persistent workgroups (as many as fit: 64 or 32 KB of LDS
+    // each; whole groups of eight so that every XCD gets its share): a tile is then as short as the wait
+    // for its first block, which only the prefetch across tiles hides (64 -> 256 channels at 56x56:
+    // 67 -> 76 TFLOP/s).  With longer K loops one workgroup per tile is faster (512 -> 512 channels at
+    // 14x14: 110 against 100 TFLOP/s): the hardware hands tiles out as workgroups finish, where the fixed
+    // rounds leave some workgroups a tile short.
+    uint32_t blocks = P.ntiles;
+    if ((sh.Ci + 63) / 64 <= 2) {
+        blocks = (uint32_t)(ncu * per_cu);
+        if (blocks >= 8) blocks &= ~7u;
+        if (blocks > P.ntiles) blocks = P.ntiles;
+    }
+    if (plan) { plan_record(plan, dim3(blocks), 256, lds, "conv_mfma_1x1_kernel<%d>", K1); return hipSuccess; }
+    static KernelCache kc;
+    void (*kern)(OneByOneParams) = &conv_mfma_1x1_kernel<K1>;
+    if ((e = allow_dynamic_lds(kc, reinterpret_cast<const void *>(kern), lds, dev)) != hipSuccess) return e;
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3(256), lds, st, P);
+    return hipGetLastError();
 }
 
 // Returns hipErrorNotSupported when the layer does not meet this kernel's conditions.  `in` is the
@@ -198,28 +234,11 @@ hipError_t launch_conv_mfma_1x1(const float *in, const float *flt, float *out, c
     // (the epilogue's 32-bit output offsets: a tile's pixels within 4 GiB of its first image's first channel)
     if ((((long long)(howo < NB ? NB / howo + 2 : 2)) * sh.Co + 64) * howo * 4LL >= (1LL << 32)) return hipErrorNotSupported;
     P.ntiles = ((P.npix + NB - 1) / NB) * P.tiles_m;
-    constexpr size_t lds = 2u * STAGE1 * sizeof(float);
-    int dev = 0, ncu = 0;
-    hipError_t e = device_cus(&dev, &ncu);
-    if (e != hipSuccess && plan) { e = hipSuccess; ncu = 256; }   // planning without a device: an MI355X's 256 compute units
-    if (e != hipSuccess) return e;
-    // Layers with one or two K blocks per tile run persistent workgroups (two per CU fit, 64 KB of LDS
-    // each; whole groups of eight so that every XCD gets its share): a tile is then as short as the wait
-    // for its first block, which only the prefetch across tiles hides (64 -> 256 channels at 56x56:
-    // 67 -> 76 TFLOP/s).  With longer K loops one workgroup per tile is faster (512 -> 512 channels at
-    // 14x14: 110 against 100 TFLOP/s): the hardware hands tiles out as workgroups finish, where the fixed
-    // rounds leave some workgroups a tile short.
-    uint32_t blocks = P.ntiles;
-    if ((sh.Ci + K1 - 1) / K1 <= 2) {
-        blocks = (uint32_t)ncu * 2u;
-        if (blocks >= 8) blocks &= ~7u;
-        if (blocks > P.ntiles) blocks = P.ntiles;
-    }
-    if (plan) { plan_record(plan, dim3(blocks), 256, lds, "conv_mfma_1x1_kernel"); return hipSuccess; }
-    static KernelCache kc;
-    if ((e = allow_dynamic_lds(kc, reinterpret_cast<const void *>(&conv_mfma_1x1_kernel), lds, dev)) != hipSuccess) return e;
-    hipLaunchKernelGGL(conv_mfma_1x1_kernel, dim3(blocks), dim3(256), lds, st, P);
-    return hipGetLastError();
+    // K blocks of 32 channels leave room for four workgroups per CU, which hide each other's barriers and
+    // load waits better than two with blocks of 64 (256 -> 256 channels at 28x28: 109 against 95 TFLOP/s);
+    // they copy eight filter rows per instruction, hence for channel counts that are multiples of eight.
+    if (sh.Co % 8 == 0) return launch_1x1_t<32>(P, sh, st, plan);
+    return launch_1x1_t<64>(P, sh, st, plan);
 }
 
 }  // namespace im2win
