@@ -66,12 +66,15 @@ TABLE2 = (
 
 
 # Layers off the specialised kernels' grid, timed by `bench.py --extra`: a channel count that is not a
-# multiple of the pipelined kernel's K block, a 1x1 layer, an asymmetric filter.
+# multiple of the pipelined kernel's K block, 1x1 layers (expanding, reducing, strided), an asymmetric filter.
 EXTRA = (
     Layer("extra_3x3_c60_56", 32, 60, 56, 56, 64, 3, 3, 1, 1, 3001, "uniform01", "he_normal"),
     Layer("extra_3x3_c100_28", 64, 100, 28, 28, 128, 3, 3, 1, 1, 3002, "uniform01", "he_normal"),
     Layer("extra_1x1_c256_28", 64, 256, 28, 28, 256, 1, 1, 1, 0, 3003, "uniform01", "he_normal"),
     Layer("extra_1x7_c64_28", 64, 64, 28, 28, 64, 1, 7, 1, 0, 3004, "uniform01", "he_normal"),
+    Layer("extra_1x1_c64_56_co256", 64, 64, 56, 56, 256, 1, 1, 1, 0, 3005, "uniform01", "he_normal"),
+    Layer("extra_1x1_c1024_14_co256", 64, 1024, 14, 14, 256, 1, 1, 1, 0, 3006, "uniform01", "he_normal"),
+    Layer("extra_1x1_s2_c256_56_co512", 64, 256, 56, 56, 512, 1, 1, 2, 0, 3007, "uniform01", "he_normal"),
 )
 
 
