@@ -575,7 +575,7 @@ hipError_t launch_conv_implicit(const float *in, const float *flt, float *out, c
     if (fe != hipErrorNotSupported) return fe;
     fe = launch_conv_mfma_fast(P, sh, blocks, st, true, 4, plan);
     if (fe != hipErrorNotSupported) return fe;
-    fe = launch_conv_mfma_1x1(in, flt, out, sh, st, plan);   // (a 1x1 layer's im2win tensor is its input)
+    fe = launch_conv_mfma_1x1(in, flt, out, sh, st, true, plan);
     if (fe != hipErrorNotSupported) return fe;
     fe = launch_generic(P, sh, blocks, st, plan);
     if (fe == hipErrorInvalidConfiguration) return launch_conv_direct(in, flt, out, sh, st, plan);
@@ -599,7 +599,7 @@ hipError_t launch_conv_mfma(const float *win, const float *flt, float *out, cons
         if (fe != hipErrorNotSupported) return fe;
     }
     if (variant == kVariantDefault) {
-        const hipError_t oe = launch_conv_mfma_1x1(win, flt, out, sh, st, plan);
+        const hipError_t oe = launch_conv_mfma_1x1(win, flt, out, sh, st, false, plan);
         if (oe != hipErrorNotSupported) return oe;
         const hipError_t pe = launch_generic_pipe(P, sh, blocks, st, plan);
         if (pe != hipErrorNotSupported) return pe;

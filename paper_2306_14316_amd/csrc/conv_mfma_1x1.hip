@@ -1,4 +1,4 @@
-// 1x1 convolution (stride 1, no padding) on the fp32 matrix cores.  For such a layer the im2win
+// 1x1 convolution (no padding) on the fp32 matrix cores.  For such a layer with stride 1 the im2win
 // tensor of Eq. 2 has the input's own layout -- every window is one element, row m of the tensor is
 // row m of the input -- and the convolution is the GEMM O[Co x P] = F[Co x Ci] * I[Ci x P] over the
 // P = N*H*W pixels, with I read channel plane by channel plane.  The generic two-stage kernel runs
@@ -17,8 +17,10 @@
 //     eight neighbouring rows fall into eight different bank groups;
 //   - K order inside a block: step 4q+i multiplies channel 8q+i on lanes 0-31 with channel 8q+4+i
 //     on lanes 32-63, so one 16-byte A read serves four MFMAs of a lane half.
-// Conditions (the launcher checks them, other layers keep their kernels): Hf = Wf = 1, stride 1,
-// pad 0, Ci a multiple of eight, Co and the planes' pixel count multiples of four, 16-byte aligned tensors.
+// Conditions (the launcher checks them, other layers keep their kernels): Hf = Wf = 1, pad 0, Ci a
+// multiple of eight, Co a multiple of four, a 16-byte aligned filter.  With a stride above 1, planes whose
+// pixel count is not a multiple of four or an unaligned source the pixels are copied one word per lane
+// instead (GATHER below); the filter side and the MFMA loop are the same.
 #include "conv_mfma_tile.h"
 #include "runtime_cache.h"
 
@@ -38,6 +40,10 @@ struct OneByOneParams {
     uint32_t npix, howo, tiles_m, ntiles;
     size_t in_elems, flt_elems;
     FastDiv d_howo, d_tm;
+    // source geometry (GATHER instances): floats in a channel plane of `in`, between its rows that hold
+    // consecutive output rows, and between the columns of neighbouring output pixels; output row length
+    uint32_t plane, rowstep, colstep, Wo;
+    FastDiv d_wo;
 };
 
 // What the loads and the epilogue need to know about a tile.
@@ -48,7 +54,13 @@ struct OneByOneTile {
     size_t b_tile;       // floats: plane 0 of the image of the tile's first pixel
 };
 
-template <int K1>
+// GATHER: the pixels of a tile are not contiguous in the source (a stride above 1: every s-th column of
+// every row of the im2win tensor, every s-th row and column of the input in the workspace-free call) or
+// do not come in groups of four.  B is then copied one word per lane -- lane = pixel, one channel row of
+// 64 pixels per instruction, each lane fetching its own pixel -- into the same LDS layout; the filter
+// still travels 16 bytes per lane.  (Eight such loads per wave and K block of 32 channels keep the
+// address path of the memory pipeline busy for half of the block's MFMA time.)
+template <int K1, bool GATHER>
 __global__ __launch_bounds__(256) void conv_mfma_1x1_kernel(OneByOneParams P)
 {
     constexpr int STAGE1 = stage1_floats<K1>();
@@ -80,11 +92,20 @@ __global__ __launch_bounds__(256) void conv_mfma_1x1_kernel(OneByOneParams P)
         T.P0 = tile_n * NB;
         T.Pend = min(T.P0 + NB - 1, P.npix - 1);
         const uint32_t img0 = fdiv(T.P0, P.d_howo);
-        T.b_tile = (size_t)img0 * P.Ci * P.howo;
-        const uint32_t Pl = min(T.P0 + 4u * (uint32_t)(lane & 15), P.npix - 4u);
-        const uint32_t img = fdiv(Pl, P.d_howo);
-        const uint32_t pin = Pl - img * P.howo;
-        T.b_voff = ((img - img0) * (uint32_t)P.Ci * P.howo + pin + (uint32_t)(lane >> 4) * P.howo) * 4u;
+        T.b_tile = (size_t)img0 * P.Ci * P.plane;
+        if constexpr (GATHER) {
+            // lane = pixel of the tile; pixels past the layer's last re-read it (never stored)
+            const uint32_t Pl = min(T.P0 + (uint32_t)lane, P.npix - 1u);
+            const uint32_t img = fdiv(Pl, P.d_howo);
+            const uint32_t pin = Pl - img * P.howo;
+            const uint32_t m = fdiv(pin, P.d_wo), n = pin - m * P.Wo;
+            T.b_voff = ((img - img0) * (uint32_t)P.Ci * P.plane + m * P.rowstep + n * P.colstep) * 4u;
+        } else {
+            const uint32_t Pl = min(T.P0 + 4u * (uint32_t)(lane & 15), P.npix - 4u);
+            const uint32_t img = fdiv(Pl, P.d_howo);
+            const uint32_t pin = Pl - img * P.howo;
+            T.b_voff = ((img - img0) * (uint32_t)P.Ci * P.plane + pin + (uint32_t)(lane >> 4) * P.plane) * 4u;
+        }
         return T;
     };
     // A: lane = (row of RPI: lane / CPR, slot: lane % CPR); instruction I of a wave covers rows RPI*I ..
@@ -100,7 +121,7 @@ __global__ __launch_bounds__(256) void conv_mfma_1x1_kernel(OneByOneParams P)
                                                  left < 0xffffffffull ? left : 0xffffffffull, 0x00020000);
     };
     const __amdgpu_buffer_rsrc_t ra = desc(P.flt, P.flt_elems);
-    const uint32_t plane4 = P.howo * 4u;
+    const uint32_t plane4 = P.plane * 4u;
 
     // K block kb of tile T on its way into stage st: wave w issues instructions w, w+4, w+8, w+12 of
     // each operand.  The last block may hold fewer than 64 channels (a multiple of eight): the channel
@@ -110,12 +131,22 @@ __global__ __launch_bounds__(256) void conv_mfma_1x1_kernel(OneByOneParams P)
         float *sB = lds + st * STAGE1, *sA = sB + K1 * NB;
         const __amdgpu_buffer_rsrc_t rb = desc(P.in + T.b_tile, P.in_elems - T.b_tile);
         const int nch = min(K1, P.Ci - kb * K1);
+        if constexpr (GATHER) {
 #pragma unroll
-        for (int j = 0; j < NI; ++j) {
-            const int I = wave + 4 * j;                       // channels 4I .. 4I+3 of the block
-            if (4 * I < nch)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (lds_void_t *)(sB + I * 256), 16, T.b_voff,
-                                                         (uint32_t)(kb * K1 + 4 * I) * plane4, 0, 0);
+            for (int j = 0; j < K1 / 4; ++j) {
+                const int c = wave + 4 * j;                   // channel c of the block: its 64 pixels
+                if (c < nch)
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (lds_void_t *)(sB + c * NB), 4, T.b_voff,
+                                                             (uint32_t)(kb * K1 + c) * plane4, 0, 0);
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < NI; ++j) {
+                const int I = wave + 4 * j;                   // channels 4I .. 4I+3 of the block
+                if (4 * I < nch)
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (lds_void_t *)(sB + I * 256), 16, T.b_voff,
+                                                             (uint32_t)(kb * K1 + 4 * I) * plane4, 0, 0);
+            }
         }
 #pragma unroll
         for (int j = 0; j < NI; ++j) {
@@ -173,7 +204,7 @@ __global__ __launch_bounds__(256) void conv_mfma_1x1_kernel(OneByOneParams P)
     }
 }
 
-template <int K1>
+template <int K1, bool GATHER>
 static hipError_t launch_1x1_t(OneByOneParams &P, const Shape &sh, hipStream_t st, LaunchPlan *plan)
 {
     constexpr size_t lds = 2u * stage1_floats<K1>() * sizeof(float);
@@ -194,51 +225,60 @@ static hipError_t launch_1x1_t(OneByOneParams &P, const Shape &sh, hipStream_t s
         if (blocks >= 8) blocks &= ~7u;
         if (blocks > P.ntiles) blocks = P.ntiles;
     }
-    if (plan) { plan_record(plan, dim3(blocks), 256, lds, "conv_mfma_1x1_kernel<%d>", K1); return hipSuccess; }
+    if (plan) { plan_record(plan, dim3(blocks), 256, lds, "conv_mfma_1x1_kernel<%d, %s>", K1, tf(GATHER)); return hipSuccess; }
     static KernelCache kc;
-    void (*kern)(OneByOneParams) = &conv_mfma_1x1_kernel<K1>;
+    void (*kern)(OneByOneParams) = &conv_mfma_1x1_kernel<K1, GATHER>;
     if ((e = allow_dynamic_lds(kc, reinterpret_cast<const void *>(kern), lds, dev)) != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(blocks), dim3(256), lds, st, P);
     return hipGetLastError();
 }
 
-// Returns hipErrorNotSupported when the layer does not meet this kernel's conditions.  `in` is the
-// im2win tensor of the layer, which for these layers is laid out exactly like the input.
-hipError_t launch_conv_mfma_1x1(const float *in, const float *flt, float *out, const Shape &sh,
-                                hipStream_t st, LaunchPlan *plan)
+// Returns hipErrorNotSupported when the layer does not meet this kernel's conditions.  `src` is the
+// im2win tensor of the layer -- for a 1x1 filter without padding: [N][Ci][Ho][Wi], the input rows m*s --
+// or, with `implicit`, the NCHW input itself (workspace-free call).
+hipError_t launch_conv_mfma_1x1(const float *src, const float *flt, float *out, const Shape &sh,
+                                hipStream_t st, bool implicit, LaunchPlan *plan)
 {
-    if (sh.Hf != 1 || sh.Wf != 1 || sh.s != 1 || sh.p != 0) return hipErrorNotSupported;
+    if (sh.Hf != 1 || sh.Wf != 1 || sh.p != 0) return hipErrorNotSupported;
     if (sh.Ci % 8 != 0 || sh.Co % 4 != 0) return hipErrorNotSupported;   // (K steps come in groups of eight channels; filter rows are copied four at a time)
+    if (reinterpret_cast<uintptr_t>(flt) % 16u != 0) return hipErrorNotSupported;
     const long long howo = (long long)sh.Ho * sh.Wo;
-    if (howo % 4 != 0) return hipErrorNotSupported;
-    if ((reinterpret_cast<uintptr_t>(in) | reinterpret_cast<uintptr_t>(flt)) % 16u != 0) return hipErrorNotSupported;
-    // 32-bit byte offsets: a tile's pixels span at most two consecutive images (plus one plane group
-    // per load), the filter is addressed from its start
-    if ((2LL * sh.Ci + 8) * howo * 4LL >= (1LL << 32)) return hipErrorNotSupported;
+    const long long plane = implicit ? (long long)sh.Hi * sh.Wi : (long long)sh.Ho * sh.Wi;
+    // 16-byte loads of the pixels: they are contiguous and come in whole groups of four
+    const bool gather = sh.s != 1 || howo % 4 != 0 || reinterpret_cast<uintptr_t>(src) % 16u != 0;
+    // 32-bit byte offsets: the images a tile's pixels span (two; more when a plane is smaller than a tile)
+    // plus the channel offset of a load; the filter is addressed from its start
+    const long long images = howo < NB ? NB / howo + 2 : 2;
+    if ((images * sh.Ci + 8) * plane * 4LL >= (1LL << 32)) return hipErrorNotSupported;
     if ((long long)sh.Co * sh.Ci * 4LL >= (1LL << 32)) return hipErrorNotSupported;
-    if (howo < NB && (NB / howo + 2) * (long long)sh.Ci * howo * 4LL >= (1LL << 32)) return hipErrorNotSupported;
+    // (the epilogue's 32-bit output offsets: a tile's pixels within 4 GiB of its first image's first channel)
+    if ((images * sh.Co + 64) * howo * 4LL >= (1LL << 32)) return hipErrorNotSupported;
 
     OneByOneParams P;
-    P.in = in; P.flt = flt;
+    P.in = src; P.flt = flt;
     P.Ci = sh.Ci;
     P.npix = (uint32_t)sh.npix;
     P.howo = (uint32_t)howo;
     P.tiles_m = (uint32_t)((sh.Co + MB - 1) / MB);
-    P.in_elems = (size_t)sh.N * sh.Ci * (size_t)howo;
+    P.in_elems = (size_t)sh.N * sh.Ci * (size_t)plane;
     P.flt_elems = (size_t)sh.Co * sh.Ci;
     P.d_howo = make_fastdiv(P.howo);
     P.d_tm = make_fastdiv(P.tiles_m);
+    P.plane = (uint32_t)plane;
+    P.rowstep = (uint32_t)(implicit ? sh.s * sh.Wi : sh.Wi);
+    P.colstep = (uint32_t)sh.s;
+    P.Wo = (uint32_t)sh.Wo;
+    P.d_wo = make_fastdiv(P.Wo);
     P.T = MfmaParams{};
     P.T.out = out; P.T.Co = sh.Co; P.T.howo = P.howo; P.T.d_howo = P.d_howo;
     P.T.out_elems = (size_t)sh.npix * sh.Co;
-    // (the epilogue's 32-bit output offsets: a tile's pixels within 4 GiB of its first image's first channel)
-    if ((((long long)(howo < NB ? NB / howo + 2 : 2)) * sh.Co + 64) * howo * 4LL >= (1LL << 32)) return hipErrorNotSupported;
     P.ntiles = ((P.npix + NB - 1) / NB) * P.tiles_m;
     // K blocks of 32 channels leave room for four workgroups per CU, which hide each other's barriers and
     // load waits better than two with blocks of 64 (256 -> 256 channels at 28x28: 109 against 95 TFLOP/s);
     // they copy eight filter rows per instruction, hence for channel counts that are multiples of eight.
-    if (sh.Co % 8 == 0) return launch_1x1_t<32>(P, sh, st, plan);
-    return launch_1x1_t<64>(P, sh, st, plan);
+    if (sh.Co % 8 == 0)
+        return gather ? launch_1x1_t<32, true>(P, sh, st, plan) : launch_1x1_t<32, false>(P, sh, st, plan);
+    return gather ? launch_1x1_t<64, true>(P, sh, st, plan) : launch_1x1_t<64, false>(P, sh, st, plan);
 }
 
 }  // namespace im2win

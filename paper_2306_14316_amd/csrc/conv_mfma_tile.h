@@ -106,7 +106,7 @@ hipError_t launch_conv_mfma_fast(MfmaParams P, const Shape &sh, uint32_t blocks,
                                  bool implicit = false, int filter_fetch_floats = 4, LaunchPlan *plan = nullptr);
 hipError_t launch_conv_mfma_shallow(const float *win, const float *flt, float *out, const Shape &sh,
                                     hipStream_t st, bool implicit = false, LaunchPlan *plan = nullptr);
-hipError_t launch_conv_mfma_1x1(const float *in, const float *flt, float *out, const Shape &sh,
-                                hipStream_t st, LaunchPlan *plan = nullptr);
+hipError_t launch_conv_mfma_1x1(const float *src, const float *flt, float *out, const Shape &sh,
+                                hipStream_t st, bool implicit = false, LaunchPlan *plan = nullptr);
 
 }  // namespace im2win

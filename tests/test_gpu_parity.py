@@ -152,43 +152,53 @@ def test_three_channel_3x3_layer_with_many_pixels(Co, pad, Wi):
     check_layer(I, F, 1, pad, basic=False, twice=False)
 
 
-# (N, Ci, Hi, Wi, Co): 1x1 layers, stride 1, no padding; the second field of each pair says whether the
-# dedicated 1x1 kernel takes the layer (Ci a multiple of eight, Co and the plane size multiples of four)
+# (N, Ci, Hi, Wi, Co, stride): 1x1 layers without padding, and the form of the dedicated 1x1 kernel that takes
+# each: "x4" (pixels by 16-byte loads: stride 1, planes of a multiple of four pixels), "gather" (one word per
+# pixel lane: strided layers, other plane sizes) or None (Ci not a multiple of eight, Co not of four)
 ONE_BY_ONE_SHAPES = [
-    ((2, 64, 8, 8, 64), True),       # one K block, one tile per image
-    ((3, 128, 14, 14, 100), True),   # two K blocks, ragged last tile, a partial block of output channels
-    ((5, 64, 6, 6, 68), True),       # planes of 36 pixels: a tile spans three images
-    ((1, 192, 10, 10, 8), True),     # three K blocks, eight output channels
-    ((8, 256, 28, 28, 256), True),   # four K blocks, four channel blocks
-    ((2, 64, 2, 2, 64), True),       # planes of four pixels, one ragged tile over both images
-    ((3, 64, 7, 7, 64), False),      # 49 pixels per plane
-    ((2, 64, 8, 8, 66), False),      # 66 output channels
-    ((2, 96, 8, 8, 64), True),       # 96 input channels: a second K block of 32
-    ((4, 8, 16, 16, 32), True),      # eight input channels: one short block
-    ((2, 200, 12, 12, 72), True),    # 200 = 3 * 64 + 8
-    ((2, 100, 8, 8, 64), False),     # 100 input channels
+    ((2, 64, 8, 8, 64, 1), "x4"),        # one K block, one tile per image
+    ((3, 128, 14, 14, 100, 1), "x4"),    # ragged last tile, a partial block of output channels, K blocks of 64
+    ((5, 64, 6, 6, 68, 1), "x4"),        # planes of 36 pixels: a tile spans three images
+    ((1, 192, 10, 10, 8, 1), "x4"),      # eight output channels
+    ((8, 256, 28, 28, 256, 1), "x4"),    # eight K blocks, four channel blocks
+    ((2, 64, 2, 2, 64, 1), "x4"),        # planes of four pixels, one ragged tile over both images
+    ((2, 96, 8, 8, 64, 1), "x4"),        # 96 input channels
+    ((4, 8, 16, 16, 32, 1), "x4"),       # eight input channels: one short block
+    ((2, 200, 12, 12, 72, 1), "x4"),     # 200 = 6 * 32 + 8
+    ((3, 64, 7, 7, 64, 1), "gather"),    # 49 pixels per plane
+    ((4, 128, 28, 28, 256, 2), "gather"),    # stride 2: every second row and column
+    ((3, 64, 15, 13, 36, 2), "gather"),      # stride 2 on odd sizes, K blocks of 64
+    ((2, 72, 17, 9, 16, 3), "gather"),       # stride 3, a short last K block
+    ((70, 64, 3, 3, 64, 2), "gather"),       # planes of four output pixels: a tile spans sixteen images
+    ((2, 64, 8, 8, 66, 1), None),        # 66 output channels
+    ((2, 100, 8, 8, 64, 1), None),       # 100 input channels
 ]
 
 
-@pytest.mark.parametrize("dims,dedicated", ONE_BY_ONE_SHAPES, ids=lambda v: "x".join(map(str, v)) if isinstance(v, tuple) else str(v))
-def test_one_by_one_layers(dims, dedicated):
-    """1x1 convolutions: a plain GEMM over the channel planes (the im2win tensor is the input's own
-    layout); both calls and the workspace-free call, every element, bit-identical between the two."""
-    N, Ci, Hi, Wi, Co = dims
-    shape = (N, Ci, Hi, Wi, Co, 1, 1, 1, 0)
+@pytest.mark.parametrize("dims,form", ONE_BY_ONE_SHAPES, ids=lambda v: "x".join(map(str, v)) if isinstance(v, tuple) else str(v))
+def test_one_by_one_layers(dims, form):
+    """1x1 convolutions: a plain GEMM over the channel planes (with stride 1 the im2win tensor is the
+    input's own layout); both calls and the workspace-free call, every element, bit-identical between
+    the two where the dedicated kernel runs."""
+    N, Ci, Hi, Wi, Co, st = dims
+    shape = (N, Ci, Hi, Wi, Co, 1, 1, st, 0)
     name = im2win.conv2d_im2win_fwd_launch_info(*shape)["kernel"]
-    assert name.startswith("conv_mfma_1x1_kernel<") == dedicated, name
+    want = {"x4": ", false>", "gather": ", true>"}
+    if form is None:
+        assert not name.startswith("conv_mfma_1x1_kernel<"), name
+    else:
+        assert name.startswith("conv_mfma_1x1_kernel<") and name.endswith(want[form]), name
     I, F = workloads.random_layer_inputs(8800 + sum(dims), N, Ci, Hi, Wi, Co, 1, 1)
     print("1x1", dims, name, flush=True)
-    check_layer(I, F, 1, 0, basic=False)
-    dW = run_transform(I, 1, 1, 1, 0)
-    dO = run_conv(dW, F, N, Ci, Hi, Wi, 1, 0)
+    check_layer(I, F, st, 0, basic=False)
+    dW = run_transform(I, 1, 1, st, 0)
+    dO = run_conv(dW, F, N, Ci, Hi, Wi, st, 0)
     dO2 = torch.full_like(dO, float("nan"))
-    im2win.conv2d_im2win_implicit_fwd(I.cuda(), F.cuda(), dO2, N, Ci, Hi, Wi, Co, 1, 1, 1, 0)
+    im2win.conv2d_im2win_implicit_fwd(I.cuda(), F.cuda(), dO2, N, Ci, Hi, Wi, Co, 1, 1, st, 0)
     torch.cuda.synchronize()
-    O_ref, B_ref = oracle.conv2d_direct(I.numpy(), F.numpy(), 1, 0)
+    O_ref, B_ref = oracle.conv2d_direct(I.numpy(), F.numpy(), st, 0)
     assert_conv_close(dO2.cpu().numpy(), O_ref, B_ref)
-    if dedicated:
+    if form is not None:
         assert torch.equal(dO.view(torch.int32), dO2.view(torch.int32))
 
 

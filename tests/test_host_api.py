@@ -155,9 +155,10 @@ def test_launch_info_names_the_dispatch(lib):
         "conv_mfma_fast_kernel<3, 3, 8, 1, 4, 3, false, false, false, false, true>"
     assert im2win.conv2d_im2win_fwd_launch_info(8, 7, 56, 56, 64, 3, 3, 1, 1)["kernel"] == "conv_mfma_kernel<9, false>"
     # 1x1 and asymmetric filters: the pipelined generic kernel; its single-stage form when two stages do not fit LDS
-    assert im2win.conv2d_im2win_fwd_launch_info(64, 256, 28, 28, 256, 1, 1, 1, 0)["kernel"] == "conv_mfma_1x1_kernel<32>"
-    assert im2win.conv2d_im2win_fwd_launch_info(64, 256, 28, 28, 256, 1, 1, 1, 0, workspace_free=True)["kernel"] == "conv_mfma_1x1_kernel<32>"
-    assert im2win.conv2d_im2win_fwd_launch_info(64, 256, 28, 28, 256, 1, 1, 2, 0)["kernel"] == "conv_mfma_pipe_kernel<1, 1>"   # strided
+    assert im2win.conv2d_im2win_fwd_launch_info(64, 256, 28, 28, 256, 1, 1, 1, 0)["kernel"] == "conv_mfma_1x1_kernel<32, false>"
+    assert im2win.conv2d_im2win_fwd_launch_info(64, 256, 28, 28, 256, 1, 1, 1, 0, workspace_free=True)["kernel"] == "conv_mfma_1x1_kernel<32, false>"
+    assert im2win.conv2d_im2win_fwd_launch_info(64, 256, 28, 28, 256, 1, 1, 2, 0)["kernel"] == "conv_mfma_1x1_kernel<32, true>"   # strided
+    assert im2win.conv2d_im2win_fwd_launch_info(64, 252, 28, 28, 256, 1, 1, 1, 0)["kernel"] == "conv_mfma_pipe_kernel<1, 1>"
     assert im2win.conv2d_im2win_fwd_launch_info(64, 64, 28, 28, 64, 1, 7, 1, 0)["kernel"] == "conv_mfma_pipe_kernel<0, 0>"
     assert im2win.conv2d_im2win_fwd_launch_info(2, 3, 35, 35, 96, 11, 11, 4, 0)["kernel"] == "conv_mfma_kernel<121, false>"
     assert im2win.conv2d_im2win_fwd_launch_info(2, 10, 35, 35, 96, 9, 9, 2, 0)["kernel"] == "conv_mfma_pipe_kernel<0, 0>"
