@@ -75,6 +75,7 @@ EXTRA = (
     Layer("extra_1x1_c64_56_co256", 64, 64, 56, 56, 256, 1, 1, 1, 0, 3005, "uniform01", "he_normal"),
     Layer("extra_1x1_c1024_14_co256", 64, 1024, 14, 14, 256, 1, 1, 1, 0, 3006, "uniform01", "he_normal"),
     Layer("extra_1x1_s2_c256_56_co512", 64, 256, 56, 56, 512, 1, 1, 2, 0, 3007, "uniform01", "he_normal"),
+    Layer("extra_1x1_c2048_7_co512", 128, 2048, 7, 7, 512, 1, 1, 1, 0, 3008, "uniform01", "he_normal"),
 )
 
 
