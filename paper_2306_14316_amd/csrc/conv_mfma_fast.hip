@@ -704,7 +704,7 @@ static hipError_t launch_fast_t(const MfmaParams &P, uint32_t blocks, hipStream_
     constexpr size_t lds = 2u * 4u * (size_t)(((MB * PF + 3) & ~3) + CB * 256 * JX);
     if (P.Ci % CB != 0) {
         // ragged last K block: whole tiles, one per workgroup (only the 16-byte filter-fetch instances exist)
-        if constexpr (CW == (HF == 7 ? 2 : 4)) {
+        if constexpr (CW == ((HF == 7 && WF == 7) ? 2 : 4)) {
             MfmaParams Q = P;
             Q.nblocks = blocks; Q.nmain = blocks; Q.nhalf = 0; Q.tail_at = blocks;
             void (*kern)(MfmaParams) = &conv_mfma_fast_kernel<HF, WF, CB, JX, CW, OCC, IMP, false, false, false, true>;
@@ -838,6 +838,21 @@ hipError_t launch_conv_mfma_fast(MfmaParams P, const Shape &sh, uint32_t blocks,
     if (sh.Hf == 7 && sh.Wf == 7 && sh.Ci >= 2 && al8) {
         if (P.S <= 512) return launch_fast_i<7, 7, 2, 2, 2, 2>(P, blocks, st, implicit, plan);
         if (P.S <= 1024) return launch_fast_i<7, 7, 2, 4, 2, 2>(P, blocks, st, implicit, plan);
+    }
+    // Asymmetric filters (1x7 / 7x1 and 1x3 / 3x1 pairs that factor a square filter): the same pipeline
+    // with eight (sixteen) channels per K block; a column filter's strips are Hf times longer.
+    if (sh.Hf == 1 && sh.Wf == 7 && sh.Ci >= 8 && al16) {
+        if (P.S <= 256) return launch_fast_i<1, 7, 8, 1, 4, 3>(P, blocks, st, implicit, plan);
+        if (P.S <= 512) return launch_fast_i<1, 7, 8, 2, 4, 2>(P, blocks, st, implicit, plan);
+    }
+    if (sh.Hf == 7 && sh.Wf == 1 && sh.Ci >= 8 && al16) {
+        if (P.S <= 512) return launch_fast_i<7, 1, 8, 2, 4, 2>(P, blocks, st, implicit, plan);
+    }
+    if (sh.Hf == 1 && sh.Wf == 3 && sh.Ci >= 16 && al16) {
+        if (P.S <= 256) return launch_fast_i<1, 3, 16, 1, 4, 2>(P, blocks, st, implicit, plan);
+    }
+    if (sh.Hf == 3 && sh.Wf == 1 && sh.Ci >= 16 && al16) {
+        if (P.S <= 256) return launch_fast_i<3, 1, 16, 1, 4, 2>(P, blocks, st, implicit, plan);
     }
     return hipErrorNotSupported;
 }

@@ -65,8 +65,8 @@ EDGE_SHAPES = [
     (2, 64, 14, 14, 70, 1, 1, 1, 0),     # 1x1, one block: single-stage kernel
     (1, 230, 9, 9, 40, 1, 1, 2, 0),      # 1x1 strided, 64 + 64 + 64 + 38 channels
     (1, 193, 12, 12, 20, 1, 1, 1, 1),    # 1x1 padded, odd channel count: a split step in the last block
-    (2, 34, 9, 30, 40, 1, 7, 1, 0),      # 1x7: eight channels per block, five blocks, the last with two
-    (2, 27, 30, 9, 40, 7, 1, 1, 3),      # 7x1 padded, odd channel count: a split step in the last block
+    (2, 50, 9, 30, 40, 1, 5, 1, 0),      # 1x5: twelve channels per block, five blocks, the last with two
+    (2, 43, 30, 9, 40, 6, 1, 1, 3),      # 6x1 padded, odd channel count: a split step in the last block
     (1, 37, 12, 14, 24, 2, 4, 2, 1),     # 2x4 stride 2: eight channels per block, five blocks, the last with five
     (1, 7, 24, 24, 12, 9, 9, 1, 0),      # 9x9: two channels per block, four blocks, a split step in the last
     (1, 3, 24, 24, 12, 9, 9, 1, 0),      # 9x9 with three channels: too few blocks, single-stage kernel
@@ -243,6 +243,47 @@ def test_many_tiles_per_workgroup(shape):
     im2win.conv2d_im2win_implicit_fwd(I.cuda(), F.cuda(), dO2, N, Ci, Hi, Wi, Co, Hf, Wf, s, p)
     torch.cuda.synchronize()
     assert torch.equal(dO.view(torch.int32), dO2.view(torch.int32))
+
+
+# Asymmetric filters with instances of the pipelined kernel (1x7 / 7x1 with eight channels per K block,
+# 1x3 / 3x1 with sixteen), and the neighbours that stay with the generic kernels.
+ASYMMETRIC_SHAPES = [
+    ((4, 16, 20, 40, 70, 1, 7, 1, 0), True),     # 1x7, two K blocks, a partial block of output channels
+    ((2, 24, 17, 150, 64, 1, 7, 2, 3), True),    # 1x7 stride 2, padded
+    ((2, 8, 9, 300, 16, 1, 7, 4, 0), True),      # 1x7 stride 4: two strip words per thread
+    ((2, 34, 9, 30, 40, 1, 7, 1, 0), True),      # 1x7, 34 channels: a last K block with two
+    ((3, 16, 40, 20, 70, 7, 1, 1, 3), True),     # 7x1 padded
+    ((2, 27, 30, 9, 40, 7, 1, 1, 3), True),      # 7x1, 27 channels: a last K block with three
+    ((2, 8, 60, 9, 24, 7, 1, 2, 0), False),      # 7x1 stride 2: a tile's strips are longer than the instance's
+    ((2, 32, 14, 30, 40, 1, 3, 1, 1), True),     # 1x3 padded, two K blocks of sixteen channels
+    ((2, 40, 14, 30, 40, 1, 3, 1, 1), True),     # 1x3, 40 channels: half a K block left over
+    ((2, 48, 30, 14, 40, 3, 1, 1, 0), True),     # 3x1
+    ((1, 17, 30, 14, 72, 3, 1, 2, 1), False),    # 3x1 stride 2: strips longer than the instance's
+    ((1, 17, 30, 14, 72, 1, 3, 2, 1), True),     # 1x3 stride 2, 17 channels
+    ((2, 12, 14, 30, 40, 1, 3, 1, 1), False),    # 1x3 with fewer channels than a K block
+    ((48, 16, 56, 56, 64, 1, 7, 1, 3), True),    # 1x7: several tiles per workgroup
+    ((32, 32, 56, 56, 64, 3, 1, 1, 1), True),    # 3x1: several tiles per workgroup
+]
+
+
+@pytest.mark.parametrize("shape,pipelined", ASYMMETRIC_SHAPES, ids=lambda v: "x".join(map(str, v)) if isinstance(v, tuple) else str(v))
+def test_asymmetric_filters(shape, pipelined):
+    N, Ci, Hi, Wi, Co, Hf, Wf, s, p = shape
+    name = im2win.conv2d_im2win_fwd_launch_info(*shape)["kernel"]
+    assert name.startswith("conv_mfma_fast_kernel<%d, %d," % (Hf, Wf)) == pipelined, name
+    I, F = workloads.random_layer_inputs(7700 + sum(shape), N, Ci, Hi, Wi, Co, Hf, Wf)
+    print("asymmetric", shape, name, flush=True)
+    check_layer(I, F, s, p, basic=False, twice=False)
+    dW = run_transform(I, Hf, Wf, s, p)
+    dO = run_conv(dW, F, N, Ci, Hi, Wi, s, p)
+    dO2 = torch.full_like(dO, float("nan"))
+    im2win.conv2d_im2win_implicit_fwd(I.cuda(), F.cuda(), dO2, N, Ci, Hi, Wi, Co, Hf, Wf, s, p)
+    torch.cuda.synchronize()
+    if pipelined:   # the workspace-free variant runs the same pipeline from the input: same bits
+        assert torch.equal(dO.view(torch.int32), dO2.view(torch.int32))
+    else:
+        O_ref, B_ref = oracle.conv2d_direct(I.numpy(), F.numpy(), s, p)
+        assert_conv_close(dO2.cpu().numpy(), O_ref, B_ref)
 
 
 # Layers whose tile count leaves a few tiles (at most an eighth of the compute units) after the
