@@ -854,6 +854,11 @@ hipError_t launch_conv_mfma_fast(MfmaParams P, const Shape &sh, uint32_t blocks,
     if (sh.Hf == 3 && sh.Wf == 1 && sh.Ci >= 16 && al16) {
         if (P.S <= 256) return launch_fast_i<3, 1, 16, 1, 4, 2>(P, blocks, st, implicit, plan);
     }
+    // 4x4 (the stride-2 down- and up-sampling layers of generator / discriminator networks): four channels per block
+    if (sh.Hf == 4 && sh.Wf == 4 && sh.Ci >= 4 && al16) {
+        if (P.S <= 512) return launch_fast_i<4, 4, 4, 2, 4, 2>(P, blocks, st, implicit, plan);
+        if (P.S <= 768) return launch_fast_i<4, 4, 4, 3, 4, 2>(P, blocks, st, implicit, plan);
+    }
     return hipErrorNotSupported;
 }
 

@@ -66,7 +66,8 @@ TABLE2 = (
 
 
 # Layers off the specialised kernels' grid, timed by `bench.py --extra`: a channel count that is not a
-# multiple of the pipelined kernel's K block, 1x1 layers (expanding, reducing, strided), an asymmetric filter.
+# multiple of the pipelined kernel's K block, 1x1 layers (expanding, reducing, strided, 7x7 planes), row and
+# column filters, a 4x4 stride-2 layer.
 EXTRA = (
     Layer("extra_3x3_c60_56", 32, 60, 56, 56, 64, 3, 3, 1, 1, 3001, "uniform01", "he_normal"),
     Layer("extra_3x3_c100_28", 64, 100, 28, 28, 128, 3, 3, 1, 1, 3002, "uniform01", "he_normal"),
@@ -76,6 +77,8 @@ EXTRA = (
     Layer("extra_1x1_c1024_14_co256", 64, 1024, 14, 14, 256, 1, 1, 1, 0, 3006, "uniform01", "he_normal"),
     Layer("extra_1x1_s2_c256_56_co512", 64, 256, 56, 56, 512, 1, 1, 2, 0, 3007, "uniform01", "he_normal"),
     Layer("extra_1x1_c2048_7_co512", 128, 2048, 7, 7, 512, 1, 1, 1, 0, 3008, "uniform01", "he_normal"),
+    Layer("extra_7x1_c128_17_co192", 128, 128, 17, 17, 192, 7, 1, 1, 3, 3009, "uniform01", "he_normal"),
+    Layer("extra_4x4_s2_c64_64_co128", 64, 64, 64, 64, 128, 4, 4, 2, 1, 3010, "uniform01", "he_normal"),
 )
 
 

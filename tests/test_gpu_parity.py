@@ -245,8 +245,8 @@ def test_many_tiles_per_workgroup(shape):
     assert torch.equal(dO.view(torch.int32), dO2.view(torch.int32))
 
 
-# Asymmetric filters with instances of the pipelined kernel (1x7 / 7x1 with eight channels per K block,
-# 1x3 / 3x1 with sixteen), and the neighbours that stay with the generic kernels.
+# Filters other than 3x3 / 5x5 / 7x7 with instances of the pipelined kernel (1x7 / 7x1 with eight channels per
+# K block, 1x3 / 3x1 with sixteen, 4x4 with four), and the neighbours that stay with the generic kernels.
 ASYMMETRIC_SHAPES = [
     ((4, 16, 20, 40, 70, 1, 7, 1, 0), True),     # 1x7, two K blocks, a partial block of output channels
     ((2, 24, 17, 150, 64, 1, 7, 2, 3), True),    # 1x7 stride 2, padded
@@ -263,6 +263,13 @@ ASYMMETRIC_SHAPES = [
     ((2, 12, 14, 30, 40, 1, 3, 1, 1), False),    # 1x3 with fewer channels than a K block
     ((48, 16, 56, 56, 64, 1, 7, 1, 3), True),    # 1x7: several tiles per workgroup
     ((32, 32, 56, 56, 64, 3, 1, 1, 1), True),    # 3x1: several tiles per workgroup
+    ((2, 8, 20, 20, 40, 4, 4, 2, 1), True),      # 4x4 stride 2: a tile spans seven rows
+    ((2, 64, 64, 64, 64, 4, 4, 2, 1), True),     # 4x4 stride 2, sixteen K blocks, two rows per tile
+    ((1, 16, 16, 130, 16, 4, 4, 2, 1), True),    # 4x4 stride 2, rows of 65 pixels
+    ((2, 12, 12, 30, 24, 4, 4, 1, 0), True),     # 4x4 stride 1, three K blocks
+    ((2, 6, 12, 30, 24, 4, 4, 1, 2), True),      # 4x4, six channels: half a K block left over
+    ((2, 8, 32, 32, 96, 4, 4, 4, 0), False),     # 4x4 stride 4: strips longer than the instances'
+    ((32, 8, 112, 112, 64, 4, 4, 2, 1), True),   # 4x4 stride 2: several tiles per workgroup
 ]
 
 
