@@ -834,6 +834,7 @@ hipError_t launch_conv_mfma_fast(MfmaParams P, const Shape &sh, uint32_t blocks,
     if (sh.Hf == 5 && sh.Wf == 5 && sh.Ci >= 4 && al16) {
         if (P.S <= 256) return launch_fast_i<5, 5, 4, 1, 4, 2>(P, blocks, st, implicit, plan);
         if (P.S <= 512) return launch_fast_i<5, 5, 4, 2, 4, 2>(P, blocks, st, implicit, plan);
+        if (P.S <= 768) return launch_fast_i<5, 5, 4, 3, 4, 2>(P, blocks, st, implicit, plan);   // (stride 2)
     }
     if (sh.Hf == 7 && sh.Wf == 7 && sh.Ci >= 2 && al8) {
         if (P.S <= 512) return launch_fast_i<7, 7, 2, 2, 2, 2>(P, blocks, st, implicit, plan);
@@ -858,6 +859,11 @@ hipError_t launch_conv_mfma_fast(MfmaParams P, const Shape &sh, uint32_t blocks,
     if (sh.Hf == 4 && sh.Wf == 4 && sh.Ci >= 4 && al16) {
         if (P.S <= 512) return launch_fast_i<4, 4, 4, 2, 4, 2>(P, blocks, st, implicit, plan);
         if (P.S <= 768) return launch_fast_i<4, 4, 4, 3, 4, 2>(P, blocks, st, implicit, plan);
+    }
+    // 2x2 (stride-2 down-sampling): sixteen channels per block.  (P.S counts one float more than the
+    // strips hold; at stride 2 a tile's 64 windows are exactly 256 floats.)
+    if (sh.Hf == 2 && sh.Wf == 2 && sh.Ci >= 16 && al16) {
+        if (P.S - 1 <= 256) return launch_fast_i<2, 2, 16, 1, 4, 2>(P, blocks, st, implicit, plan);
     }
     return hipErrorNotSupported;
 }

@@ -246,7 +246,8 @@ def test_many_tiles_per_workgroup(shape):
 
 
 # Filters other than 3x3 / 5x5 / 7x7 with instances of the pipelined kernel (1x7 / 7x1 with eight channels per
-# K block, 1x3 / 3x1 with sixteen, 4x4 with four), and the neighbours that stay with the generic kernels.
+# K block, 1x3 / 3x1 / 2x2 with sixteen, 4x4 with four; 5x5 at stride 2), and the neighbours that stay with the
+# generic kernels.
 ASYMMETRIC_SHAPES = [
     ((4, 16, 20, 40, 70, 1, 7, 1, 0), True),     # 1x7, two K blocks, a partial block of output channels
     ((2, 24, 17, 150, 64, 1, 7, 2, 3), True),    # 1x7 stride 2, padded
@@ -270,6 +271,12 @@ ASYMMETRIC_SHAPES = [
     ((2, 6, 12, 30, 24, 4, 4, 1, 2), True),      # 4x4, six channels: half a K block left over
     ((2, 8, 32, 32, 96, 4, 4, 4, 0), False),     # 4x4 stride 4: strips longer than the instances'
     ((32, 8, 112, 112, 64, 4, 4, 2, 1), True),   # 4x4 stride 2: several tiles per workgroup
+    ((2, 16, 20, 20, 40, 2, 2, 2, 0), True),     # 2x2 stride 2, one K block of sixteen channels
+    ((2, 48, 33, 31, 70, 2, 2, 2, 1), True),     # 2x2 stride 2 padded, odd sizes
+    ((2, 40, 16, 16, 24, 2, 2, 1, 0), True),     # 2x2 stride 1, 40 channels: half a K block left over
+    ((32, 32, 112, 112, 64, 2, 2, 2, 0), True),  # 2x2 stride 2: several tiles per workgroup
+    ((2, 8, 24, 100, 40, 5, 5, 2, 2), True),     # 5x5 stride 2: three strip words per thread
+    ((1, 10, 30, 110, 70, 5, 5, 2, 0), True),    # 5x5 stride 2, ten channels: half a K block left over
 ]
 
 
