@@ -245,7 +245,8 @@ __global__ __launch_bounds__(256) void conv_mfma_kernel(MfmaParams P)
 
 // ---------------------------------------------------------------------------
 // Pipelined form of the generic kernel (the double buffer and prefetch of Section 3.3 for the layers
-// none of the specialised kernels takes: 1x1 and asymmetric filters, few channels).  Same tile,
+// none of the specialised kernels takes: padded 1x1, filter shapes without an instance of the
+// software-pipelined kernel, few channels).  Same tile,
 // strip geometry and K order as conv_mfma_kernel, but two LDS stages, and both operands of K block
 // kb+1 travel from global memory straight into the other stage (buffer loads with the LDS
 // destination in M0: no staging registers, no LDS store instructions) while the matrix cores work

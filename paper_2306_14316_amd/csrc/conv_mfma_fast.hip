@@ -1,6 +1,6 @@
 // Software-pipelined MFMA im2win convolution for layers with many input
 // channels and a compile-time filter (3x3, 5x5, 7x7: all multi-channel layers of
-// the paper's Table 2).  Same 64x64 tile, strip geometry and pair-step K order
+// the paper's Table 2; also 1x7, 7x1, 1x3, 3x1, 2x2 and 4x4).  Same 64x64 tile, strip geometry and pair-step K order
 // as conv_mfma.hip; what differs:
 //   - the filter shape and the channels per K block are template constants,
 //     so every LDS operand address is base + immediate and all staging

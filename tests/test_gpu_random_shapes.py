@@ -129,3 +129,46 @@ def test_random_shape_leftover_tiles(shape):
     im2win.conv2d_im2win_implicit_fwd(I.cuda(), F.cuda(), dO2, N, Ci, Hi, Wi, Co, Hf, Wf, s, p)
     torch.cuda.synchronize()
     assert torch.equal(dO.view(torch.int32), dO2.view(torch.int32))
+
+
+def _other_filter_shapes(seed, count):
+    """Row, column, 2x2, 4x4 and 1x1 filters with enough channels for their instances of the pipelined
+    kernel (and the 1x1 kernel), strides 1 to 3, paddings up to the filter's reach, ragged channel counts."""
+    rng = np.random.default_rng(seed)
+    filters = [(1, 7), (7, 1), (1, 3), (3, 1), (2, 2), (4, 4), (1, 1), (5, 5)]
+    out = []
+    while len(out) < count:
+        Hf, Wf = filters[int(rng.integers(0, len(filters)))]
+        Ci = int(rng.choice([8, 16, 17, 24, 32, 40, 64, 72]))
+        s = int(rng.choice([1, 1, 2, 2, 3]))
+        p = 0 if Hf == Wf == 1 else int(rng.integers(0, min(Hf, Wf) + 1))
+        Hi, Wi = int(rng.integers(max(Hf, 2), 40)), int(rng.integers(max(Wf, 2), 80))
+        Co = int(rng.choice([8, 20, 36, 64, 64, 72, 100, 128]))
+        N = int(rng.integers(1, 12))
+        Ho, Wo = (Hi + 2 * p - Hf) // s + 1, (Wi + 2 * p - Wf) // s + 1
+        if Ho < 1 or Wo < 1 or N * Co * Ho * Wo * Ci * Hf * Wf > 6e8:
+            continue
+        out.append((N, Ci, Hi, Wi, Co, Hf, Wf, s, p))
+    return out
+
+
+OTHER_FILTER_SHAPES = _other_filter_shapes(20230616, 40)
+
+
+@pytest.mark.parametrize("shape", OTHER_FILTER_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_random_shape_other_filters(shape):
+    N, Ci, Hi, Wi, Co, Hf, Wf, s, p = shape
+    I, F = workloads.random_layer_inputs(4200 + sum(shape), N, Ci, Hi, Wi, Co, Hf, Wf)
+    name = im2win.conv2d_im2win_fwd_launch_info(*shape)["kernel"]
+    print("random other-filter shape", shape, name, flush=True)
+    O_ref, B_ref = oracle.conv2d_direct(I.numpy(), F.numpy(), s, p)
+    dW = run_transform(I, Hf, Wf, s, p)
+    assert_bitwise_equal(dW, oracle.im2win(I.numpy(), Hf, Wf, s, p))
+    dO = run_conv(dW, F, N, Ci, Hi, Wi, s, p)
+    assert_conv_close(dO.cpu().numpy(), O_ref, B_ref)
+    dO2 = torch.full_like(dO, POISON)
+    im2win.conv2d_im2win_implicit_fwd(I.cuda(), F.cuda(), dO2, N, Ci, Hi, Wi, Co, Hf, Wf, s, p)
+    torch.cuda.synchronize()
+    assert_conv_close(dO2.cpu().numpy(), O_ref, B_ref)
+    if not name.startswith("conv_mfma_pipe_kernel"):
+        assert torch.equal(dO.view(torch.int32), dO2.view(torch.int32))
