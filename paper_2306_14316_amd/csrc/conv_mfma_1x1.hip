@@ -6,9 +6,12 @@
 // the address path of the memory pipeline takes four lanes per cycle whatever their width, so two
 // resident workgroups already saturate it.  This kernel moves the same bytes with 16-byte
 // direct-to-LDS loads (buffer_load_dwordx4 ... lds, new on gfx950):
-//   - tile 64 channels x 64 pixels, K blocks of 32 (or 64) input channels (the last one may be shorter), two LDS
-//     stages; persistent workgroups run their tiles as one sequence of blocks, the loads of the next block
-//     (of the next tile, after a tile's last) in flight while the matrix cores work; one barrier per block;
+//   - tile 64 (or 128) channels x 64 pixels, K blocks of 32 (or 64) input channels (the last one may be
+//     shorter), a ring of NST LDS stages; a workgroup runs its tiles as one sequence of blocks, the loads of
+//     the next NST - 1 blocks (of the next tile, after a tile's last) in flight while the matrix cores work;
+//     one barrier per block.  Two stages are the fastest: a third (loads two blocks ahead) costs a resident
+//     workgroup per CU, and four workgroups hide each other's waits better than deeper prefetch does
+//     (512 -> 512 channels at 14x14: 117 TFLOP/s with two stages, 112 with three, 97 with four);
 //   - B (pixels): [channel][64 pixels], one wave instruction copies four channel rows (4 x 256
 //     contiguous bytes of four planes) into 1 KB of LDS; a lane's B read is base + immediate;
 //   - A (filter): [row][K1 k], pitch K1 floats, the 16-byte chunks of a row stored at slot
@@ -29,8 +32,9 @@ namespace im2win {
 typedef __attribute__((address_space(3))) void lds_void_t;
 typedef float float4v_t __attribute__((ext_vector_type(4)));
 
-// K1: input channels per K block (64 or 32).  floats per LDS stage: B [K1][NB], then A [MB][K1]
-template <int K1> constexpr int stage1_floats() { return K1 * NB + MB * K1; }
+// K1: input channels per K block (64 or 32); MT: blocks of 64 output channels per workgroup tile (1 or 2).
+// floats per LDS stage: B [K1][NB], then A [MT * MB][K1]
+template <int K1, int MT> constexpr int stage1_floats() { return K1 * NB + MT * MB * K1; }
 
 struct OneByOneParams {
     const float *in;     // [N][Ci][howo]
@@ -46,7 +50,16 @@ struct OneByOneParams {
     FastDiv d_wo;
 };
 
-// What the loads and the epilogue need to know about a tile.
+// LDS stages of the K blocks of 32 and largest tile height in blocks of 64 channels (build-time choices,
+// measured; see the header and the launcher)
+#ifndef ONE_BY_ONE_STAGES
+#define ONE_BY_ONE_STAGES 2
+#endif
+#ifndef ONE_BY_ONE_MT
+#define ONE_BY_ONE_MT 2
+#endif
+
+// What the loads need to know about a tile.
 struct OneByOneTile {
     uint32_t P0, Pend;
     int m0;
@@ -60,15 +73,20 @@ struct OneByOneTile {
 // 64 pixels per instruction, each lane fetching its own pixel -- into the same LDS layout; the filter
 // still travels 16 bytes per lane.  (Eight such loads per wave and K block of 32 channels keep the
 // address path of the memory pipeline busy for half of the block's MFMA time.)
-template <int K1, bool GATHER>
+// MT = 2: the workgroup's tile is 128 output channels x 64 pixels, every wave owns two 32x32 blocks (rows
+// r and r + 64) whose MFMA chains are independent and share their pixel operand: half the pixel traffic and
+// LDS reads per MFMA, and two chains to interleave.
+template <int K1, bool GATHER, int NST, bool RAG, int MT>
 __global__ __launch_bounds__(256) void conv_mfma_1x1_kernel(OneByOneParams P)
 {
-    constexpr int STAGE1 = stage1_floats<K1>();
+    static_assert(NST >= 2 && NST <= 4, "two to four LDS stages");
+    static_assert(MT == 1 || MT == 2, "one or two blocks of 64 output channels");
+    constexpr int STAGE1 = stage1_floats<K1, MT>();
     constexpr int CPR = K1 / 4;          // 16-byte chunks per filter row and block
     constexpr int RPI = 64 / CPR;        // filter rows per load instruction (a wave's 1 KB)
     constexpr int NI = K1 / 16;          // load instructions per wave, block and operand
     extern __shared__ __align__(16) unsigned char smem[];
-    float *lds = reinterpret_cast<float *>(smem);   // two stages
+    float *lds = reinterpret_cast<float *>(smem);   // NST stages
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -88,7 +106,7 @@ __global__ __launch_bounds__(256) void conv_mfma_1x1_kernel(OneByOneParams P)
     auto geometry = [&](uint32_t t) __attribute__((always_inline)) {
         OneByOneTile T;
         const uint32_t tile_n = fdiv(t, P.d_tm);
-        T.m0 = (int)(t - tile_n * P.tiles_m) * MB;
+        T.m0 = (int)(t - tile_n * P.tiles_m) * (MT * MB);
         T.P0 = tile_n * NB;
         T.Pend = min(T.P0 + NB - 1, P.npix - 1);
         const uint32_t img0 = fdiv(T.P0, P.d_howo);
@@ -123,33 +141,34 @@ __global__ __launch_bounds__(256) void conv_mfma_1x1_kernel(OneByOneParams P)
     const __amdgpu_buffer_rsrc_t ra = desc(P.flt, P.flt_elems);
     const uint32_t plane4 = P.plane * 4u;
 
-    // K block kb of tile T on its way into stage st: wave w issues instructions w, w+4, w+8, w+12 of
-    // each operand.  The last block may hold fewer than 64 channels (a multiple of eight): the channel
-    // groups it does not have are not fetched, and the filter chunks past the row's end (whatever
-    // follows in memory, zeros past the tensor) land in slots no MFMA of that block reads.
+    // K block kb of tile T on its way into stage st: wave w issues instructions w, w+4, ... of each operand,
+    // the same number for every block (the wait below counts them).  The last block may hold fewer than K1
+    // channels (a multiple of eight): the channel groups it does not have re-read the layer's last channels,
+    // and the filter chunks past the row's end bring whatever follows in memory (zeros past the tensor); both
+    // land in slots no MFMA of that block reads.
+    constexpr int LPI = (GATHER ? K1 / 4 : NI) + MT * NI;     // load instructions per wave and block
     auto issue = [&](const OneByOneTile &T, int kb, int st) __attribute__((always_inline)) {
         float *sB = lds + st * STAGE1, *sA = sB + K1 * NB;
         const __amdgpu_buffer_rsrc_t rb = desc(P.in + T.b_tile, P.in_elems - T.b_tile);
-        const int nch = min(K1, P.Ci - kb * K1);
         if constexpr (GATHER) {
 #pragma unroll
             for (int j = 0; j < K1 / 4; ++j) {
                 const int c = wave + 4 * j;                   // channel c of the block: its 64 pixels
-                if (c < nch)
-                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (lds_void_t *)(sB + c * NB), 4, T.b_voff,
-                                                             (uint32_t)(kb * K1 + c) * plane4, 0, 0);
+                const int ch = min(kb * K1 + c, P.Ci - 1);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (lds_void_t *)(sB + c * NB), 4, T.b_voff,
+                                                         (uint32_t)ch * plane4, 0, 0);
             }
         } else {
 #pragma unroll
             for (int j = 0; j < NI; ++j) {
                 const int I = wave + 4 * j;                   // channels 4I .. 4I+3 of the block
-                if (4 * I < nch)
-                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (lds_void_t *)(sB + I * 256), 16, T.b_voff,
-                                                             (uint32_t)(kb * K1 + 4 * I) * plane4, 0, 0);
+                const int ch = min(kb * K1 + 4 * I, P.Ci - 4);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (lds_void_t *)(sB + I * 256), 16, T.b_voff,
+                                                         (uint32_t)ch * plane4, 0, 0);
             }
         }
 #pragma unroll
-        for (int j = 0; j < NI; ++j) {
+        for (int j = 0; j < MT * NI; ++j) {
             const int I = wave + 4 * j;                       // filter rows RPI*I .. of the tile
             const int row = min(T.m0 + RPI * I, P.T.Co - RPI);
             __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (lds_void_t *)(sA + I * 256), 16, a_voff,
@@ -163,52 +182,106 @@ __global__ __launch_bounds__(256) void conv_mfma_1x1_kernel(OneByOneParams P)
     const int a_lane = K1 * NB + row * K1;
     const int nkb = (P.Ci + K1 - 1) / K1;
 
-    // One flat sequence of K blocks over all of the workgroup's tiles: the loads of the next block -- the
-    // next tile's first one after a tile's last -- are always in flight while the matrix cores work, and
-    // a tile's stores go out while its successor's first block arrives.
-    OneByOneTile cur = geometry(tile0);
-    issue(cur, 0, 0);
+    // One flat sequence of K blocks over all of the workgroup's tiles.  The loads run NST - 1 blocks ahead of
+    // the matrix cores -- into the next tile after a tile's last block, so a tile's stores go out while its
+    // successor's first blocks arrive.  "Issue cursor": the block whose loads go out next.
+    uint32_t t_i = tile0;
+    int kb_i = 0;
+    bool live = true;                                         // blocks are left to request
+    OneByOneTile Ti = geometry(tile0);
+    auto issue_next = [&](int st) __attribute__((always_inline)) {
+        issue(Ti, kb_i, st);
+        if (++kb_i == nkb) {
+            kb_i = 0;
+            t_i += tstep;
+            if (t_i < P.ntiles) Ti = geometry(t_i); else live = false;
+        }
+    };
+#pragma unroll
+    for (int i = 0; i < NST - 1; ++i)
+        if (live) issue_next(i);
     int st = 0;
     for (uint32_t t = tile0; t < P.ntiles; t += tstep) {
-        const bool more = t + tstep < P.ntiles;
-        OneByOneTile nxt = cur;
-        floatx16 acc;
+        floatx16 acc[MT];
 #pragma unroll
-        for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
-        for (int kb = 0; kb < nkb; ++kb, st ^= 1) {
-            __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): this wave's loads of the block have landed
-            __syncthreads();                      // everyone's have, and the other stage is free again
-            if (kb + 1 < nkb) {
-                issue(cur, kb + 1, st ^ 1);
-            } else if (more) {
-                nxt = geometry(t + tstep);
-                issue(nxt, 0, st ^ 1);
-            }
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[mt][v] = 0.0f;
+        for (int kb = 0; kb < nkb; ++kb) {
+            // This wave's loads of the block have landed: memory operations retire in issue order, and after
+            // the block's loads at most NST - 2 blocks' worth (and a tile's stores) were issued.  At the end
+            // of the sequence, where fewer are in flight, wait for all.
+            constexpr int AHEAD = LPI * (NST - 2);
+            if (NST > 2 && live) __builtin_amdgcn_s_waitcnt(0x0F70 | (AHEAD & 15) | ((AHEAD >> 4) << 14));
+            else __builtin_amdgcn_s_waitcnt(0x0F70);
+            // everyone's have, and the stage read last is free again.  (A bare barrier instruction: a fence,
+            // also one over LDS only, makes the compiler wait for every load in flight, since the loads
+            // write LDS.  The wait above is what orders this wave's part of the block before the barrier;
+            // the wave's LDS reads of the previous block were consumed by its MFMAs.)
+            asm volatile("s_barrier" ::: "memory");
+            int st_free = st + NST - 1;
+            if (st_free >= NST) st_free -= NST;
+            if (live) issue_next(st_free);
             const float *sS = lds + st * STAGE1;
             const float *bp = sS + b_lane;
             const float *ap = sS + a_lane;
             const int nq = min(K1, P.Ci - kb * K1) >> 3;   // groups of eight channels in this block
+            // chunk 2q + h of the row sits at slot (2q + h) ^ (row & 7)
+            if constexpr (!RAG) {
+                // whole blocks only (Ci a multiple of K1): all operand reads go out first (LDS answers in order,
+                // so an MFMA waits for its own operands only and the later reads travel under the earlier MFMAs)
+                float4v_t a[MT][K1 / 8];
+                float b[K1 / 2];
 #pragma unroll
-            for (int q = 0; q < K1 / 8; ++q) {
-                if (q >= nq) break;
-                // chunk 2q + h of the row sits at slot (2q + h) ^ (row & 7)
-                const float4v_t a = *reinterpret_cast<const float4v_t *>(ap + 4 * ((2 * q + h) ^ (row & 7)));
-                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, bp[(8 * q + 0) * NB], acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, bp[(8 * q + 1) * NB], acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, bp[(8 * q + 2) * NB], acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, bp[(8 * q + 3) * NB], acc, 0, 0, 0);
+                for (int q = 0; q < K1 / 8; ++q) {
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt)
+                        a[mt][q] = *reinterpret_cast<const float4v_t *>(ap + mt * (MB * K1) + 4 * ((2 * q + h) ^ (row & 7)));
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) b[4 * q + i] = bp[(8 * q + i) * NB];
+                }
+#pragma unroll
+                for (int q = 0; q < K1 / 8; ++q) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+#pragma unroll
+                        for (int mt = 0; mt < MT; ++mt)
+                            acc[mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mt][q][i], b[4 * q + i], acc[mt], 0, 0, 0);
+                }
+            } else {
+                for (int q = 0; q < nq; ++q) {
+                    float4v_t a[MT];
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt)
+                        a[mt] = *reinterpret_cast<const float4v_t *>(ap + mt * (MB * K1) + 4 * ((2 * q + h) ^ (row & 7)));
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const float b = bp[(8 * q + i) * NB];
+#pragma unroll
+                        for (int mt = 0; mt < MT; ++mt)
+                            acc[mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mt][i], b, acc[mt], 0, 0, 0);
+                    }
+                }
             }
+            if (++st == NST) st = 0;
         }
-        store_tile_desc(P.T, acc, cur.P0, cur.Pend, cur.m0, wm, wn, h, l32);
-        cur = nxt;
+        const uint32_t tile_n = fdiv(t, P.d_tm);
+        const uint32_t P0 = tile_n * NB;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+            store_tile_desc(P.T, acc[mt], P0, min(P0 + NB - 1, P.npix - 1), (int)(t - tile_n * P.tiles_m) * (MT * MB) + mt * MB,
+                            wm, wn, h, l32);
     }
 }
 
-template <int K1, bool GATHER>
+template <int K1, bool GATHER, int NST, bool RAG, int MT>
 static hipError_t launch_1x1_t(OneByOneParams &P, const Shape &sh, hipStream_t st, LaunchPlan *plan)
 {
-    constexpr size_t lds = 2u * stage1_floats<K1>() * sizeof(float);
-    constexpr int per_cu = 128 / K1;   // resident workgroups per CU (LDS)
+    constexpr size_t lds = (size_t)NST * stage1_floats<K1, MT>() * sizeof(float);
+    P.tiles_m = (uint32_t)((sh.Co + MT * MB - 1) / (MT * MB));
+    P.d_tm = make_fastdiv(P.tiles_m);
+    P.ntiles = ((P.npix + NB - 1) / NB) * P.tiles_m;
+    constexpr int per_cu = (int)(160u * 1024u / lds) < 4 ? (int)(160u * 1024u / lds) : 4;   // resident workgroups per CU (LDS; four at most)
     int dev = 0, ncu = 0;
     hipError_t e = device_cus(&dev, &ncu);
     if (e != hipSuccess && plan) { e = hipSuccess; ncu = 256; }   // planning without a device: an MI355X's 256 compute units
@@ -225,9 +298,9 @@ static hipError_t launch_1x1_t(OneByOneParams &P, const Shape &sh, hipStream_t s
         if (blocks >= 8) blocks &= ~7u;
         if (blocks > P.ntiles) blocks = P.ntiles;
     }
-    if (plan) { plan_record(plan, dim3(blocks), 256, lds, "conv_mfma_1x1_kernel<%d, %s>", K1, tf(GATHER)); return hipSuccess; }
+    if (plan) { plan_record(plan, dim3(blocks), 256, lds, "conv_mfma_1x1_kernel<%d, %s, %d, %s, %d>", K1, tf(GATHER), NST, tf(RAG), MT); return hipSuccess; }
     static KernelCache kc;
-    void (*kern)(OneByOneParams) = &conv_mfma_1x1_kernel<K1, GATHER>;
+    void (*kern)(OneByOneParams) = &conv_mfma_1x1_kernel<K1, GATHER, NST, RAG, MT>;
     if ((e = allow_dynamic_lds(kc, reinterpret_cast<const void *>(kern), lds, dev)) != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(blocks), dim3(256), lds, st, P);
     return hipGetLastError();
@@ -276,9 +349,22 @@ hipError_t launch_conv_mfma_1x1(const float *src, const float *flt, float *out, 
     // K blocks of 32 channels leave room for four workgroups per CU, which hide each other's barriers and
     // load waits better than two with blocks of 64 (256 -> 256 channels at 28x28: 109 against 95 TFLOP/s);
     // they copy eight filter rows per instruction, hence for channel counts that are multiples of eight.
-    if (sh.Co % 8 == 0)
-        return gather ? launch_1x1_t<32, true>(P, sh, st, plan) : launch_1x1_t<32, false>(P, sh, st, plan);
-    return gather ? launch_1x1_t<64, true>(P, sh, st, plan) : launch_1x1_t<64, false>(P, sh, st, plan);
+    // (RAG instances: a last K block shorter than the others)
+    if (sh.Co % 8 == 0) {
+        constexpr int S = ONE_BY_ONE_STAGES;
+        if (sh.Ci % 32 == 0) {
+            // Tiles of 128 output channels halve the pixel traffic; they pay where the planes are large and the
+            // K loop short (128 -> 512 channels at 28x28, 256 -> 512 at 56x56 stride 2, 256 -> 128 at 56x56:
+            // +2 to +4 %) and cost 2-3 % on long K loops over small planes (512 channels and more at 14x14, 7x7).
+            if (sh.Co % 128 == 0 && sh.Ci <= 256 && ONE_BY_ONE_MT == 2)
+                return gather ? launch_1x1_t<32, true, S, false, ONE_BY_ONE_MT>(P, sh, st, plan) : launch_1x1_t<32, false, S, false, ONE_BY_ONE_MT>(P, sh, st, plan);
+            return gather ? launch_1x1_t<32, true, S, false, 1>(P, sh, st, plan) : launch_1x1_t<32, false, S, false, 1>(P, sh, st, plan);
+        }
+        return gather ? launch_1x1_t<32, true, S, true, 1>(P, sh, st, plan) : launch_1x1_t<32, false, S, true, 1>(P, sh, st, plan);
+    }
+    if (sh.Ci % 64 == 0)
+        return gather ? launch_1x1_t<64, true, 2, false, 1>(P, sh, st, plan) : launch_1x1_t<64, false, 2, false, 1>(P, sh, st, plan);
+    return gather ? launch_1x1_t<64, true, 2, true, 1>(P, sh, st, plan) : launch_1x1_t<64, false, 2, true, 1>(P, sh, st, plan);
 }
 
 }  // namespace im2win
