@@ -35,17 +35,17 @@ PEAK_HBM_GBS = 8000.0             # MI355X HBM3E
 # gives the commands; tests/test_host_api.py holds the two to each other.  Layers that were not
 # measured report null.
 MEASURED_CONV_TRAFFIC_BYTES = {
-    "cfg1_tiny_3x3": 209076,
-    "cfg2_3x3_c64_56": 107716105,
-    "cfg3_3x3_c256_14": 220875757,
-    "cfg4_7x7_s2_c3_224": 689065747,
-    "cfg5_11x11_s4_c3_227": 362869319}
+    "cfg1_tiny_3x3": 209022,
+    "cfg2_3x3_c64_56": 107720279,
+    "cfg3_3x3_c256_14": 214531450,
+    "cfg4_7x7_s2_c3_224": 689090031,
+    "cfg5_11x11_s4_c3_227": 362581240}
 MEASURED_TRANSFORM_TRAFFIC_BYTES = {
     "cfg1_tiny_3x3": 63485,
-    "cfg2_3x3_c64_56": 105603081,
-    "cfg3_3x3_c256_14": 113848109,
-    "cfg4_7x7_s2_c3_224": 362290151,
-    "cfg5_11x11_s4_c3_227": 298434500}
+    "cfg2_3x3_c64_56": 105602785,
+    "cfg3_3x3_c256_14": 113851195,
+    "cfg4_7x7_s2_c3_224": 362288565,
+    "cfg5_11x11_s4_c3_227": 298427442}
 
 
 def parse_args():
