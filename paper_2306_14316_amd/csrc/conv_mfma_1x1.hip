@@ -76,7 +76,7 @@ struct OneByOneTile {
 // MT = 2: the workgroup's tile is 128 output channels x 64 pixels, every wave owns two 32x32 blocks (rows
 // r and r + 64) whose MFMA chains are independent and share their pixel operand: half the pixel traffic and
 // LDS reads per MFMA, and two chains to interleave.
-template <int K1, bool GATHER, int NST, bool RAG, int MT>
+template <int K1, bool GATHER, int NST, int MT>
 __global__ __launch_bounds__(256) void conv_mfma_1x1_kernel(OneByOneParams P)
 {
     static_assert(NST >= 2 && NST <= 4, "two to four LDS stages");
@@ -227,9 +227,9 @@ __global__ __launch_bounds__(256) void conv_mfma_1x1_kernel(OneByOneParams P)
             const float *ap = sS + a_lane;
             const int nq = min(K1, P.Ci - kb * K1) >> 3;   // groups of eight channels in this block
             // chunk 2q + h of the row sits at slot (2q + h) ^ (row & 7)
-            if constexpr (!RAG) {
-                // whole blocks only (Ci a multiple of K1): all operand reads go out first (LDS answers in order,
-                // so an MFMA waits for its own operands only and the later reads travel under the earlier MFMAs)
+            if constexpr (MT == 2) {
+                // whole blocks only (the launcher sees to it): all operand reads go out first -- LDS answers in
+                // order, so an MFMA waits for its own operands only -- and the two blocks' chains alternate
                 float4v_t a[MT][K1 / 8];
                 float b[K1 / 2];
 #pragma unroll
@@ -249,18 +249,14 @@ __global__ __launch_bounds__(256) void conv_mfma_1x1_kernel(OneByOneParams P)
                             acc[mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mt][q][i], b[4 * q + i], acc[mt], 0, 0, 0);
                 }
             } else {
-                for (int q = 0; q < nq; ++q) {
-                    float4v_t a[MT];
 #pragma unroll
-                    for (int mt = 0; mt < MT; ++mt)
-                        a[mt] = *reinterpret_cast<const float4v_t *>(ap + mt * (MB * K1) + 4 * ((2 * q + h) ^ (row & 7)));
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const float b = bp[(8 * q + i) * NB];
-#pragma unroll
-                        for (int mt = 0; mt < MT; ++mt)
-                            acc[mt] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mt][i], b, acc[mt], 0, 0, 0);
-                    }
+                for (int q = 0; q < K1 / 8; ++q) {
+                    if (q >= nq) break;
+                    const float4v_t a = *reinterpret_cast<const float4v_t *>(ap + 4 * ((2 * q + h) ^ (row & 7)));
+                    acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, bp[(8 * q + 0) * NB], acc[0], 0, 0, 0);
+                    acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, bp[(8 * q + 1) * NB], acc[0], 0, 0, 0);
+                    acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, bp[(8 * q + 2) * NB], acc[0], 0, 0, 0);
+                    acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, bp[(8 * q + 3) * NB], acc[0], 0, 0, 0);
                 }
             }
             if (++st == NST) st = 0;
@@ -274,7 +270,7 @@ __global__ __launch_bounds__(256) void conv_mfma_1x1_kernel(OneByOneParams P)
     }
 }
 
-template <int K1, bool GATHER, int NST, bool RAG, int MT>
+template <int K1, bool GATHER, int NST, int MT>
 static hipError_t launch_1x1_t(OneByOneParams &P, const Shape &sh, hipStream_t st, LaunchPlan *plan)
 {
     constexpr size_t lds = (size_t)NST * stage1_floats<K1, MT>() * sizeof(float);
@@ -298,9 +294,9 @@ static hipError_t launch_1x1_t(OneByOneParams &P, const Shape &sh, hipStream_t s
         if (blocks >= 8) blocks &= ~7u;
         if (blocks > P.ntiles) blocks = P.ntiles;
     }
-    if (plan) { plan_record(plan, dim3(blocks), 256, lds, "conv_mfma_1x1_kernel<%d, %s, %d, %s, %d>", K1, tf(GATHER), NST, tf(RAG), MT); return hipSuccess; }
+    if (plan) { plan_record(plan, dim3(blocks), 256, lds, "conv_mfma_1x1_kernel<%d, %s, %d, %d>", K1, tf(GATHER), NST, MT); return hipSuccess; }
     static KernelCache kc;
-    void (*kern)(OneByOneParams) = &conv_mfma_1x1_kernel<K1, GATHER, NST, RAG, MT>;
+    void (*kern)(OneByOneParams) = &conv_mfma_1x1_kernel<K1, GATHER, NST, MT>;
     if ((e = allow_dynamic_lds(kc, reinterpret_cast<const void *>(kern), lds, dev)) != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(blocks), dim3(256), lds, st, P);
     return hipGetLastError();
@@ -349,22 +345,17 @@ hipError_t launch_conv_mfma_1x1(const float *src, const float *flt, float *out, 
     // K blocks of 32 channels leave room for four workgroups per CU, which hide each other's barriers and
     // load waits better than two with blocks of 64 (256 -> 256 channels at 28x28: 109 against 95 TFLOP/s);
     // they copy eight filter rows per instruction, hence for channel counts that are multiples of eight.
-    // (RAG instances: a last K block shorter than the others)
     if (sh.Co % 8 == 0) {
         constexpr int S = ONE_BY_ONE_STAGES;
-        if (sh.Ci % 32 == 0) {
-            // Tiles of 128 output channels halve the pixel traffic; they pay where the planes are large and the
-            // K loop short (128 -> 512 channels at 28x28, 256 -> 512 at 56x56 stride 2, 256 -> 128 at 56x56:
-            // +2 to +4 %) and cost 2-3 % on long K loops over small planes (512 channels and more at 14x14, 7x7).
-            if (sh.Co % 128 == 0 && sh.Ci <= 256 && ONE_BY_ONE_MT == 2)
-                return gather ? launch_1x1_t<32, true, S, false, ONE_BY_ONE_MT>(P, sh, st, plan) : launch_1x1_t<32, false, S, false, ONE_BY_ONE_MT>(P, sh, st, plan);
-            return gather ? launch_1x1_t<32, true, S, false, 1>(P, sh, st, plan) : launch_1x1_t<32, false, S, false, 1>(P, sh, st, plan);
-        }
-        return gather ? launch_1x1_t<32, true, S, true, 1>(P, sh, st, plan) : launch_1x1_t<32, false, S, true, 1>(P, sh, st, plan);
+        // Tiles of 128 output channels halve the pixel traffic; they pay where the pixel planes are large and
+        // the K loop short (64 -> 256 and 256 -> 128 channels at 56x56: +3 to +4 %; 128 -> 512 at 28x28: +2 %)
+        // and cost up to 3 % elsewhere (256 -> 256 at 28x28; 512 channels and more at 14x14 and 7x7).  Their
+        // MFMA loop takes whole K blocks only.
+        if (ONE_BY_ONE_MT == 2 && sh.Co % 128 == 0 && sh.Ci % 32 == 0 && (sh.Ci <= 128 || (sh.Ci <= 256 && howo >= 2048)))
+            return gather ? launch_1x1_t<32, true, S, ONE_BY_ONE_MT>(P, sh, st, plan) : launch_1x1_t<32, false, S, ONE_BY_ONE_MT>(P, sh, st, plan);
+        return gather ? launch_1x1_t<32, true, S, 1>(P, sh, st, plan) : launch_1x1_t<32, false, S, 1>(P, sh, st, plan);
     }
-    if (sh.Ci % 64 == 0)
-        return gather ? launch_1x1_t<64, true, 2, false, 1>(P, sh, st, plan) : launch_1x1_t<64, false, 2, false, 1>(P, sh, st, plan);
-    return gather ? launch_1x1_t<64, true, 2, true, 1>(P, sh, st, plan) : launch_1x1_t<64, false, 2, true, 1>(P, sh, st, plan);
+    return gather ? launch_1x1_t<64, true, 2, 1>(P, sh, st, plan) : launch_1x1_t<64, false, 2, 1>(P, sh, st, plan);
 }
 
 }  // namespace im2win

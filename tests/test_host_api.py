@@ -156,9 +156,9 @@ def test_launch_info_names_the_dispatch(lib):
     assert im2win.conv2d_im2win_fwd_launch_info(8, 7, 56, 56, 64, 3, 3, 1, 1)["kernel"] == "conv_mfma_kernel<9, false>"
     # 1x1 layers: their own kernel; 1x7 / 7x1 / 1x3 / 3x1: instances of the pipelined kernel; other asymmetric filters:
     # the pipelined generic kernel, its single-stage form when two stages do not fit LDS
-    assert im2win.conv2d_im2win_fwd_launch_info(64, 256, 28, 28, 256, 1, 1, 1, 0)["kernel"] == "conv_mfma_1x1_kernel<32, false, 2, false, 2>"
-    assert im2win.conv2d_im2win_fwd_launch_info(64, 256, 28, 28, 256, 1, 1, 1, 0, workspace_free=True)["kernel"] == "conv_mfma_1x1_kernel<32, false, 2, false, 2>"
-    assert im2win.conv2d_im2win_fwd_launch_info(64, 256, 28, 28, 256, 1, 1, 2, 0)["kernel"] == "conv_mfma_1x1_kernel<32, true, 2, false, 2>"   # strided
+    assert im2win.conv2d_im2win_fwd_launch_info(64, 256, 28, 28, 256, 1, 1, 1, 0)["kernel"] == "conv_mfma_1x1_kernel<32, false, 2, 1>"
+    assert im2win.conv2d_im2win_fwd_launch_info(64, 256, 28, 28, 256, 1, 1, 1, 0, workspace_free=True)["kernel"] == "conv_mfma_1x1_kernel<32, false, 2, 1>"
+    assert im2win.conv2d_im2win_fwd_launch_info(64, 256, 28, 28, 256, 1, 1, 2, 0)["kernel"] == "conv_mfma_1x1_kernel<32, true, 2, 1>"   # strided
     assert im2win.conv2d_im2win_fwd_launch_info(64, 252, 28, 28, 256, 1, 1, 1, 0)["kernel"] == "conv_mfma_pipe_kernel<1, 1>"
     assert im2win.conv2d_im2win_fwd_launch_info(64, 64, 28, 28, 64, 1, 7, 1, 0)["kernel"].startswith("conv_mfma_fast_kernel<1, 7, 8, 1, 4, 3, false,")
     assert im2win.conv2d_im2win_fwd_launch_info(64, 64, 28, 28, 64, 7, 1, 1, 3, workspace_free=True)["kernel"].startswith("conv_mfma_fast_kernel<7, 1, 8, 2, 4, 2, true,")
