@@ -504,7 +504,16 @@ __global__ __launch_bounds__(256, OCC) void conv_mfma_fast_kernel(MfmaParams P)
     constexpr int NILS = (NIW + LPS - 1) / LPS;                                      // slots that load strip words
     static_assert(NFW + NIWS + NILS <= NSLOT, "staging work must fit before the barrier");
 
-    float a[R], b[R];
+    // BW: a filter height of four (two) makes every window start a multiple of four (two) floats into its
+    // strip (and all strip and stage sizes are), so the B operands of BW consecutive steps -- one window
+    // column -- are one aligned 16-byte (8-byte) LDS read.  With single-word reads such a layer is bound by
+    // LDS: its windows start s*Hf floats apart, at 4x4 stride 2 a wave's 32 reads fall into four banks
+    // (bank-conflict cycles were 71 % of the LDS-active cycles, LDS active 94 % of the time; 64 -> 128
+    // channels at 64x64: 117 -> 136 TFLOP/s with the wide reads).  The ring then holds R/BW vectors of B.
+    constexpr int BW = (HALF || R % 4 != 0) ? 1 : (HF == 4 ? 4 : (HF == 2 ? 2 : 1));
+    typedef float bvec_t __attribute__((ext_vector_type(BW == 1 ? 2 : BW)));   // (no one-element vector type: unused then)
+    float a[R], b[BW == 1 ? R : 1];
+    bvec_t bq[BW == 1 ? 1 : R / BW];
     // operands of step i (0 <= i < NM) of a block, from LDS stage st, into ring slot i % R;
     // bp: the B base of the tile the block belongs to
     auto lds_op = [&](int st, int i, const lds_float *bp) __attribute__((always_inline)) {
@@ -514,7 +523,20 @@ __global__ __launch_bounds__(256, OCC) void conv_mfma_fast_kernel(MfmaParams P)
         // offsets (merged two-address reads have 8-bit offsets and would need a VALU
         // add each -- and VALU work comes out of the MFMA rate).
         a[i % R] = *(const volatile lds_float *)(ap0 + st * STAGE + 2 * g * KHW + u * WF + v);
-        b[i % R] = *(const volatile lds_float *)(bp + st * STAGE + 2 * g * SS + t);
+        if constexpr (BW > 1) {
+            // the vector of steps i-BW+1 .. i goes out with its last step: its ring slot was read by the
+            // MFMAs R steps earlier, the last of which has just been issued
+            if (i % BW == BW - 1) {
+                typedef __attribute__((address_space(3))) bvec_t lds_bvec;
+                bq[(i / BW) % (R / BW)] = *(const volatile lds_bvec *)(bp + st * STAGE + 2 * g * SS + (t - (BW - 1)));
+            }
+        } else {
+            b[i % R] = *(const volatile lds_float *)(bp + st * STAGE + 2 * g * SS + t);
+        }
+    };
+    auto b_of = [&](int i) __attribute__((always_inline)) -> float {
+        if constexpr (BW > 1) return bq[(i / BW) % (R / BW)][i % BW];
+        else return b[i % R];
     };
 
     // NX1 / NX2: the block after this one / the one after that belongs to the next tile (a
@@ -528,7 +550,7 @@ __global__ __launch_bounds__(256, OCC) void conv_mfma_fast_kernel(MfmaParams P)
 #pragma unroll
         for (int i = 0; i < NM; ++i) {
             if (HAS1 && i == NSLOT) __syncthreads();
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i % R], b[i % R], acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i % R], b_of(i), acc, 0, 0, 0);
             // ring slot i % R is free again: fetch the operands of step i + R (of this
             // block, or of the next one out of the other stage)
             if (i + R < NM) lds_op(ST, i + R, bp_c);
