@@ -70,10 +70,50 @@ template <int HF, int WF, int CI>
 struct Steps {
     static constexpr int KHW = HF * WF, KH2 = (KHW + 1) / 2, NPAIR = CI / 2, ODD = CI & 1;
     static constexpr int T = NPAIR * KHW + ODD * KH2;
+    // The odd channel's window is split between the lane halves: lanes 0-31 take positions [0, SPL), lanes
+    // 32-63 [SPL, KHW), KH2 steps with one zero slice where a half has one position fewer.  11x11: SPL is a
+    // multiple of four floats (60, the zero slice then being the first half's last step), which keeps the second
+    // half's operands 16-byte aligned; the other windows split at KH2 (zero slice: the second half's last step).
+    static constexpr int SPL = HF == 11 ? ((KHW / 2) & ~3) : KH2;
+    static_assert(SPL <= KH2 && KHW - SPL <= KH2, "both halves fit the split steps");
+    // window position of split step t for lane half hh, or -1: zero slice
+    __host__ __device__ static constexpr int split_pos(int t, int hh) { return hh ? (SPL + t < KHW ? SPL + t : -1) : (t < SPL ? t : -1); }
     __host__ __device__ static constexpr bool is_pair(int i) { return i < NPAIR * KHW; }
     // window position (v*HF + u) -> filter position (u*WF + v)
     __host__ __device__ static constexpr int filt_pos(int t) { return (t % HF) * WF + (t / HF); }
 };
+
+// The B operand reads of one wave's TW steps (steps ksi*TW ...), grouped into units: four consecutive steps whose
+// operands are four consecutive LDS words starting at a multiple of four -- one 16-byte read -- or a single step.
+// Offsets are relative to the lane's pair base (window start in the strip of its channel of the pair) or split
+// base (window start + its half's first position in the odd channel's strip); SS: floats per channel strip.
+template <int TW>
+struct ReadUnits {
+    int n;
+    int first[TW], len[TW], split[TW], off[TW];   // per unit: first step, steps, which base, offset in floats
+    int unit_of[TW];                              // per step: its unit
+};
+template <class St, int TW, int SS>
+constexpr ReadUnits<TW> make_read_units(int ksi)
+{
+    ReadUnits<TW> u{};
+    auto is_split = [](int i) { return !St::is_pair(i); };
+    auto offs = [](int i) { return St::is_pair(i) ? 2 * (i / St::KHW) * SS + i % St::KHW : i - St::NPAIR * St::KHW; };
+    int k = 0;
+    for (int s = 0; s < TW;) {
+        const int i = ksi * TW + s;
+        bool quad = s + 3 < TW && offs(i) % 4 == 0;
+        for (int e = 1; e < 4 && quad; ++e)
+            quad = is_split(i + e) == is_split(i) && offs(i + e) == offs(i) + e;
+        const int len = quad ? 4 : 1;
+        u.first[k] = s; u.len[k] = len; u.split[k] = is_split(i) ? 1 : 0; u.off[k] = offs(i);
+        for (int e = 0; e < len; ++e) u.unit_of[s + e] = k;
+        s += len;
+        ++k;
+    }
+    u.n = k;
+    return u;
+}
 
 // IMP: workspace-free variant.  P.win is the NCHW input and each tile's im2win strips
 // (Eq. 2) are gathered from it: strip word kk*HF + u of a row segment is input row
@@ -95,7 +135,12 @@ struct Steps {
 template <int HF, bool IMP, int G>
 constexpr int shallow_waves_per_simd() { return (HF == 7 && G == 1 && !IMP) ? 3 : 1; }
 
-template <int HF, int WF, int CI, int WM, int KS, int JX, bool IMP, int G, bool WIDE>
+// BV (11x11 with a stride that is a multiple of four, two-call path): every window then starts a multiple
+// of four floats into its row segment, the segments are placed at multiples of four floats in LDS, and the B
+// operands of four consecutive K steps -- four consecutive window words -- are one aligned 16-byte LDS read.
+// Windows 44 floats apart put a wave's 32 single-word reads into eight banks (4-way conflicts); the 16-byte
+// reads of eight neighbouring lanes cover all 32.
+template <int HF, int WF, int CI, int WM, int KS, int JX, bool IMP, int G, bool WIDE, bool BV = false>
 __global__ __launch_bounds__(64 * WM * 2 * KS) __attribute__((amdgpu_waves_per_eu(shallow_waves_per_simd<HF, IMP, G>())))
 void conv_mfma_shallow_kernel(ShallowParams P)
 {
@@ -110,6 +155,7 @@ void conv_mfma_shallow_kernel(ShallowParams P)
     static_assert(T % KS == 0, "K steps must split evenly between the waves of a block");
     static_assert(G == 1 || KS == 1, "pixel groups are not combined with a split K");
     static_assert(!WIDE || G == 4, "16-byte stores take one pixel from each of four groups");
+    static_assert(!BV || (G == 1 && !IMP && !WIDE && St::SPL % 4 == 0 && HF % 2 == 1), "16-byte operand reads: aligned windows and split");
 
     extern __shared__ __align__(16) unsigned char smem[];
     lds_f32 *lds = (lds_f32 *)reinterpret_cast<float *>(smem);   // [2][STAGE] then the exchange area
@@ -131,8 +177,8 @@ void conv_mfma_shallow_kernel(ShallowParams P)
         const bool live = mrow < P.Co;
         auto elem = [](int i, int hh) -> int {   // -1: zero slice
             if (St::is_pair(i)) return (2 * (i / KHW) + hh) * KHW + St::filt_pos(i % KHW);
-            const int t = i - NPAIR * KHW + hh * KH2;
-            return t < KHW ? (CI - 1) * KHW + St::filt_pos(t) : -1;
+            const int t = St::split_pos(i - NPAIR * KHW, hh);
+            return t >= 0 ? (CI - 1) * KHW + St::filt_pos(t) : -1;
         };
 #pragma unroll
         for (int ii = 0; ii < TW; ++ii) {
@@ -306,7 +352,9 @@ void conv_mfma_shallow_kernel(ShallowParams P)
             const uint32_t img = fdiv(q, P.d_ho);
             const int mq = (int)(q - img * (uint32_t)P.Ho);
             const int nhi = (q == nq1) ? (int)(nPend - q * (uint32_t)P.Wo) : P.Wo - 1;
-            const int pos = nlen0 + (r - 1) * P.fullseg;
+            // LDS position of the segment: right behind the one before it (BV: at the next multiple of four floats)
+            const int pos1 = BV ? (nlen0 + 3) & ~3 : nlen0;
+            const int pos = r == 1 ? pos1 : (BV ? (pos1 + P.fullseg + 3) & ~3 : pos1 + P.fullseg);
             const int d = (int)(img - nimg0) * P.img_stride + (mq - nm0r) * P.rowlen - nnlo0 * sHf - pos;
             if (r == 1) { nt1 = has ? pos : 0x3fffffff; nd1 = has ? d : 0; }
             else        { nt2 = has ? pos : 0x3fffffff; nd2 = has ? d : 0; }
@@ -317,7 +365,8 @@ void conv_mfma_shallow_kernel(ShallowParams P)
                 if (r == 1) { gncol1 = nc; grcp1 = rc; ghb1 = hb; gwb1 = -P.p; ggb1 = gb; }
                 else        { gncol2 = nc; grcp2 = rc; ghb2 = hb; gwb2 = -P.p; ggb2 = gb; }
             }
-            nfilled += has ? (nhi * P.s + WF) * HF : 0;
+            if (BV) nfilled = has ? pos + (nhi * P.s + WF) * HF : nfilled;
+            else nfilled += has ? (nhi * P.s + WF) * HF : 0;
             if (r == 1) { pin(nt1); pin(nd1); } else { pin(nt2); pin(nd2); }
             pin(nfilled);
         } else if constexpr (p >= P_OFF && p < P_LD) {
@@ -392,7 +441,8 @@ void conv_mfma_shallow_kernel(ShallowParams P)
                 const uint32_t ql = fdiv(Pl, P.d_wo);
                 const int nl = (int)(Pl - ql * (uint32_t)P.Wo);
                 const int rho = (int)(ql - nq0);
-                nwpos[g] = rho == 0 ? (nl - nnlo0) * sHf : nlen0 + (rho - 1) * P.fullseg + nl * sHf;
+                if (BV) nwpos[g] = rho == 0 ? (nl - nnlo0) * sHf : (rho == 1 ? nt1 : nt2) + nl * sHf;   // (the segment's own position)
+                else nwpos[g] = rho == 0 ? (nl - nnlo0) * sHf : nlen0 + (rho - 1) * P.fullseg + nl * sHf;
             }
         } else if constexpr (p >= P_OPTR && p < P_ST) {
             constexpr int g = p - P_OPTR;
@@ -482,8 +532,11 @@ void conv_mfma_shallow_kernel(ShallowParams P)
 #pragma unroll
         for (int g = 0; g < G; ++g) {
             bpair[g] = sbase + cwpos[g] + h * SS;
-            bsplit[g] = sbase + cwpos[g] + (CI - 1) * SS + h * KH2;
-            bzero[g] = (h && (KHW & 1)) ? sbase + CI * SS : bsplit[g] + (KH2 - 1);
+            bsplit[g] = sbase + cwpos[g] + (CI - 1) * SS + h * St::SPL;
+            // the zero slice: a zero word where the half's last step would read past the window (the second half,
+            // split at KH2); a first half that ends early re-reads the other half's first position, times a zero
+            // filter register (a word of the lane's own window)
+            bzero[g] = (h && St::SPL + KH2 > KHW) ? sbase + CI * SS : bsplit[g] + (KH2 - 1);
         }
         auto run = [&](auto ksc) __attribute__((always_inline)) {
             constexpr int KSI = decltype(ksc)::value;
@@ -497,33 +550,68 @@ void conv_mfma_shallow_kernel(ShallowParams P)
                 if (t == KH2 - 1) return *(const volatile lds_f32 *)bzero[g];
                 return *(const volatile lds_f32 *)(bsplit[g] + t);
             };
-            float b[G][SH_G];   // rings of B operands, SH_G steps ahead of the MFMAs
-#pragma unroll
-            for (int e = 0; e < SH_G; ++e)
-#pragma unroll
-                for (int g = 0; g < G; ++g)
-                    if (e < TW) b[g][e] = bread(e, g);
-            __builtin_amdgcn_sched_barrier(0);
-            static_for<TW>([&](auto ic) __attribute__((always_inline)) {
-                constexpr int ii = decltype(ic)::value;
-                static_for<G>([&](auto gc) __attribute__((always_inline)) {
-                    constexpr int g = decltype(gc)::value;
+            if constexpr (BV) {
+                // 16-byte operand reads: a ring of NU units (quads or single words), unit k + NU fetched right
+                // behind the last MFMA of unit k
+                constexpr ReadUnits<TW> U = make_read_units<St, TW, SS>(KSI);
+                constexpr int NU = 3;
+                typedef float f32x4 __attribute__((ext_vector_type(4)));
+                typedef __attribute__((address_space(3))) f32x4 lds_f32x4;
+                f32x4 bu[NU];
+                auto fetch = [&](auto kc) __attribute__((always_inline)) {
+                    constexpr int k = decltype(kc)::value;
+                    const lds_f32 *ptr = (U.split[k] ? bsplit[0] : bpair[0]) + U.off[k];
+                    if constexpr (U.len[k] == 4) bu[k % NU] = *(const volatile lds_f32x4 *)ptr;
+                    else bu[k % NU].x = *(const volatile lds_f32 *)ptr;
+                };
+                static_for<(NU < U.n ? NU : U.n)>([&](auto kc) __attribute__((always_inline)) { fetch(kc); });
+                __builtin_amdgcn_sched_barrier(0);
+                static_for<TW>([&](auto ic) __attribute__((always_inline)) {
+                    constexpr int ii = decltype(ic)::value;
+                    constexpr int k = U.unit_of[ii], e = ii - U.first[k];
                     if constexpr (ii == 0) {
                         floatx16 z;
 #pragma unroll
                         for (int v = 0; v < 16; ++v) z[v] = 0.0f;
-                        acc[AP][g] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[0], b[g][0], z, 0, 0, 0);
+                        acc[AP][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[0], bu[0][0], z, 0, 0, 0);
                     } else {
-                        acc[AP][g] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[ii], b[g][ii % SH_G], acc[AP][g], 0, 0, 0);
+                        acc[AP][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[ii], bu[k % NU][e], acc[AP][0], 0, 0, 0);
                     }
-                    if (ii + SH_G < TW) b[g][ii % SH_G] = bread(ii + SH_G, g);
-                    // pieces whose slot is this MFMA: piece p rides behind MFMA p*(TW*G)/NP of the tile
-                    constexpr int m = ii * G + g, NM = TW * G;
+                    if constexpr (e == U.len[k] - 1 && k + NU < U.n) fetch(std::integral_constant<int, k + NU>{});
+                    constexpr int m = ii, NM = TW;
                     constexpr int plo = (m * NP + NM - 1) / NM, phi = ((m + 1) * NP + NM - 1) / NM;
                     pieces(std::integral_constant<int, plo>{}, std::integral_constant<int, phi>{}, nxt, PAR ^ 1, acc[AP ^ 1], PAR ^ 1);
                     __builtin_amdgcn_sched_barrier(0);
                 });
-            });
+            } else {
+                float b[G][SH_G];   // rings of B operands, SH_G steps ahead of the MFMAs
+    #pragma unroll
+                for (int e = 0; e < SH_G; ++e)
+    #pragma unroll
+                    for (int g = 0; g < G; ++g)
+                        if (e < TW) b[g][e] = bread(e, g);
+                __builtin_amdgcn_sched_barrier(0);
+                static_for<TW>([&](auto ic) __attribute__((always_inline)) {
+                    constexpr int ii = decltype(ic)::value;
+                    static_for<G>([&](auto gc) __attribute__((always_inline)) {
+                        constexpr int g = decltype(gc)::value;
+                        if constexpr (ii == 0) {
+                            floatx16 z;
+    #pragma unroll
+                            for (int v = 0; v < 16; ++v) z[v] = 0.0f;
+                            acc[AP][g] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[0], b[g][0], z, 0, 0, 0);
+                        } else {
+                            acc[AP][g] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[ii], b[g][ii % SH_G], acc[AP][g], 0, 0, 0);
+                        }
+                        if (ii + SH_G < TW) b[g][ii % SH_G] = bread(ii + SH_G, g);
+                        // pieces whose slot is this MFMA: piece p rides behind MFMA p*(TW*G)/NP of the tile
+                        constexpr int m = ii * G + g, NM = TW * G;
+                        constexpr int plo = (m * NP + NM - 1) / NM, phi = ((m + 1) * NP + NM - 1) / NM;
+                        pieces(std::integral_constant<int, plo>{}, std::integral_constant<int, phi>{}, nxt, PAR ^ 1, acc[AP ^ 1], PAR ^ 1);
+                        __builtin_amdgcn_sched_barrier(0);
+                    });
+                });
+            }
             if constexpr (WIDE) {
                 // The tile's sums leave right behind its chain, from the one set of accumulators: register q
                 // of the wave's four blocks is a lane's four neighbouring pixels of channel dj (all inside the
@@ -590,7 +678,7 @@ void conv_mfma_shallow_kernel(ShallowParams P)
     else pieces(std::integral_constant<int, P_ST>{}, std::integral_constant<int, P_LDS>{}, 0u, 0, acc[1], 1);
 }
 
-template <int HF, int WF, int CI, int WM, int KS, int JX, bool IMP, int G, bool WIDE>
+template <int HF, int WF, int CI, int WM, int KS, int JX, bool IMP, int G, bool WIDE, bool BV = false>
 static hipError_t launch_shallow_k(ShallowParams P, int mgroups, hipStream_t st, LaunchPlan *plan)
 {
     P.ntiles = (P.npix + NB * G - 1) / (NB * G);
@@ -598,7 +686,7 @@ static hipError_t launch_shallow_k(ShallowParams P, int mgroups, hipStream_t st,
     constexpr int SS = JX * NT;
     constexpr int STAGE = CI * SS + 4;
     constexpr size_t lds = 4u * (size_t)(2 * STAGE + (KS == 2 ? 2 * WM * 2 * 2 * 8 * 64 : 0));
-    auto kern = &conv_mfma_shallow_kernel<HF, WF, CI, WM, KS, JX, IMP, G, WIDE>;
+    auto kern = &conv_mfma_shallow_kernel<HF, WF, CI, WM, KS, JX, IMP, G, WIDE, BV>;
     static KernelCache kc;
     int dev = 0, ncu = 0;
     hipError_t e = device_cus(&dev, &ncu);
@@ -621,8 +709,8 @@ static hipError_t launch_shallow_k(ShallowParams P, int mgroups, hipStream_t st,
     if (gx < 1) gx = 1;
     if (gx > P.ntiles) gx = P.ntiles;
     if (plan) {
-        plan_record(plan, dim3(gx, mgroups), NT, lds, "conv_mfma_shallow_kernel<%d, %d, %d, %d, %d, %d, %s, %d, %s>",
-                    HF, WF, CI, WM, KS, JX, tf(IMP), G, tf(WIDE));
+        plan_record(plan, dim3(gx, mgroups), NT, lds, "conv_mfma_shallow_kernel<%d, %d, %d, %d, %d, %d, %s, %d, %s, %s>",
+                    HF, WF, CI, WM, KS, JX, tf(IMP), G, tf(WIDE), tf(BV));
         return hipSuccess;
     }
     hipLaunchKernelGGL(kern, dim3(gx, mgroups), dim3(NT), lds, st, P);
@@ -689,6 +777,12 @@ hipError_t launch_conv_mfma_shallow(const float *win, const float *flt, float *o
         if (wm == 2 && S <= 4 * 256) return launch_shallow_t<7, 7, 3, 2, 1, 4>(P, mgroups, st, implicit, plan);
         if (wm == 3 && S <= 3 * 384) return launch_shallow_t<7, 7, 3, 3, 1, 3>(P, mgroups, st, implicit, plan);
     } else if (sh.Hf == 11 && sh.Wf == 11) {
+        // 16-byte operand reads where every window starts a multiple of four floats into its row segment (the
+        // segments are then placed at multiples of four in LDS: up to three floats of padding before two of them)
+        const bool bv = !implicit && sh.s % 4 == 0;
+        if (bv && wm == 1 && S + 6 <= 12 * 256) return launch_shallow_k<11, 11, 3, 1, 2, 12, false, 1, false, true>(P, mgroups, st, plan);
+        if (bv && wm == 2 && S + 6 <= 6 * 512) return launch_shallow_k<11, 11, 3, 2, 2, 6, false, 1, false, true>(P, mgroups, st, plan);
+        if (bv && wm == 3 && S + 6 <= 4 * 768) return launch_shallow_k<11, 11, 3, 3, 2, 4, false, 1, false, true>(P, mgroups, st, plan);
         if (wm == 1 && S <= 12 * 256) return launch_shallow_t<11, 11, 3, 1, 2, 12>(P, mgroups, st, implicit, plan);
         if (wm == 2 && S <= 6 * 512) return launch_shallow_t<11, 11, 3, 2, 2, 6>(P, mgroups, st, implicit, plan);
         if (wm == 3 && S <= 4 * 768) return launch_shallow_t<11, 11, 3, 3, 2, 4>(P, mgroups, st, implicit, plan);

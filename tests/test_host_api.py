@@ -162,6 +162,10 @@ def test_launch_info_names_the_dispatch(lib):
     assert im2win.conv2d_im2win_fwd_launch_info(64, 252, 28, 28, 256, 1, 1, 1, 0)["kernel"] == "conv_mfma_pipe_kernel<1, 1>"
     assert im2win.conv2d_im2win_fwd_launch_info(64, 64, 28, 28, 64, 1, 7, 1, 0)["kernel"].startswith("conv_mfma_fast_kernel<1, 7, 8, 1, 4, 3, false,")
     assert im2win.conv2d_im2win_fwd_launch_info(64, 64, 28, 28, 64, 7, 1, 1, 3, workspace_free=True)["kernel"].startswith("conv_mfma_fast_kernel<7, 1, 8, 2, 4, 2, true,")
+    # 11x11 on three channels: 16-byte operand reads on the two-call path when the stride is a multiple of four
+    assert im2win.conv2d_im2win_fwd_launch_info(128, 3, 227, 227, 96, 11, 11, 4, 0)["kernel"] == "conv_mfma_shallow_kernel<11, 11, 3, 3, 2, 4, false, 1, false, true>"
+    assert im2win.conv2d_im2win_fwd_launch_info(128, 3, 227, 227, 96, 11, 11, 4, 0, workspace_free=True)["kernel"] == "conv_mfma_shallow_kernel<11, 11, 3, 3, 2, 4, true, 1, false, false>"
+    assert im2win.conv2d_im2win_fwd_launch_info(32, 3, 227, 227, 96, 11, 11, 2, 0)["kernel"].endswith(", false, 1, false, false>")
     assert im2win.conv2d_im2win_fwd_launch_info(64, 64, 28, 28, 64, 1, 5, 1, 0)["kernel"] == "conv_mfma_pipe_kernel<0, 0>"
     assert im2win.conv2d_im2win_fwd_launch_info(2, 3, 35, 35, 96, 11, 11, 4, 0)["kernel"] == "conv_mfma_kernel<121, false>"
     assert im2win.conv2d_im2win_fwd_launch_info(2, 10, 35, 35, 96, 9, 9, 2, 0)["kernel"] == "conv_mfma_pipe_kernel<0, 0>"
