@@ -415,7 +415,12 @@ void conv_mfma_shallow_kernel(ShallowParams P)
                 if constexpr (IMP) {
                     ir[w] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rw, noff[w % JX], soff, 0));
                 } else {
-                    lds_f32 *dst = lds + st_next * STAGE + (w / JX) * SS + NT * (w % JX) + wave * 64;
+                    // (the wave's share of the destination is made opaque here: left to itself the compiler keeps
+                    // all 2*NIW destinations of the two stages in scalar registers for the whole kernel, spills them
+                    // to vector lanes and reads each back with a vector instruction per tile)
+                    uint32_t wv = (uint32_t)wave * 64u;
+                    if constexpr (!WIDE) asm volatile("" : "+s"(wv));   // (the one-workgroup-per-CU instances measured 1 % slower with it)
+                    lds_f32 *dst = lds + st_next * STAGE + (w / JX) * SS + NT * (w % JX) + wv;
                     __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, (__attribute__((address_space(3))) void *)dst, 4,
                                                              noff[w % JX], soff, 0, 0);
                 }
