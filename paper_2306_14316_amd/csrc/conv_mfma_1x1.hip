@@ -334,8 +334,10 @@ hipError_t launch_conv_mfma_1x1(const float *src, const float *flt, float *out, 
     P.d_howo = make_fastdiv(P.howo);
     P.d_tm = make_fastdiv(P.tiles_m);
     P.plane = (uint32_t)plane;
-    P.rowstep = (uint32_t)(implicit ? sh.s * sh.Wi : sh.Wi);
-    P.colstep = (uint32_t)sh.s;
+    // (with a single output row or column the step is never taken; a stride beyond the image then stays out
+    // of the products -- the stride has no upper bound)
+    P.rowstep = sh.Ho > 1 ? (uint32_t)(implicit ? sh.s * sh.Wi : sh.Wi) : 0u;
+    P.colstep = sh.Wo > 1 ? (uint32_t)sh.s : 0u;
     P.Wo = (uint32_t)sh.Wo;
     P.d_wo = make_fastdiv(P.Wo);
     P.T = MfmaParams{};

@@ -170,6 +170,7 @@ ONE_BY_ONE_SHAPES = [
     ((3, 64, 15, 13, 36, 2), "gather"),      # stride 2 on odd sizes, K blocks of 64
     ((2, 72, 17, 9, 16, 3), "gather"),       # stride 3, a short last K block
     ((70, 64, 3, 3, 64, 2), "gather"),       # planes of four output pixels: a tile spans sixteen images
+    ((70, 16, 3, 3, 8, 1 << 26), "gather"),  # a stride far beyond the image: one output pixel per image
     ((2, 64, 8, 8, 66, 1), None),        # 66 output channels
     ((2, 100, 8, 8, 64, 1), None),       # 100 input channels
 ]
