@@ -136,8 +136,13 @@ def time_layer(L, steps, warmup):
     torch.cuda.synchronize()
     t1 = time.perf_counter()
 
+    # Each kernel's batches follow 20 ms of that kernel alone: the clocks take a few milliseconds to settle
+    # when the load changes from memory-bound to matrix-bound work and back (without it the first batch of
+    # the convolution after the transform's batches read up to 8 % long on some boxes).
     nk = max(steps, KERNEL_SAMPLES)
+    _ramp(tr, 0.02)
     tr_b = [_event_ms(tr, nk) for _ in range(3)]
+    _ramp(cv, 0.02)
     cv_b = [_event_ms(cv, nk) for _ in range(3)]
     # The workspace-free variant (strips built in LDS from the input): one call replaces the whole
     # step.  Timed the same way as the step, after the main measurement.
