@@ -35,17 +35,17 @@ PEAK_HBM_GBS = 8000.0             # MI355X HBM3E
 # gives the commands; tests/test_host_api.py holds the two to each other.  Layers that were not
 # measured report null.
 MEASURED_CONV_TRAFFIC_BYTES = {
-    "cfg1_tiny_3x3": 209076,
-    "cfg2_3x3_c64_56": 107716936,
-    "cfg3_3x3_c256_14": 215240654,
-    "cfg4_7x7_s2_c3_224": 689052728,
-    "cfg5_11x11_s4_c3_227": 362601859}
+    "cfg1_tiny_3x3": 209324,
+    "cfg2_3x3_c64_56": 107723384,
+    "cfg3_3x3_c256_14": 215418276,
+    "cfg4_7x7_s2_c3_224": 689076020,
+    "cfg5_11x11_s4_c3_227": 362789419}
 MEASURED_TRANSFORM_TRAFFIC_BYTES = {
     "cfg1_tiny_3x3": 63485,
-    "cfg2_3x3_c64_56": 105603026,
-    "cfg3_3x3_c256_14": 113850082,
-    "cfg4_7x7_s2_c3_224": 362313338,
-    "cfg5_11x11_s4_c3_227": 298218608}
+    "cfg2_3x3_c64_56": 105594963,
+    "cfg3_3x3_c256_14": 113847631,
+    "cfg4_7x7_s2_c3_224": 362295763,
+    "cfg5_11x11_s4_c3_227": 298416819}
 
 
 def parse_args():
